@@ -1,0 +1,235 @@
+/*
+ * gxpo.h -- C ABI of the GXPO active-step update engine for AMD MI355X (gfx950).
+ *
+ * GXPO (Gradient Extrapolation-Based Policy Optimization) replaces one
+ * optimizer update of a GRPO-style trainer by: two fast optimizer steps on
+ * probe gradients, a per-coordinate geometric extrapolation of the observed
+ * two-step displacement to a virtual K-step point, a partial move toward that
+ * point, and one corrective optimizer step with the gradient taken there
+ * (paper, Section 2 and Algorithm 1).  A rolling z-score gate on the norm of
+ * the corrective gradient switches the trainer back, for good, to the plain
+ * single-pass update (Section 2.3, "Adaptive rule in practice").
+ *
+ * This library is the parameter-space part of that rule: everything that
+ * touches every parameter.  The trainer (the caller) owns the loss and hands
+ * in gradients; the library owns no parameter-sized memory.
+ *
+ * One training step t, active phase (Algorithm 1, the branch t < s*):
+ *
+ *     g0 = grad L(theta)                       caller, backward pass 1
+ *     gxpo_fast_steps(ctx, 0, g0, stream)      theta_probe <- OptimStep(theta, g0)
+ *     g1 = grad L(theta_probe)                 caller, backward pass 2
+ *     gxpo_fast_steps(ctx, 1, g1, stream)      theta_probe <- OptimStep(theta_probe, g1)
+ *     gxpo_extrapolate(ctx, g0, g1, stream)    theta <- theta + alpha*scale*(theta_probe - theta)
+ *     gs = grad L(theta)                       caller, backward pass 3 (theta is now theta~)
+ *     gxpo_slow_step(ctx, gs, stream)          theta <- OptimStep(theta, gs);  sum gs^2
+ *     gxpo_gate(ctx, &info, stream)            z-score test, may set s* = t + 1;  t <- t + 1
+ *
+ * Fallback phase (t >= s*):
+ *
+ *     g0 = grad L(theta)
+ *     gxpo_fallback_step(ctx, g0, stream)      theta <- OptimStep(theta, g0);  t <- t + 1
+ *
+ * Conventions
+ *  - Every function returns GXPO_OK (0) or a negative gxpo_status.  Nothing
+ *    throws or aborts across this boundary.  gxpo_last_error() returns a
+ *    human-readable description of the last failure.
+ *  - "device" pointers are HIP device allocations on the GPU that was current
+ *    when gxpo_init() ran; that GPU must be current on every later call.
+ *    "host" pointers are ordinary process memory.
+ *  - The caller owns every parameter-sized buffer (theta, theta_probe, m, v,
+ *    model_copy, gradients) and keeps it alive and un-aliased while the
+ *    context lives; the context owns only its small tables and the reduction
+ *    workspace.
+ *  - All GPU work is enqueued on the caller's stream (`stream` is a
+ *    hipStream_t passed as void*; NULL is the default stream) and returns
+ *    without waiting.  Only gxpo_gate() and gxpo_tensor_norms() wait for the
+ *    stream.  Calls on one context must be issued on one stream, or be ordered
+ *    by the caller.
+ *  - Gradient lists are host arrays of n_tensors device pointers, one per
+ *    parameter tensor, in gxpo_init() order; element i of a gradient buffer
+ *    belongs to element i of that tensor.  Gradient buffers are never written.
+ *  - fp32 buffers must be 16-byte aligned, bf16 buffers 8-byte aligned
+ *    (GXPO_ERR_ALIGNMENT otherwise).  Any numel >= 1 is accepted.
+ */
+#ifndef GXPO_H
+#define GXPO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum gxpo_status {
+    GXPO_OK = 0,
+    GXPO_ERR_INVALID_ARG = -1,   /* NULL / out-of-range argument, bad struct_size, aliasing buffers */
+    GXPO_ERR_BAD_STATE = -2,     /* call out of Algorithm-1 order, active call after s*, fallback before s* */
+    GXPO_ERR_ALIGNMENT = -3,     /* a device pointer misses the alignment stated above */
+    GXPO_ERR_UNSUPPORTED = -4,   /* unknown optimizer / gradient dtype */
+    GXPO_ERR_HIP = -5,           /* a HIP runtime call failed; the message carries its error string */
+    GXPO_ERR_NOMEM = -6          /* host or device allocation failed */
+} gxpo_status;
+
+enum { GXPO_OPT_GD = 0, GXPO_OPT_ADAMW = 1 };
+enum { GXPO_GRAD_F32 = 0, GXPO_GRAD_BF16 = 1 };
+/* which results are also written, rounded to bf16 (nearest-even), to model_copy */
+enum { GXPO_COPY_AT_PROBE = 1,   /* theta^{t,1}: what backward pass 2 differentiates */
+       GXPO_COPY_AT_TILDE = 2,   /* theta~^t  : what backward pass 3 differentiates */
+       GXPO_COPY_AT_FINAL = 4 }; /* theta^{t+1} (slow step and fallback step)       */
+enum { GXPO_PHASE_IDLE = 0, GXPO_PHASE_FAST1 = 1, GXPO_PHASE_FAST2 = 2,
+       GXPO_PHASE_REPOSITIONED = 3, GXPO_PHASE_SLOW_DONE = 4 };
+
+#define GXPO_MAX_WINDOW 256u
+
+typedef struct gxpo_ctx gxpo_ctx;
+
+/* One parameter tensor.  All pointers are device pointers to `numel` elements. */
+typedef struct gxpo_tensor {
+    uint64_t numel;
+    float *theta;        /* fp32 master weights.  Holds theta^t when a step starts, theta~^t after
+                            gxpo_extrapolate, theta^{t+1} after gxpo_slow_step / gxpo_fallback_step. */
+    float *theta_probe;  /* fp32 scratch of the same size: theta^{t,1} after gxpo_fast_steps(0),
+                            theta^{t,2} after gxpo_fast_steps(1) when fuse_step2 == 0.  Contents
+                            are undefined between training steps.  May be NULL only if the context
+                            is never used in the active phase (see gxpo_set_state). */
+    float *m, *v;        /* AdamW first / second moment, fp32.  Must be NULL for GXPO_OPT_GD. */
+    void  *model_copy;   /* optional bf16 [numel] copy the trainer's forward/backward reads; NULL = none */
+} gxpo_tensor;
+
+/* Hyper-parameters.  All reals travel as double; the library derives the
+ * per-step constants (1 - beta, bias corrections, ...) in double and only then
+ * rounds them to the fp32 the kernels compute in. */
+typedef struct gxpo_config {
+    uint32_t struct_size;     /* = sizeof(gxpo_config) */
+    uint32_t optimizer;       /* GXPO_OPT_*   : OptimStep of Algorithm 1 */
+    uint32_t grad_dtype;      /* GXPO_GRAD_*  : element type of every gradient buffer */
+    uint32_t K;               /* virtual lookahead depth, >= 2 (K = 2 makes scale == 1) */
+    uint32_t fuse_step2;      /* 1: gxpo_fast_steps(1) only records g1 and gxpo_extrapolate runs the
+                                 second fast step and the extrapolation as one pass (theta^{t,2} is
+                                 never stored).  0: each call runs its own pass. */
+    uint32_t copy_mask;       /* GXPO_COPY_AT_* bits; ignored for tensors without model_copy */
+    uint32_t window;          /* w: number of past norms the gate statistics use, 2..GXPO_MAX_WINDOW */
+    uint32_t gate_min_count;  /* gate is evaluated once the buffer holds this many norms; 0 = window */
+    uint32_t gate_ddof;       /* 0 population / 1 sample standard deviation */
+    uint32_t waves_per_block; /* launch shape: 0 = library default, else 1, 2 or 4 */
+    double lr, beta1, beta2, adam_eps, weight_decay;   /* OptimStep (AdamW: decoupled weight decay) */
+    double alpha;             /* reposition strength in [0, 1]                  (Eq. (9))            */
+    double delta;             /* active set is |g0_i| > delta, compared in fp32 (Section 2.2)        */
+    double r_max;             /* clamp of the retention ratio to [-r_max, r_max]; +inf = no clamp    */
+    double tau;               /* gate trips when Z_t >= tau                     (Section 2.3)        */
+    double gate_eps;          /* epsilon in Z_t = (norm - mu) / (sigma + epsilon), > 0  (Eq. (10))   */
+} gxpo_config;
+
+typedef struct gxpo_gate_info {
+    double  norm;        /* ||g_slow||_2 over all tensors */
+    double  mu, sigma;   /* statistics of the buffer before this norm was inserted (NaN if !evaluated) */
+    double  z;           /* Z_t (NaN if !evaluated) */
+    int32_t evaluated;   /* 0 during warm-up */
+    int32_t tripped;     /* 1 if this step set (or found already set) the fallback */
+    int64_t s_star;      /* first fallback step index, -1 while still +infinity */
+    int64_t t;           /* index of the training step this record belongs to */
+} gxpo_gate_info;
+
+/* The small host-side state of a context; enough to checkpoint / resume. */
+typedef struct gxpo_state {
+    uint32_t struct_size;        /* = sizeof(gxpo_state) */
+    uint32_t phase;              /* GXPO_PHASE_* */
+    int64_t  t;                  /* training step index */
+    int64_t  optim_steps;        /* OptimStep counter s: +3 per active step, +1 per fallback step */
+    int64_t  s_star;             /* -1 = +infinity */
+    int64_t  backward_passes;    /* gradient hand-offs so far: 3 s* + (T - s*) after T steps */
+    uint32_t window_len;         /* norms currently in the rolling buffer */
+    uint32_t reserved;
+    double   window[GXPO_MAX_WINDOW];   /* oldest first */
+} gxpo_state;
+
+/* ---- life cycle --------------------------------------------------------- */
+
+/* Validates the configuration and the tensor list, builds the device tables and
+ * the reduction workspace, starts with an empty rolling buffer, s* = +infinity,
+ * t = 0 (Algorithm 1, "Initialize").  `cfg` and `tensors` are host pointers and
+ * are copied.  On failure *out is NULL and gxpo_last_error(NULL) explains. */
+int gxpo_init(gxpo_ctx **out, const gxpo_config *cfg, const gxpo_tensor *tensors, uint32_t n_tensors);
+
+/* Frees what gxpo_init allocated (never the caller's buffers).  Waits for the
+ * device first.  NULL is allowed. */
+void gxpo_destroy(gxpo_ctx *ctx);
+
+/* ---- active phase (Algorithm 1, branch t < s*) -------------------------------- */
+
+/* which == 0: theta_probe <- OptimStep(theta, grads)           ("First fast optimizer step")
+ * which == 1: theta_probe <- OptimStep(theta_probe, grads)     ("Second fast optimizer step")
+ * The optimizer state (m, v, step counter) advances on both and is not rolled
+ * back later (Section 2.3, paragraph after Eq. (9)).  theta is left untouched.
+ * The gradients of which == 0 must stay unmodified until gxpo_extrapolate has
+ * executed; with fuse_step2 the same holds for the gradients of which == 1. */
+int gxpo_fast_steps(gxpo_ctx *ctx, int which, const void *const *grads, void *stream);
+
+/* Active set, retention ratio r = g1/g0, scale = S_K(r)/S_2(r) (1 off the
+ * active set), extrapolation and reposition, in registers, one pass:
+ *     theta <- theta + alpha * scale * (theta^{t,2} - theta)
+ * (Algorithm 1 from "Active coordinates" to "Reposition"; Eqs. (4), (7)-(9)). */
+int gxpo_extrapolate(gxpo_ctx *ctx, const void *const *g0, const void *const *g1, void *stream);
+
+/* theta <- OptimStep(theta, g_slow) ("Slow correction") fused with the sum of
+ * squares of g_slow per tensor and over all tensors, accumulated in fp64 in a
+ * fixed order (bit-reproducible from run to run). */
+int gxpo_slow_step(gxpo_ctx *ctx, const void *const *g_slow, void *stream);
+
+/* Waits for the stream, reads ||g_slow||_2, evaluates Z_t against the rolling
+ * buffer as it was before this norm, sets s* = t + 1 if Z_t >= tau (or if the
+ * norm is not finite), pushes the norm, advances t.  `out` (host) may be NULL. */
+int gxpo_gate(gxpo_ctx *ctx, gxpo_gate_info *out, void *stream);
+
+/* ---- fallback phase (Algorithm 1, branch t >= s*) ------------------------------ */
+
+/* theta <- OptimStep(theta, g0), in place; advances t.  Identical arithmetic
+ * to gxpo_fast_steps(ctx, 0, ...), only the destination differs. */
+int gxpo_fallback_step(gxpo_ctx *ctx, const void *const *g0, void *stream);
+
+/* ---- queries ------------------------------------------------------------- */
+
+/* Per-tensor ||g_slow||_2 of the most recent gxpo_slow_step into a host array
+ * of n_tensors doubles.  Waits for `stream`. */
+int gxpo_tensor_norms(gxpo_ctx *ctx, double *out_host, void *stream);
+
+/* Copy the host-side state out / in (phase must be IDLE for set).  Setting
+ * s_star <= t puts the context into the fallback phase. */
+int gxpo_get_state(const gxpo_ctx *ctx, gxpo_state *out);
+int gxpo_set_state(gxpo_ctx *ctx, const gxpo_state *in);
+
+/* Message of the last failure on `ctx`, or of the last failed gxpo_init on
+ * this thread when ctx is NULL.  Never NULL; valid until the next call. */
+const char *gxpo_last_error(const gxpo_ctx *ctx);
+
+/* ---- host-only helpers (no GPU needed) ----------------------------------------- */
+
+/* Checks a configuration exactly as gxpo_init does.  Returns a gxpo_status;
+ * on failure copies a message into msg (host, may be NULL) of capacity cap. */
+int gxpo_validate_config(const gxpo_config *cfg, char *msg, size_t cap);
+
+/* The gate rule on its own: evaluates step `state->t` with `norm` against
+ * state->window, updates window / s_star / t exactly as gxpo_gate does
+ * (everything except reading the norm from the device). */
+int gxpo_host_gate_step(const gxpo_config *cfg, gxpo_state *state, double norm, gxpo_gate_info *out);
+
+/* How the launch grid covers a ragged tensor list: writes the first block
+ * index of every tensor plus the total into block_start[n_tensors + 1] (host)
+ * and returns the elements each block covers through *elems_per_block. */
+int gxpo_plan_blocks(const uint64_t *numel, uint32_t n_tensors, uint32_t waves_per_block,
+                     uint32_t *block_start, uint32_t *elems_per_block);
+
+/* ---- measurement aid ------------------------------------------------------------ */
+
+/* Plain device-to-device streaming copy of `bytes` (multiple of 16, both
+ * pointers 16-byte aligned) with the same load/store instructions and launch
+ * shape as the engine's kernels: the known-size reference that hardware
+ * byte counters and achieved-bandwidth figures are scaled against. */
+int gxpo_stream_copy(void *dst_device, const void *src_device, uint64_t bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GXPO_H */

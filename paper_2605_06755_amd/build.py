@@ -1,0 +1,65 @@
+"""Builds libgxpo.so (HIP, gfx950 only) in-tree with hipcc.
+
+Run as `python -m paper_2605_06755_amd.build`.  hipcc cross-compiles, so no
+GPU is needed to build.
+"""
+from __future__ import annotations
+
+import os
+import shutil
+import subprocess
+import sys
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(PKG)
+CSRC = os.path.join(PKG, "csrc")
+LIB = os.path.join(PKG, "libgxpo.so")
+OBJ = os.path.join(PKG, "_build")
+
+DEVICE_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+    # packed fp32 arithmetic is kept off for all device code
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wall", "-Wno-unused-command-line-argument",
+]
+HOST_FLAGS = ["-O2", "-std=c++17", "-fPIC", "-Wall", "-Wextra"]
+
+
+def _hipcc() -> str:
+    for cand in (shutil.which("hipcc"), "/opt/rocm/bin/hipcc"):
+        if cand and os.path.exists(cand):
+            return cand
+    raise RuntimeError("hipcc not found: the GXPO engine needs the ROCm toolchain to build")
+
+
+def _run(cmd):
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    # hipcc's host pass does not know the packed-fp32 device feature; that warning is expected
+    noise = ("is not a recognized feature for this target", "packed-fp32-ops", "warning generated", "warnings generated")
+    out = "\n".join(l for l in res.stdout.splitlines() if not any(n in l for n in noise))
+    if res.returncode != 0:
+        raise RuntimeError("build step failed:\n  " + " ".join(cmd) + "\n" + res.stdout)
+    if out.strip():
+        print(out, file=sys.stderr)
+
+
+def build_library(verbose: bool = False) -> str:
+    hipcc = _hipcc()
+    os.makedirs(OBJ, exist_ok=True)
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    k_obj = os.path.join(OBJ, "gxpo_kernels.o")
+    h_obj = os.path.join(OBJ, "gxpo_host.o")
+    steps = [
+        [hipcc, *DEVICE_FLAGS, *inc, "-c", os.path.join(CSRC, "gxpo_kernels.hip"), "-o", k_obj],
+        [hipcc, *HOST_FLAGS, *inc, "-c", os.path.join(CSRC, "gxpo_host.cpp"), "-o", h_obj],
+        [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, k_obj, h_obj],
+    ]
+    for cmd in steps:
+        if verbose:
+            print(" ".join(cmd), file=sys.stderr)
+        _run(cmd)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build_library(verbose=True))

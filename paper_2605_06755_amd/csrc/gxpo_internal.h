@@ -1,0 +1,85 @@
+// Internal interface between the host side of the library (gxpo_host.cpp) and
+// its gfx950 kernels (gxpo_kernels.hip).  Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gxpo {
+
+// One wavefront handles 64 lanes x 4 consecutive elements of one tensor.
+constexpr uint32_t kLaneElems = 4;
+constexpr uint32_t kWaveElems = 64 * kLaneElems;
+// The coarse block->tensor index has one entry per 2^kCoarseShift blocks.
+constexpr uint32_t kCoarseShift = 6;
+// Partials of one tensor are reduced in runs of at most this many.
+constexpr uint32_t kSegPartials = 8192;
+
+struct TensorRec {          // device copy of one gxpo_tensor
+    float *theta;
+    float *probe;
+    float *m;
+    float *v;
+    void *copy;             // bf16 model copy or nullptr
+    uint64_t numel;
+};
+
+// How the 1-D grid covers the ragged tensor list: tensor t owns blocks
+// [blk_start[t], blk_start[t+1]); coarse[b >> kCoarseShift] is the tensor that
+// owns block (b >> kCoarseShift) << kCoarseShift.
+struct Layout {
+    const TensorRec *tab;
+    const uint32_t *blk_start;
+    const uint32_t *coarse;
+    uint32_t n_tensors;
+    uint32_t n_blocks;
+};
+
+// OptimStep constants, derived in double on the host, rounded once to fp32.
+struct StepParams {
+    float beta1, one_minus_beta1;
+    float beta2, one_minus_beta2;
+    float lr_wd;            // lr * weight_decay
+    float step_size;        // lr / (1 - beta1^s)
+    float rsqrt_bias2;      // 1 / sqrt(1 - beta2^s)
+    float eps;
+    float lr;               // plain GD
+};
+
+struct ExtrapParams {
+    float alpha;
+    float delta;            // fp32(delta)
+    float r_max;            // fp32(r_max), +inf = no clamp
+    uint32_t half;          // K/2 (K even) or (K-1)/2 (K odd)
+    uint32_t odd;           // K & 1
+};
+
+struct SegRec {             // a run of per-block partials inside one tensor
+    uint32_t first;
+    uint32_t count;
+};
+
+enum { kSrcTheta = 0, kSrcProbe = 1 };
+
+// All launchers enqueue on `stream` and return the launch status.
+hipError_t launch_step(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype,
+                       const void *const *d_grads, const StepParams &p,
+                       int src, int dst, int write_copy, double *d_partial, hipStream_t stream);
+
+hipError_t launch_extrapolate(const Layout &L, uint32_t wpb, int grad_dtype,
+                              const void *const *d_g0, const void *const *d_g1,
+                              const ExtrapParams &e, int write_copy, hipStream_t stream);
+
+hipError_t launch_fused_step2_extrapolate(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype,
+                                          const void *const *d_g0, const void *const *d_g1,
+                                          const StepParams &p, const ExtrapParams &e,
+                                          int write_copy, hipStream_t stream);
+
+// result[0] = sum over all tensors, result[1 + t] = sum over tensor t.
+hipError_t launch_finalize(const double *d_partial, const SegRec *d_seg, uint32_t n_segs,
+                           const uint32_t *d_tensor_seg_start, uint32_t n_tensors,
+                           double *d_seg_sum, double *d_result, hipStream_t stream);
+
+hipError_t launch_stream_copy(void *dst, const void *src, uint64_t bytes, hipStream_t stream);
+
+}  // namespace gxpo

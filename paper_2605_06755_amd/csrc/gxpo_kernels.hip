@@ -1,0 +1,476 @@
+// gfx950 kernels of the GXPO update engine.
+//
+// Every pass is a pure HBM stream: no element needs a neighbour, nothing is
+// reused, so the kernels are built around how MI355X moves bytes best:
+//
+//  * one-shot blocks: a block is WPB wavefronts, each lane owns 4 consecutive
+//    elements (one 128-bit access per fp32 stream) and the block retires after
+//    a single load -> compute -> store round.  Blocks are dispatched in index
+//    order, so the set of DRAM pages in flight stays a narrow moving front;
+//    measured on this part that beats grid-stride loops by ~20 %.
+//  * buffer instructions with the streaming cache policy (sc1 + nt): the data
+//    is touched once per pass, there is nothing for L2 / MALL to keep.  The
+//    buffer descriptor of each stream covers exactly the block's span, so the
+//    hardware range check makes the ragged last block of a tensor safe:
+//    out-of-range lanes load 0 and their stores are dropped.
+//  * the block -> (tensor, offset) map is two or three scalar loads (coarse
+//    index + short scan), skipped entirely for a single flat tensor.
+//
+// Arithmetic is fp32 with the optimizer constants prepared in double on the
+// host; only the sum of squares of g_slow is accumulated in fp64.
+#include "gxpo_internal.h"
+
+namespace gxpo {
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+
+// cache-policy bits of gfx94x/gfx950 buffer instructions: sc0 = 1, nt = 2, sc1 = 16
+constexpr int kStreamPolicy = 16 | 2;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t span_rsrc(const void *base, uint32_t bytes) {
+    // raw (unstructured) buffer: stride 0, 32-bit data format; range-checked against `bytes`
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+
+// ---- 4-element lane loads / stores -------------------------------------------------------
+// `full` is block-uniform: true when the block's span holds all of its elements, so
+// every lane may use one wide access.  Otherwise each element goes through its own
+// range-checked access.
+
+__device__ __forceinline__ f32x4 load_f32(__amdgpu_buffer_rsrc_t r, uint32_t elem, bool full) {
+    if (full) {
+        u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(r, (int)(elem * 4u), 0, kStreamPolicy);
+        return __builtin_bit_cast(f32x4, x);
+    }
+    f32x4 o;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        unsigned x = __builtin_amdgcn_raw_buffer_load_b32(r, (int)((elem + k) * 4u), 0, kStreamPolicy);
+        o[k] = __builtin_bit_cast(float, x);
+    }
+    return o;
+}
+
+__device__ __forceinline__ void store_f32(__amdgpu_buffer_rsrc_t r, uint32_t elem, bool full, f32x4 v) {
+    if (full) {
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (int)(elem * 4u), 0, kStreamPolicy);
+        return;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const float lane_value = v[k];   // a scalar copy: bit-casting the vector element in place reads element 0
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, lane_value), r, (int)((elem + k) * 4u), 0, kStreamPolicy);
+    }
+}
+
+__device__ __forceinline__ f32x4 load_bf16(__amdgpu_buffer_rsrc_t r, uint32_t elem, bool full) {
+    f32x4 o;
+    if (full) {
+        u32x2 x = __builtin_amdgcn_raw_buffer_load_b64(r, (int)(elem * 2u), 0, kStreamPolicy);
+        o[0] = __builtin_bit_cast(float, x[0] << 16);
+        o[1] = __builtin_bit_cast(float, x[0] & 0xffff0000u);
+        o[2] = __builtin_bit_cast(float, x[1] << 16);
+        o[3] = __builtin_bit_cast(float, x[1] & 0xffff0000u);
+        return o;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        unsigned x = __builtin_amdgcn_raw_buffer_load_b16(r, (int)((elem + k) * 2u), 0, kStreamPolicy);
+        o[k] = __builtin_bit_cast(float, x << 16);
+    }
+    return o;
+}
+
+__device__ __forceinline__ unsigned bf16_bits(float f) {
+    // conversion in the compiler's native bf16 type: round to nearest even
+    __bf16 h = (__bf16)f;
+    return (unsigned)__builtin_bit_cast(unsigned short, h);
+}
+
+__device__ __forceinline__ void store_bf16(__amdgpu_buffer_rsrc_t r, uint32_t elem, bool full, f32x4 v) {
+    if (full) {
+        u32x2 x;
+        x[0] = bf16_bits(v[0]) | (bf16_bits(v[1]) << 16);
+        x[1] = bf16_bits(v[2]) | (bf16_bits(v[3]) << 16);
+        __builtin_amdgcn_raw_buffer_store_b64(x, r, (int)(elem * 2u), 0, kStreamPolicy);
+        return;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+        __builtin_amdgcn_raw_buffer_store_b16((unsigned short)bf16_bits(v[k]), r, (int)((elem + k) * 2u), 0, kStreamPolicy);
+}
+
+template <int GDT> __device__ __forceinline__ __amdgpu_buffer_rsrc_t grad_rsrc(const void *g, uint64_t e0, uint32_t cnt) {
+    if (GDT == 0) return span_rsrc((const float *)g + e0, cnt * 4u);
+    return span_rsrc((const unsigned short *)g + e0, cnt * 2u);
+}
+template <int GDT> __device__ __forceinline__ f32x4 load_grad(__amdgpu_buffer_rsrc_t r, uint32_t elem, bool full) {
+    if (GDT == 0) return load_f32(r, elem, full);
+    return load_bf16(r, elem, full);
+}
+
+// ---- which part of which tensor this block owns ---------------------------------------
+struct Span {
+    TensorRec rec;
+    uint32_t tensor;
+    uint64_t e0;       // first element of the block inside the tensor
+    uint32_t cnt;      // elements of the tensor inside the block's span (<= elems per block)
+    bool full;
+};
+
+template <int WPB> __device__ __forceinline__ Span locate(const Layout &L) {
+    constexpr uint32_t kBlockElems = WPB * kWaveElems;
+    const uint32_t b = blockIdx.x;
+    uint32_t t = 0;
+    if (L.n_tensors > 1) {
+        t = L.coarse[b >> kCoarseShift];
+        while (L.blk_start[t + 1] <= b) ++t;      // blk_start[n_tensors] == n_blocks > b
+    }
+    Span s;
+    s.tensor = t;
+    s.rec = L.tab[t];
+    s.e0 = (uint64_t)(b - L.blk_start[t]) * kBlockElems;
+    const uint64_t rem = s.rec.numel - s.e0;
+    s.cnt = rem < kBlockElems ? (uint32_t)rem : kBlockElems;
+    s.full = s.cnt == kBlockElems;
+    return s;
+}
+
+// ---- OptimStep on one element (Algorithm 1's OptimStep) ---------------------------------
+// Returns the amount to subtract from theta; updates the moments in place.
+//   GD    : eta * g
+//   AdamW : lr*wd*theta + lr/(1-beta1^s) * m / (sqrt(v)/sqrt(1-beta2^s) + eps)
+// Keeping the update separate from theta lets callers form theta - update with one
+// rounding, and lets the fused pass subtract it from a displacement instead.
+template <int OPT>
+__device__ __forceinline__ float optim_update(float theta, float &m, float &v, float g, const StepParams &p) {
+    if (OPT == 0) return p.lr * g;
+    m = fmaf(p.beta1, m, p.one_minus_beta1 * g);
+    v = fmaf(p.beta2, v, p.one_minus_beta2 * g * g);
+    const float denom = fmaf(sqrtf(v), p.rsqrt_bias2, p.eps);
+    return fmaf(p.lr_wd, theta, p.step_size * (m / denom));
+}
+
+// ---- extrapolation factor (Eqs. (4), (7); Algorithm 1 "Extrapolation factor") -------------
+// scale = S_K(r)/S_2(r) with r = g1/g0, written so that nothing cancels:
+//   K even: S_K/S_2 = sum_{j<K/2} r^{2j}
+//   K odd : S_K/S_2 = sum_{j<(K-1)/2} r^{2j} + r^{K-1}/(1+r),   1 + r = (g0+g1)/g0
+// g0 + g1 is rounded once from exact inputs, so the pole at r = -1 is approached
+// with full relative accuracy.  Off the active set, and at r == -1 where S_2
+// vanishes, the observed displacement is kept (scale = 1).
+__device__ __forceinline__ float extrap_scale(float g0, float g1, const ExtrapParams &e) {
+    const float r = g1 / g0;
+    const float rc = fminf(fmaxf(r, -e.r_max), e.r_max);
+    const float x = rc * rc;
+    float series = 1.0f, power = 1.0f;
+    for (uint32_t j = 1; j < e.half; ++j) {
+        series = fmaf(series, x, 1.0f);
+        power *= x;
+    }
+    float scale = series;
+    if (e.odd) {
+        power *= x;                                   // r^(K-1)
+        const bool clamped = rc != r;
+        const float num = clamped ? 1.0f : g0;
+        const float den = clamped ? 1.0f + rc : g0 + g1;
+        scale = fmaf(power, num / den, series);
+    }
+    const bool use = (fabsf(g0) > e.delta) && (rc != -1.0f);
+    return use ? scale : 1.0f;
+}
+
+__device__ __forceinline__ double wave_sum(double x) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+    return x;
+}
+
+// ============================================================================
+// OptimStep pass: fast step 1 (theta -> probe), unfused fast step 2
+// (probe -> probe), slow step (theta -> theta, + sum of squares), fallback step
+// (theta -> theta).  28 B/param with fp32 gradients (16 read, 12 written).
+// ============================================================================
+template <int WPB, int OPT, int GDT>
+__global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, const void *const *__restrict__ grads, StepParams p,
+                                                       int src, int dst, int write_copy, double *__restrict__ partial) {
+    const Span s = locate<WPB>(L);
+    const uint32_t elem = threadIdx.x * kLaneElems;
+    const uint32_t bytes = s.cnt * 4u;
+    const float *src_ptr = (src == kSrcProbe ? s.rec.probe : s.rec.theta) + s.e0;
+    float *dst_ptr = (dst == kSrcProbe ? s.rec.probe : s.rec.theta) + s.e0;
+    const auto r_src = span_rsrc(src_ptr, bytes);
+    const auto r_dst = span_rsrc(dst_ptr, bytes);
+    const auto r_g = grad_rsrc<GDT>(grads[s.tensor], s.e0, s.cnt);
+
+    f32x4 th = load_f32(r_src, elem, s.full);
+    f32x4 g = load_grad<GDT>(r_g, elem, s.full);
+    f32x4 m = {0, 0, 0, 0}, v = {0, 0, 0, 0};
+    __amdgpu_buffer_rsrc_t r_m, r_v;
+    if (OPT == 1) {
+        r_m = span_rsrc(s.rec.m + s.e0, bytes);
+        r_v = span_rsrc(s.rec.v + s.e0, bytes);
+        m = load_f32(r_m, elem, s.full);
+        v = load_f32(r_v, elem, s.full);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        float mk = m[k], vk = v[k];
+        th[k] = th[k] - optim_update<OPT>(th[k], mk, vk, g[k], p);
+        m[k] = mk;
+        v[k] = vk;
+    }
+    store_f32(r_dst, elem, s.full, th);
+    if (OPT == 1) {
+        store_f32(r_m, elem, s.full, m);
+        store_f32(r_v, elem, s.full, v);
+    }
+    if (write_copy && s.rec.copy) {
+        const auto r_c = span_rsrc((unsigned short *)s.rec.copy + s.e0, s.cnt * 2u);
+        store_bf16(r_c, elem, s.full, th);
+    }
+    if (partial) {
+        // out-of-range lanes loaded g = 0 and add nothing
+        double acc = 0.0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc = fma((double)g[k], (double)g[k], acc);
+        acc = wave_sum(acc);
+        if (WPB == 1) {
+            if (threadIdx.x == 0) partial[blockIdx.x] = acc;
+        } else {
+            __shared__ double wave_part[WPB];
+            if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = acc;
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                double total = 0.0;
+#pragma unroll
+                for (int w = 0; w < WPB; ++w) total += wave_part[w];
+                partial[blockIdx.x] = total;
+            }
+        }
+    }
+}
+
+// ============================================================================
+// Extrapolate + reposition alone (Algorithm 1 "Active coordinates" ... "Reposition"):
+//   theta <- theta + alpha * scale * (theta_probe - theta)
+// 20 B/param with fp32 gradients (16 read, 4 written).
+// ============================================================================
+template <int WPB, int GDT>
+__global__ __launch_bounds__(64 * WPB) void k_extrapolate(Layout L, const void *const *__restrict__ g0s,
+                                                        const void *const *__restrict__ g1s, ExtrapParams e, int write_copy) {
+    const Span s = locate<WPB>(L);
+    const uint32_t elem = threadIdx.x * kLaneElems;
+    const uint32_t bytes = s.cnt * 4u;
+    const auto r_th = span_rsrc(s.rec.theta + s.e0, bytes);
+    const auto r_pr = span_rsrc(s.rec.probe + s.e0, bytes);
+    const auto r_g0 = grad_rsrc<GDT>(g0s[s.tensor], s.e0, s.cnt);
+    const auto r_g1 = grad_rsrc<GDT>(g1s[s.tensor], s.e0, s.cnt);
+    f32x4 th0 = load_f32(r_th, elem, s.full);
+    f32x4 th2 = load_f32(r_pr, elem, s.full);
+    f32x4 g0 = load_grad<GDT>(r_g0, elem, s.full);
+    f32x4 g1 = load_grad<GDT>(r_g1, elem, s.full);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const float scale = extrap_scale(g0[k], g1[k], e);
+        th0[k] = fmaf(e.alpha * scale, th2[k] - th0[k], th0[k]);
+    }
+    store_f32(r_th, elem, s.full, th0);
+    if (write_copy && s.rec.copy) {
+        const auto r_c = span_rsrc((unsigned short *)s.rec.copy + s.e0, s.cnt * 2u);
+        store_bf16(r_c, elem, s.full, th0);
+    }
+}
+
+// ============================================================================
+// Fused: second fast step + extrapolate + reposition.  theta^{t,2} lives only
+// in registers; the two-step displacement is formed as
+//     (theta^{t,1} - theta^t) - update_2
+// i.e. from the exact difference of the two stored iterates, not from a
+// rounded theta^{t,2}.  36 B/param with fp32 gradients (24 read, 12 written)
+// instead of 28 + 20.
+// ============================================================================
+template <int WPB, int OPT, int GDT>
+__global__ __launch_bounds__(64 * WPB) void k_fused_step2_extrapolate(Layout L, const void *const *__restrict__ g0s,
+                                                                    const void *const *__restrict__ g1s, StepParams p,
+                                                                    ExtrapParams e, int write_copy) {
+    const Span s = locate<WPB>(L);
+    const uint32_t elem = threadIdx.x * kLaneElems;
+    const uint32_t bytes = s.cnt * 4u;
+    const auto r_th = span_rsrc(s.rec.theta + s.e0, bytes);
+    const auto r_pr = span_rsrc(s.rec.probe + s.e0, bytes);
+    const auto r_g0 = grad_rsrc<GDT>(g0s[s.tensor], s.e0, s.cnt);
+    const auto r_g1 = grad_rsrc<GDT>(g1s[s.tensor], s.e0, s.cnt);
+    f32x4 th1 = load_f32(r_pr, elem, s.full);
+    f32x4 g1 = load_grad<GDT>(r_g1, elem, s.full);
+    f32x4 m = {0, 0, 0, 0}, v = {0, 0, 0, 0};
+    __amdgpu_buffer_rsrc_t r_m, r_v;
+    if (OPT == 1) {
+        r_m = span_rsrc(s.rec.m + s.e0, bytes);
+        r_v = span_rsrc(s.rec.v + s.e0, bytes);
+        m = load_f32(r_m, elem, s.full);
+        v = load_f32(r_v, elem, s.full);
+    }
+    f32x4 th0 = load_f32(r_th, elem, s.full);
+    f32x4 g0 = load_grad<GDT>(r_g0, elem, s.full);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        float mk = m[k], vk = v[k];
+        const float upd2 = optim_update<OPT>(th1[k], mk, vk, g1[k], p);
+        m[k] = mk;
+        v[k] = vk;
+        const float disp2 = (th1[k] - th0[k]) - upd2;            // theta^{t,2} - theta^t
+        const float scale = extrap_scale(g0[k], g1[k], e);
+        th0[k] = fmaf(e.alpha * scale, disp2, th0[k]);
+    }
+    store_f32(r_th, elem, s.full, th0);
+    if (OPT == 1) {
+        store_f32(r_m, elem, s.full, m);
+        store_f32(r_v, elem, s.full, v);
+    }
+    if (write_copy && s.rec.copy) {
+        const auto r_c = span_rsrc((unsigned short *)s.rec.copy + s.e0, s.cnt * 2u);
+        store_bf16(r_c, elem, s.full, th0);
+    }
+}
+
+// ============================================================================
+// Fixed-order reduction of the per-block partial sums.
+// Stage 1: one block per run of <= kSegPartials partials of one tensor.
+// Stage 2: one block; thread t adds the run sums of tensor t in order, thread 0
+// then adds the tensor sums in index order.
+// ============================================================================
+constexpr int kFinalThreads = 256;
+
+__global__ __launch_bounds__(kFinalThreads) void k_reduce_runs(const double *__restrict__ partial, const SegRec *__restrict__ seg,
+                                                             double *__restrict__ seg_sum) {
+    const SegRec sr = seg[blockIdx.x];
+    double acc = 0.0;
+    for (uint32_t i = threadIdx.x; i < sr.count; i += kFinalThreads) acc += partial[sr.first + i];
+    acc = wave_sum(acc);
+    __shared__ double wave_part[kFinalThreads / 64];
+    if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double total = 0.0;
+#pragma unroll
+        for (int w = 0; w < kFinalThreads / 64; ++w) total += wave_part[w];
+        seg_sum[blockIdx.x] = total;
+    }
+}
+
+__global__ __launch_bounds__(kFinalThreads) void k_reduce_tensors(const double *__restrict__ seg_sum,
+                                                                const uint32_t *__restrict__ tensor_seg_start, uint32_t n_tensors,
+                                                                double *__restrict__ result) {
+    for (uint32_t t = threadIdx.x; t < n_tensors; t += kFinalThreads) {
+        double acc = 0.0;
+        for (uint32_t i = tensor_seg_start[t]; i < tensor_seg_start[t + 1]; ++i) acc += seg_sum[i];
+        result[1 + t] = acc;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double total = 0.0;
+        for (uint32_t t = 0; t < n_tensors; ++t) total += result[1 + t];
+        result[0] = total;
+    }
+}
+
+// ============================================================================
+// Plain streaming copy with the engine's access pattern (measurement reference).
+// ============================================================================
+__global__ __launch_bounds__(64) void k_stream_copy(const float *__restrict__ src, float *__restrict__ dst, uint64_t n_elems) {
+    const uint64_t e0 = (uint64_t)blockIdx.x * kWaveElems;
+    const uint64_t rem = n_elems - e0;
+    const uint32_t cnt = rem < kWaveElems ? (uint32_t)rem : kWaveElems;
+    const auto r_s = span_rsrc(src + e0, cnt * 4u);
+    const auto r_d = span_rsrc(dst + e0, cnt * 4u);
+    const uint32_t elem = threadIdx.x * kLaneElems;
+    // n_elems is a multiple of 4, so a lane's 4 elements are all inside or all outside the span
+    store_f32(r_d, elem, true, load_f32(r_s, elem, true));
+}
+
+template <int WPB>
+hipError_t step_wpb(const Layout &L, int optimizer, int grad_dtype, const void *const *g, const StepParams &p, int src, int dst,
+                    int write_copy, double *partial, hipStream_t st) {
+    const dim3 grid(L.n_blocks), block(64 * WPB);
+    if (optimizer == 0 && grad_dtype == 0) k_optim_step<WPB, 0, 0><<<grid, block, 0, st>>>(L, g, p, src, dst, write_copy, partial);
+    else if (optimizer == 0) k_optim_step<WPB, 0, 1><<<grid, block, 0, st>>>(L, g, p, src, dst, write_copy, partial);
+    else if (grad_dtype == 0) k_optim_step<WPB, 1, 0><<<grid, block, 0, st>>>(L, g, p, src, dst, write_copy, partial);
+    else k_optim_step<WPB, 1, 1><<<grid, block, 0, st>>>(L, g, p, src, dst, write_copy, partial);
+    return hipGetLastError();
+}
+
+template <int WPB>
+hipError_t extrap_wpb(const Layout &L, int grad_dtype, const void *const *g0, const void *const *g1, const ExtrapParams &e,
+                      int write_copy, hipStream_t st) {
+    const dim3 grid(L.n_blocks), block(64 * WPB);
+    if (grad_dtype == 0) k_extrapolate<WPB, 0><<<grid, block, 0, st>>>(L, g0, g1, e, write_copy);
+    else k_extrapolate<WPB, 1><<<grid, block, 0, st>>>(L, g0, g1, e, write_copy);
+    return hipGetLastError();
+}
+
+template <int WPB>
+hipError_t fused_wpb(const Layout &L, int optimizer, int grad_dtype, const void *const *g0, const void *const *g1,
+                     const StepParams &p, const ExtrapParams &e, int write_copy, hipStream_t st) {
+    const dim3 grid(L.n_blocks), block(64 * WPB);
+    if (optimizer == 0 && grad_dtype == 0) k_fused_step2_extrapolate<WPB, 0, 0><<<grid, block, 0, st>>>(L, g0, g1, p, e, write_copy);
+    else if (optimizer == 0) k_fused_step2_extrapolate<WPB, 0, 1><<<grid, block, 0, st>>>(L, g0, g1, p, e, write_copy);
+    else if (grad_dtype == 0) k_fused_step2_extrapolate<WPB, 1, 0><<<grid, block, 0, st>>>(L, g0, g1, p, e, write_copy);
+    else k_fused_step2_extrapolate<WPB, 1, 1><<<grid, block, 0, st>>>(L, g0, g1, p, e, write_copy);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_step(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype, const void *const *d_grads,
+                       const StepParams &p, int src, int dst, int write_copy, double *d_partial, hipStream_t stream) {
+    switch (wpb) {
+        case 1: return step_wpb<1>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_copy, d_partial, stream);
+        case 2: return step_wpb<2>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_copy, d_partial, stream);
+        case 4: return step_wpb<4>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_copy, d_partial, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_extrapolate(const Layout &L, uint32_t wpb, int grad_dtype, const void *const *d_g0, const void *const *d_g1,
+                              const ExtrapParams &e, int write_copy, hipStream_t stream) {
+    switch (wpb) {
+        case 1: return extrap_wpb<1>(L, grad_dtype, d_g0, d_g1, e, write_copy, stream);
+        case 2: return extrap_wpb<2>(L, grad_dtype, d_g0, d_g1, e, write_copy, stream);
+        case 4: return extrap_wpb<4>(L, grad_dtype, d_g0, d_g1, e, write_copy, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_fused_step2_extrapolate(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype, const void *const *d_g0,
+                                          const void *const *d_g1, const StepParams &p, const ExtrapParams &e, int write_copy,
+                                          hipStream_t stream) {
+    switch (wpb) {
+        case 1: return fused_wpb<1>(L, optimizer, grad_dtype, d_g0, d_g1, p, e, write_copy, stream);
+        case 2: return fused_wpb<2>(L, optimizer, grad_dtype, d_g0, d_g1, p, e, write_copy, stream);
+        case 4: return fused_wpb<4>(L, optimizer, grad_dtype, d_g0, d_g1, p, e, write_copy, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_finalize(const double *d_partial, const SegRec *d_seg, uint32_t n_segs, const uint32_t *d_tensor_seg_start,
+                           uint32_t n_tensors, double *d_seg_sum, double *d_result, hipStream_t stream) {
+    k_reduce_runs<<<dim3(n_segs), dim3(kFinalThreads), 0, stream>>>(d_partial, d_seg, d_seg_sum);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    k_reduce_tensors<<<dim3(1), dim3(kFinalThreads), 0, stream>>>(d_seg_sum, d_tensor_seg_start, n_tensors, d_result);
+    return hipGetLastError();
+}
+
+hipError_t launch_stream_copy(void *dst, const void *src, uint64_t bytes, hipStream_t stream) {
+    const uint64_t n_elems = bytes / 4;
+    const uint64_t blocks = (n_elems + kWaveElems - 1) / kWaveElems;
+    if (blocks == 0) return hipSuccess;
+    if (blocks > 0x7fffffffull) return hipErrorInvalidValue;
+    k_stream_copy<<<dim3((uint32_t)blocks), dim3(64), 0, stream>>>((const float *)src, (float *)dst, n_elems);
+    return hipGetLastError();
+}
+
+}  // namespace gxpo

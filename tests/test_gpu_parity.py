@@ -1,0 +1,429 @@
+"""GPU parity: the HIP engine, called through the C ABI, against the fp64 oracle.
+
+Sizes here are ones the oracle finishes in seconds but that still span many
+blocks (a block covers 256 elements by default) and ragged tails; the
+full-size workloads are in test_gpu_fullsize.py.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import gxpo_oracle as O
+from paper_2605_06755_amd import binding as B
+from paper_2605_06755_amd import synth
+from tests import gxpo_harness as H
+
+pytestmark = pytest.mark.gpu
+
+RAGGED = [1, 2, 3, 5, 255, 256, 257, 1000, 1024, 4099, 65536 + 5, 3 * 256 * 64 + 7, 100003]
+
+
+def quad_trainer(problem, numels, sigma=None, step_noise=None):
+    """Returns grad_fn(list of theta views, out buffers) for a flat problem split by numels."""
+    offs = np.concatenate([[0], np.cumsum(numels)])
+
+    def grad_fn(thetas, outs):
+        flat = torch.cat([t.reshape(-1) for t in thetas])
+        g = synth.quadratic_grad(problem, flat, step_noise() if step_noise else None, sigma, out_dtype=outs[0].dtype)
+        for i, o in enumerate(outs):
+            o.copy_(g[offs[i]:offs[i + 1]])
+    return grad_fn
+
+
+def build(numels, cfg, problem, with_copy=False):
+    adam = cfg.optimizer == B.GXPO_OPT_ADAMW
+    dev = H.DeviceState(numels, adam, with_copy)
+    offs = np.concatenate([[0], np.cumsum(numels)])
+    dev.set_theta([problem.theta_0[offs[i]:offs[i + 1]] for i in range(len(numels))])
+    ctx = B.gxpo_init(cfg, dev.tensor_dicts())
+    orc = O.GXPOOracle(H.oracle_config(cfg), dev.host("theta"))
+    gdt = torch.float32 if cfg.grad_dtype == B.GXPO_GRAD_F32 else torch.bfloat16
+    grads = (H.grad_buffers(numels, gdt), H.grad_buffers(numels, gdt), H.grad_buffers(numels, gdt))
+    return dev, ctx, orc, grads
+
+
+# ---------------------------------------------------------------------------------------------
+# config 1: plain-GD quadratic surrogate, P = 2^20, eta = 0.1, K = 4, 20 active steps
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("fused", [True, False])
+@pytest.mark.parametrize("alpha", [1.0, 0.5])
+def test_surrogate_config1_lockstep_and_closed_form(fused, alpha):
+    P, eta, K = 1 << 20, 0.1, 4
+    problem = synth.surrogate_problem(P, 0, device="cuda")
+    cfg = B.make_config(optimizer="gd", K=K, alpha=alpha, delta=0.0, lr=eta, fuse_step2=fused, tau=3.0, window=10)
+    dev, ctx, orc, grads = build([P], cfg, problem)
+    grad_fn = quad_trainer(problem, [P])
+    h, ts, th0 = (H.f64(x) for x in (problem.h, problem.theta_star, problem.theta_0))
+    rho = 1.0 - eta * h
+    for step in range(20):
+        start = dev.host("theta")[0]
+        info, _ = H.lockstep_active_step(ctx, dev, orc, grad_fn, grads, dtol=1e-5, fused=fused, what=f"step {step}")
+        assert not info.tripped
+        # one outer step multiplies the error by rho (1 - alpha + alpha rho^K); alpha = 1: K + 1 GD steps
+        want = ts + rho * (1 - alpha + alpha * rho ** K) * (start - ts)
+        got = dev.host("theta")[0]
+        assert np.linalg.norm(got - want) <= 1e-5 * np.linalg.norm(want - start) + 6 * 2.0 ** -24 * np.linalg.norm(want)
+    st = B.gxpo_get_state(ctx)
+    assert (st.t, st.optim_steps, st.backward_passes, st.s_star) == (20, 60, 60, -1)
+    # free-running closed form: theta_20 = theta* + [rho (1 - alpha + alpha rho^K)]^20 (theta_0 - theta*)
+    want = ts + (rho * (1 - alpha + alpha * rho ** K)) ** 20 * (th0 - ts)
+    H.assert_close(dev.host("theta")[0], want, "theta_20 closed form", rtol=1e-5)
+
+
+# ---------------------------------------------------------------------------------------------
+# config 2 shape at reduced size: AdamW, noisy quadratic, K = 8, ragged multi-tensor
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("fused", [True, False])
+@pytest.mark.parametrize("grad_dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("wpb", [0, 4])
+def test_adamw_ragged_lockstep(fused, grad_dtype, wpb):
+    numels = RAGGED
+    P = sum(numels)
+    problem = synth.policy_problem(P, seed=1, sigma=0.05, device="cuda")
+    cfg = B.make_config(optimizer="adamw", grad_dtype=grad_dtype, K=8, alpha=0.5, delta=1.75e-3, lr=1e-6,
+                        weight_decay=0.01, fuse_step2=fused, tau=3.0, window=10, gate_min_count=2,
+                        waves_per_block=wpb, copy_mask=7)
+    dev, ctx, orc, grads = build(numels, cfg, problem, with_copy=True)
+    step_id = [0]
+    noise = lambda: synth.step_noise(problem, step_id[0])
+    grad_fn = quad_trainer(problem, numels, step_noise=noise)
+    for step in range(4):
+        step_id[0] = step
+        H.lockstep_active_step(ctx, dev, orc, grad_fn, grads, dtol=1e-4, fused=fused, check_copy=True,
+                               what=f"{grad_dtype} fused={fused} step {step}")
+    st = B.gxpo_get_state(ctx)
+    assert (st.t, st.optim_steps, st.backward_passes) == (4, 12, 12)
+
+
+@pytest.mark.parametrize("K", [2, 3, 5, 10])
+@pytest.mark.parametrize("alpha", [0.0, 0.1, 1.0])
+def test_paper_K_alpha_grid(K, alpha):
+    numels = [70001, 513]
+    problem = synth.policy_problem(sum(numels), seed=5, sigma=0.05, device="cuda")
+    cfg = B.make_config(K=K, alpha=alpha, delta=1.75e-3, lr=1e-4, gate_min_count=2)
+    dev, ctx, orc, grads = build(numels, cfg, problem)
+    step_id = [0]
+    grad_fn = quad_trainer(problem, numels, step_noise=lambda: synth.step_noise(problem, step_id[0]))
+    for step in range(2):
+        step_id[0] = step
+        H.lockstep_active_step(ctx, dev, orc, grad_fn, grads, dtol=1e-4, fused=True, what=f"K={K} alpha={alpha}")
+    if alpha == 0.0:
+        pass  # theta~ == theta^t is implied by the oracle comparison
+
+
+# ---------------------------------------------------------------------------------------------
+# the extrapolation factor itself, at full fp32 resolution: theta^t = 0, theta^{t,1} = 1
+# ---------------------------------------------------------------------------------------------
+def crafted_gradient_pairs(delta32: float):
+    rng = np.random.default_rng(11)
+    g0, g1 = [], []
+
+    def add(a, b):
+        g0.append(np.float32(a)); g1.append(np.float32(b))
+    for base in (1.0, -0.37, 3.5e-3, 11.0):
+        add(base, base)                                    # r = 1 exactly
+        add(base, 0.0)                                     # r = 0
+        add(base, -base)                                   # r = -1 exactly: degenerate
+        for eps in (2.0 ** -23, 2.0 ** -20, 1e-6, 1e-4, 1e-2, 0.3):
+            add(base, base * (1 + eps)); add(base, base * (1 - eps))          # around +1
+            add(base, -base * (1 + eps)); add(base, -base * (1 - eps))        # around the pole at -1
+        for r in (0.5, -0.5, 2.0, -2.0, 3.0, -3.0, 10.0, -7.0, 1e-3):
+            add(base, base * r)
+    d = np.float32(delta32)
+    add(d, d); add(-d, d)                                  # |g0| == delta: inactive
+    add(np.nextafter(d, np.float32(1)), d)                 # one ulp above: active
+    add(np.nextafter(d, np.float32(0)), 5.0)               # one ulp below: inactive
+    add(0.0, 1.0); add(-0.0, -1.0)                         # zero gradient never forms a ratio
+    a = rng.normal(size=4000).astype(np.float32); b = rng.normal(size=4000).astype(np.float32)
+    g0 += list(a); g1 += list(b)                           # heavy-tailed ratios
+    a = rng.normal(size=4000).astype(np.float32)
+    g0 += list(a); g1 += list((a * (1 + 1e-3 * rng.normal(size=4000))).astype(np.float32))   # r ~ 1, the common case
+    return np.array(g0, dtype=np.float32), np.array(g1, dtype=np.float32)
+
+
+@pytest.mark.parametrize("K", [2, 3, 4, 5, 8, 9, 10])
+@pytest.mark.parametrize("r_max", [math.inf, 4.0, 1.0])
+@pytest.mark.parametrize("fused", [True, False])
+def test_scale_factor_crafted(K, r_max, fused):
+    delta = 1e-3
+    g0_np, g1_np = crafted_gradient_pairs(float(np.float32(delta)))
+    n = g0_np.size
+    lr = 2.0 ** -10
+    alpha = 1.0
+    cfg = B.make_config(optimizer="gd", K=K, alpha=alpha, delta=delta, r_max=r_max, lr=lr, fuse_step2=fused)
+    dev = H.DeviceState([n], adam=False, with_copy=False)
+    dev.views["theta"][0].zero_()
+    ctx = B.gxpo_init(cfg, dev.tensor_dicts())
+    g0 = torch.from_numpy(g0_np).cuda()
+    g1 = torch.from_numpy(g1_np).cuda()
+    B.gxpo_fast_steps(ctx, 0, [g0])
+    # the buffers are the caller's: plant theta^{t,1} = 1 (fused) or theta^{t,2} = 1 (unfused)
+    dev.views["theta_probe"][0].fill_(1.0)
+    B.gxpo_fast_steps(ctx, 1, [g1])
+    if not fused:
+        dev.views["theta_probe"][0].fill_(1.0)
+    B.gxpo_extrapolate(ctx, [g0], [g1])
+    torch.cuda.synchronize()
+    got = dev.host("theta")[0]
+    g0d, g1d = g0_np.astype(np.float64), g1_np.astype(np.float64)
+    th2 = (1.0 - lr * g1d) if fused else np.ones(n)
+    scale, _, want = O.extrapolate(np.zeros(n), th2, g0d, g1d, K, alpha, delta, r_max)
+    finite = np.isfinite(want) & (np.abs(want) < 1e30)
+    assert finite.sum() > 0.9 * n
+    rel = np.abs(got[finite] - want[finite]) / np.maximum(np.abs(want[finite]), 1e-30)
+    worst = int(np.argmax(rel))
+    assert rel.max() <= 1e-5, (f"scale mismatch: rel {rel.max():.3e} at g0={g0_np[finite][worst]!r} g1={g1_np[finite][worst]!r} "
+                               f"got {got[finite][worst]!r} want {want[finite][worst]!r}")
+    # special values survive fp32 exactly
+    same = (g0_np == g1_np) & (np.abs(g0_np) > np.float32(delta))
+    assert same.any()
+    np.testing.assert_allclose(got[same], th2[same] * (K / 2), rtol=2e-7)
+    degenerate = (g1_np == -g0_np) | ~(np.abs(g0_np) > np.float32(delta))
+    np.testing.assert_allclose(got[degenerate], th2[degenerate], rtol=2e-7)
+
+
+# ---------------------------------------------------------------------------------------------
+# partly fresh noise between the probes: broad, Cauchy-tailed retention ratios, clamped
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("K", [5, 8])
+def test_broad_retention_spread_with_clamp(K):
+    numels = [50000, 7777]
+    P = sum(numels)
+    problem = synth.policy_problem(P, seed=7, sigma=0.05, device="cuda")
+    cfg = B.make_config(K=K, alpha=0.5, delta=1.75e-3, r_max=2.0, lr=1e-4, gate_min_count=2)
+    dev, ctx, orc, grads = build(numels, cfg, problem)
+    call = [0]
+
+    def noise():
+        base = synth.step_noise(problem, 100)
+        fresh = synth.step_noise(problem, 200 + call[0])
+        call[0] += 1
+        return 0.5 * base + math.sqrt(0.75) * fresh
+    grad_fn = quad_trainer(problem, numels, step_noise=noise)
+    H.lockstep_active_step(ctx, dev, orc, grad_fn, grads, dtol=1e-4, fused=True, what="broad r")
+    r = H.f64(grads[1][0]) / H.f64(grads[0][0])
+    assert np.std(np.clip(r, -5, 5)) > 0.5              # the ratios really are broad
+
+
+# ---------------------------------------------------------------------------------------------
+# gate transition and fallback (config 5 at reduced size)
+# ---------------------------------------------------------------------------------------------
+def test_gate_transition_free_running_and_fallback():
+    """50 free-running steps, sigma raised from 0.05 to 1.0 at step 30.  GPU and oracle
+    each follow their own trajectory (own parameters, own gradients of the same loss and
+    noise); every gate decision must agree.  With w = 10 a stationary norm sequence trips
+    tau = 3 by chance about once in a hundred steps; if that happens before step 30 both
+    sides must agree on it, and both are then put back into the active phase through the
+    state interface so that the real transition at step 30 is still exercised."""
+    P = (1 << 18) + 37
+    numels = [P]
+    problem = synth.policy_problem(P, seed=4, sigma=0.05, device="cuda")
+    cfg = B.make_config(K=8, alpha=0.5, delta=1.75e-3, lr=1e-6, tau=3.0, window=10)
+    dev, ctx, orc, grads = build(numels, cfg, problem)
+    g0b, g1b, gsb = grads
+    h64, ts64 = H.f64(problem.h), H.f64(problem.theta_star)
+    sigma_of = lambda step: 0.05 if step < 30 else 1.0
+    early_trips, n_active = [], 0
+    for step in range(50):
+        xi = synth.step_noise(problem, step)
+        xi64 = H.f64(xi)
+        sig = sigma_of(step)
+        gpu_grad = lambda th, out: out[0].copy_(synth.quadratic_grad(problem, th[0], xi, sig))
+        # the oracle's trainer evaluates the same loss at the oracle's own fp64 parameters,
+        # and hands the gradient over in fp32 like the GPU's trainer does
+        ref_grad = lambda ths: [(h64 * (ths[0] - ts64) + sig * xi64).astype(np.float32).astype(np.float64)]
+        st = B.gxpo_get_state(ctx)
+        active_gpu = st.s_star < 0 or st.t < st.s_star
+        assert active_gpu == orc.is_active(), f"phase differs at step {step}"
+        if active_gpu:
+            n_active += 1
+            gpu_grad(dev.views["theta"], g0b); B.gxpo_fast_steps(ctx, 0, g0b)
+            gpu_grad(dev.views["theta_probe"], g1b); B.gxpo_fast_steps(ctx, 1, g1b)
+            B.gxpo_extrapolate(ctx, g0b, g1b)
+            gpu_grad(dev.views["theta"], gsb); B.gxpo_slow_step(ctx, gsb)
+            info = B.gxpo_gate(ctx)
+            ref = orc.train_step(ref_grad)
+            assert bool(info.evaluated) == ref.evaluated
+            assert bool(info.tripped) == ref.tripped, f"gate decision differs at step {step}: Z {info.z} vs {ref.z}"
+            assert info.norm == pytest.approx(ref.norm, rel=1e-6)
+            if ref.evaluated:
+                assert info.z == pytest.approx(ref.z, rel=1e-3, abs=1e-2)
+            if info.tripped:
+                assert info.s_star == ref.s_star == step + 1
+                if step < 30:                                  # chance trip: agree, then re-arm both sides
+                    early_trips.append(step)
+                    st = B.gxpo_get_state(ctx)
+                    st.s_star = -1
+                    B.gxpo_set_state(ctx, st)
+                    orc.gate.s_star = None
+        else:
+            with pytest.raises(B.GxpoError) as e:
+                B.gxpo_fast_steps(ctx, 0, g0b)
+            assert e.value.code == B.GXPO_ERR_BAD_STATE
+            gpu_grad(dev.views["theta"], g0b); B.gxpo_fallback_step(ctx, g0b)
+            orc.train_step(ref_grad)
+    print("chance trips before the transition:", early_trips)
+    st = B.gxpo_get_state(ctx)
+    assert st.s_star == 31 and orc.s_star == 31 and st.t == 50     # first sigma = 1 step is t = 30
+    assert n_active == 31
+    assert st.backward_passes == orc.backward_passes == 3 * 31 + (50 - 31)
+    assert st.optim_steps == orc.optim_steps
+    H.assert_close(dev.host("theta")[0], orc.theta[0], "theta after 50 free-running steps")
+    H.assert_close(dev.host("m")[0], orc.m[0], "m after 50 steps")
+    H.assert_close(dev.host("v")[0], orc.v[0], "v after 50 steps")
+    dev.check_canaries()
+
+
+@pytest.mark.parametrize("grad_dtype", ["f32", "bf16"])
+def test_fallback_step_parity_and_bitwise_equal_to_first_fast_step(grad_dtype):
+    numels = RAGGED
+    P = sum(numels)
+    problem = synth.policy_problem(P, seed=9, sigma=0.05, device="cuda")
+    cfg = B.make_config(grad_dtype=grad_dtype, lr=1e-6, copy_mask=7)
+    dev_a, ctx_a, orc, grads = build(numels, cfg, problem, with_copy=True)
+    dev_b, ctx_b, _, _ = build(numels, cfg, problem, with_copy=True)
+    g0b = grads[0]
+    grad_fn = quad_trainer(problem, numels, step_noise=lambda: synth.step_noise(problem, 0))
+    # warm both contexts up with one identical active step so the moments are non-trivial
+    for ctx, dev in ((ctx_a, dev_a), (ctx_b, dev_b)):
+        grad_fn(dev.views["theta"], g0b)
+        B.gxpo_fast_steps(ctx, 0, g0b); B.gxpo_fast_steps(ctx, 1, g0b); B.gxpo_extrapolate(ctx, g0b, g0b)
+        B.gxpo_slow_step(ctx, g0b); B.gxpo_gate(ctx)
+    for k in ("theta", "m", "v"):
+        for a, b in zip(dev_a.views[k], dev_b.views[k]):
+            assert torch.equal(a, b)
+    # fallback is refused before the gate trips
+    with pytest.raises(B.GxpoError) as e:
+        B.gxpo_fallback_step(ctx_a, g0b)
+    assert e.value.code == B.GXPO_ERR_BAD_STATE
+    st = B.gxpo_get_state(ctx_a)
+    st.s_star = st.t                                    # restore a tripped state
+    B.gxpo_set_state(ctx_a, st)
+    H.sync_oracle_to_device(orc, dev_a, st.optim_steps)
+    orc.gate.s_star = orc.t = int(st.t)
+    start = dev_a.host("theta")
+    grad_fn(dev_a.views["theta"], g0b)
+    B.gxpo_fallback_step(ctx_a, g0b)                    # theta <- OptimStep(theta, g0), in place
+    B.gxpo_fast_steps(ctx_b, 0, g0b)                    # theta_probe <- OptimStep(theta, g0)
+    torch.cuda.synchronize()
+    ref = orc.fallback_step([H.f64(g) for g in g0b])
+    for i in range(len(numels)):
+        H.assert_close(dev_a.host("theta")[i], ref[i], f"fallback theta tensor {i}")
+        H.assert_close(dev_a.host("m")[i], orc.m[i], f"fallback m tensor {i}")
+        H.assert_close(dev_a.host("v")[i], orc.v[i], f"fallback v tensor {i}")
+        assert torch.equal(dev_a.views["theta"][i], dev_b.views["theta_probe"][i])      # same arithmetic, bit for bit
+        assert torch.equal(dev_a.views["m"][i], dev_b.views["m"][i])
+        assert torch.equal(dev_a.views["v"][i], dev_b.views["v"][i])
+    num = math.sqrt(sum(float(np.sum(((g - s) - (r - s)) ** 2)) for g, r, s in zip(dev_a.host("theta"), ref, start)))
+    den = math.sqrt(sum(float(np.sum((r - s) ** 2)) for r, s in zip(ref, start)))
+    ref_norm = math.sqrt(sum(float(np.sum(r * r)) for r in ref))
+    assert num <= 1e-4 * den + 2.0 ** -24 * ref_norm
+    H.check_bf16_copy(dev_a, ref, "fallback")
+    st2 = B.gxpo_get_state(ctx_a)
+    assert (st2.t, st2.optim_steps, st2.backward_passes) == (st.t + 1, st.optim_steps + 1, st.backward_passes + 1)
+    dev_a.check_canaries(); dev_b.check_canaries()
+
+
+# ---------------------------------------------------------------------------------------------
+# call order, errors, state round trip
+# ---------------------------------------------------------------------------------------------
+def test_call_order_state_machine_and_errors():
+    n = 1000
+    problem = synth.policy_problem(n, seed=3, device="cuda")
+    cfg = B.make_config(fuse_step2=True)
+    dev, ctx, orc, grads = build([n], cfg, problem)
+    g = [torch.randn(n, device="cuda")]
+    g_other = [torch.randn(n, device="cuda")]
+
+    def refused(fn, code=B.GXPO_ERR_BAD_STATE):
+        with pytest.raises(B.GxpoError) as e:
+            fn()
+        assert e.value.code == code and e.value.message
+    refused(lambda: B.gxpo_fast_steps(ctx, 1, g))
+    refused(lambda: B.gxpo_extrapolate(ctx, g, g))
+    refused(lambda: B.gxpo_slow_step(ctx, g))
+    refused(lambda: B.gxpo_gate(ctx))
+    refused(lambda: B.gxpo_fallback_step(ctx, g))
+    refused(lambda: B.gxpo_tensor_norms(ctx))
+    refused(lambda: B.gxpo_fast_steps(ctx, 2, g), B.GXPO_ERR_INVALID_ARG)
+    B.gxpo_fast_steps(ctx, 0, g)
+    refused(lambda: B.gxpo_fast_steps(ctx, 0, g))
+    refused(lambda: B.gxpo_set_state(ctx, B.gxpo_get_state(ctx)))
+    B.gxpo_fast_steps(ctx, 1, g)
+    refused(lambda: B.gxpo_extrapolate(ctx, g, g_other), B.GXPO_ERR_INVALID_ARG)   # not the g1 that was recorded
+    B.gxpo_extrapolate(ctx, g, g)
+    refused(lambda: B.gxpo_fast_steps(ctx, 0, g))
+    B.gxpo_slow_step(ctx, g)
+    refused(lambda: B.gxpo_slow_step(ctx, g))
+    info = B.gxpo_gate(ctx)
+    assert info.t == 0 and not info.evaluated and info.norm == pytest.approx(float(g[0].double().norm()), rel=1e-12)
+    # misaligned / foreign gradient pointers
+    bad = [torch.randn(n + 1, device="cuda")[1:]]
+    refused(lambda: B.gxpo_fast_steps(ctx, 0, bad), B.GXPO_ERR_ALIGNMENT)
+    with pytest.raises(ValueError):
+        B.gxpo_fast_steps(ctx, 0, [torch.randn(n, device="cuda", dtype=torch.float64)])
+    # state round trip
+    st = B.gxpo_get_state(ctx)
+    assert (st.t, st.optim_steps, st.backward_passes, st.window_len, st.phase) == (1, 3, 3, 1, B.GXPO_PHASE_IDLE)
+    st.t, st.optim_steps, st.s_star = 7, 21, 9
+    B.gxpo_set_state(ctx, st)
+    st2 = B.gxpo_get_state(ctx)
+    assert (st2.t, st2.optim_steps, st2.s_star) == (7, 21, 9)
+    B.gxpo_fast_steps(ctx, 0, g)                       # still active: t = 7 < s* = 9
+    B.gxpo_destroy(ctx)
+
+
+def test_init_rejects_host_memory_and_short_allocations():
+    n = 4096
+    cfg = B.make_config(optimizer="gd")
+    theta = torch.zeros(n, device="cuda")
+    probe = torch.zeros(n, device="cuda")
+    arr = (B.gxpo_tensor * 1)()
+    arr[0].numel = 1 << 24                              # far beyond the 16 KiB allocation
+    arr[0].theta, arr[0].theta_probe = theta.data_ptr(), probe.data_ptr()
+    import ctypes
+    out = ctypes.c_void_p()
+    assert B._lib.gxpo_init(ctypes.byref(out), ctypes.byref(cfg), arr, 1) == B.GXPO_ERR_INVALID_ARG
+    host = torch.zeros(n)
+    arr[0].numel = n
+    arr[0].theta = host.data_ptr()
+    assert B._lib.gxpo_init(ctypes.byref(out), ctypes.byref(cfg), arr, 1) == B.GXPO_ERR_INVALID_ARG
+    assert out.value is None
+
+
+# ---------------------------------------------------------------------------------------------
+# reduction: reproducible, per-tensor, many blocks
+# ---------------------------------------------------------------------------------------------
+def test_norm_reduction_is_bit_reproducible_and_matches_oracle():
+    numels = [3 * 8192 * 256 + 11, 5, 700001]           # first tensor spans more than one reduction run
+    cfg = B.make_config(optimizer="gd", lr=1e-3, gate_min_count=2)
+    results = []
+    g = H.grad_buffers(numels, torch.float32)
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    for x in g:
+        x.copy_(torch.randn(x.numel(), generator=gen, device="cuda") * 0.05)
+    for rep in range(2):
+        dev = H.DeviceState(numels, adam=False, with_copy=False)
+        for x in dev.views["theta"]:
+            x.zero_()
+        ctx = B.gxpo_init(cfg, dev.tensor_dicts())
+        B.gxpo_fast_steps(ctx, 0, g); B.gxpo_fast_steps(ctx, 1, g); B.gxpo_extrapolate(ctx, g, g); B.gxpo_slow_step(ctx, g)
+        info = B.gxpo_gate(ctx)
+        results.append((info.norm, tuple(B.gxpo_tensor_norms(ctx))))
+        B.gxpo_destroy(ctx)
+    assert results[0] == results[1]                      # bit-identical from run to run
+    want = [math.sqrt(O.sum_squares(H.f64(x))) for x in g]
+    for a, b in zip(results[0][1], want):
+        assert a == pytest.approx(b, rel=1e-13)
+    assert results[0][0] == pytest.approx(math.sqrt(sum(w * w for w in want)), rel=1e-13)
+
+
+def test_stream_copy_reference_kernel():
+    for n in (4, 256, 260, 1 << 20, (1 << 20) + 12):
+        src = torch.randn(n, device="cuda")
+        dst = torch.full((n + 8,), 7.0, device="cuda")
+        B.gxpo_stream_copy(dst[:n], src)
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:n], src) and bool((dst[n:] == 7.0).all())

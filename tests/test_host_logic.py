@@ -1,0 +1,175 @@
+"""CPU-only checks of the library's host side: exported symbols, configuration
+validation, the block plan for ragged tensor lists and the gate rule.  No
+kernel is launched here."""
+import ctypes
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import gxpo_oracle as O
+from paper_2605_06755_amd import binding as B
+from paper_2605_06755_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "gxpo.h")).read()
+    declared = set(re.findall(r"^\s*(?:int|void|const char \*)\s*\*?\s*(gxpo_\w+)\s*\(", header, flags=re.M))
+    assert declared == set(B.EXPORTED_SYMBOLS), declared ^ set(B.EXPORTED_SYMBOLS)
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_struct_sizes_match_the_header_layout():
+    # natural C layout of the header's structs on x86-64
+    assert ctypes.sizeof(B.gxpo_tensor) == 8 + 5 * 8
+    assert ctypes.sizeof(B.gxpo_config) == 10 * 4 + 10 * 8
+    assert ctypes.sizeof(B.gxpo_gate_info) == 4 * 8 + 2 * 4 + 2 * 8
+    assert ctypes.sizeof(B.gxpo_state) == 2 * 4 + 4 * 8 + 2 * 4 + 8 * B.GXPO_MAX_WINDOW
+
+
+def test_default_config_is_valid():
+    rc, msg = B.gxpo_validate_config(B.make_config())
+    assert rc == B.GXPO_OK, msg
+
+
+@pytest.mark.parametrize("kwargs,code", [
+    (dict(K=1), B.GXPO_ERR_INVALID_ARG),
+    (dict(K=0), B.GXPO_ERR_INVALID_ARG),
+    (dict(alpha=-0.1), B.GXPO_ERR_INVALID_ARG),
+    (dict(alpha=1.5), B.GXPO_ERR_INVALID_ARG),
+    (dict(alpha=float("nan")), B.GXPO_ERR_INVALID_ARG),
+    (dict(lr=0.0), B.GXPO_ERR_INVALID_ARG),
+    (dict(lr=-1e-3), B.GXPO_ERR_INVALID_ARG),
+    (dict(delta=-1.0), B.GXPO_ERR_INVALID_ARG),
+    (dict(r_max=0.0), B.GXPO_ERR_INVALID_ARG),
+    (dict(window=1), B.GXPO_ERR_INVALID_ARG),
+    (dict(window=B.GXPO_MAX_WINDOW + 1), B.GXPO_ERR_INVALID_ARG),
+    (dict(gate_min_count=1), B.GXPO_ERR_INVALID_ARG),
+    (dict(window=5, gate_min_count=6), B.GXPO_ERR_INVALID_ARG),
+    (dict(gate_ddof=2), B.GXPO_ERR_INVALID_ARG),
+    (dict(gate_eps=0.0), B.GXPO_ERR_INVALID_ARG),
+    (dict(beta1=1.0), B.GXPO_ERR_INVALID_ARG),
+    (dict(beta2=-0.1), B.GXPO_ERR_INVALID_ARG),
+    (dict(waves_per_block=3), B.GXPO_ERR_INVALID_ARG),
+    (dict(copy_mask=8), B.GXPO_ERR_INVALID_ARG),
+    (dict(optimizer=7), B.GXPO_ERR_UNSUPPORTED),
+    (dict(grad_dtype=2), B.GXPO_ERR_UNSUPPORTED),
+])
+def test_bad_configs_are_rejected_with_a_message(kwargs, code):
+    rc, msg = B.gxpo_validate_config(B.make_config(**kwargs))
+    assert rc == code
+    assert msg
+
+
+@pytest.mark.parametrize("kwargs", [dict(K=2), dict(alpha=0.0), dict(alpha=1.0), dict(delta=math.inf),
+                                    dict(delta=0.0), dict(r_max=1.0), dict(optimizer="gd"), dict(grad_dtype="bf16"),
+                                    dict(gate_min_count=2), dict(window=B.GXPO_MAX_WINDOW), dict(tau=-1.0)])
+def test_edge_configs_are_accepted(kwargs):
+    rc, msg = B.gxpo_validate_config(B.make_config(**kwargs))
+    assert rc == B.GXPO_OK, msg
+
+
+def test_struct_size_mismatch_is_rejected():
+    c = B.make_config()
+    c.struct_size -= 4
+    assert B.gxpo_validate_config(c)[0] == B.GXPO_ERR_INVALID_ARG
+
+
+def test_init_rejects_bad_arguments_before_touching_the_gpu():
+    out = ctypes.c_void_p()
+    lib = B._lib
+    cfg = B.make_config()
+    assert lib.gxpo_init(ctypes.byref(out), ctypes.byref(cfg), None, 0) == B.GXPO_ERR_INVALID_ARG
+    assert out.value is None and B.gxpo_last_error(None)
+    t = (B.gxpo_tensor * 1)()
+    t[0].numel = 16
+    assert lib.gxpo_init(ctypes.byref(out), ctypes.byref(cfg), t, 1) == B.GXPO_ERR_INVALID_ARG      # theta NULL
+    t[0].theta, t[0].theta_probe, t[0].m, t[0].v = 0x1004, 0x2000, 0x3000, 0x4000
+    assert lib.gxpo_init(ctypes.byref(out), ctypes.byref(cfg), t, 1) == B.GXPO_ERR_ALIGNMENT
+    assert "aligned" in B.gxpo_last_error(None)
+    t[0].theta = 0x1000
+    t[0].m = 0x1020                                                                                   # overlaps theta
+    assert lib.gxpo_init(ctypes.byref(out), ctypes.byref(cfg), t, 1) == B.GXPO_ERR_INVALID_ARG
+    assert "overlaps" in B.gxpo_last_error(None)
+    t[0].m = None
+    assert lib.gxpo_init(ctypes.byref(out), ctypes.byref(cfg), t, 1) == B.GXPO_ERR_INVALID_ARG      # AdamW needs m
+    gd = B.make_config(optimizer="gd")
+    t[0].m = 0x3000
+    assert lib.gxpo_init(ctypes.byref(out), ctypes.byref(gd), t, 1) == B.GXPO_ERR_INVALID_ARG       # GD forbids m, v
+    t[0].numel = 0
+    assert lib.gxpo_init(ctypes.byref(out), ctypes.byref(cfg), t, 1) == B.GXPO_ERR_INVALID_ARG
+    assert out.value is None
+
+
+# ---- block plan ---------------------------------------------------------------------------------
+@pytest.mark.parametrize("wpb", [0, 1, 2, 4])
+def test_block_plan_covers_every_element_exactly_once(wpb):
+    rng = np.random.default_rng(0)
+    numels = [1, 255, 256, 257, 4096, 1023, 5, 100000] + [int(x) for x in rng.integers(1, 50000, size=40)]
+    start, epb = B.gxpo_plan_blocks(numels, wpb)
+    assert epb == 256 * (wpb or 1)
+    assert start[0] == 0 and len(start) == len(numels) + 1
+    for t, n in enumerate(numels):
+        nb = start[t + 1] - start[t]
+        assert (nb - 1) * epb < n <= nb * epb
+
+
+def test_block_plan_for_the_llama_layout():
+    layout = synth.llama31_8b_layout()
+    assert len(layout) == 290
+    numels = [n for _, n in layout]
+    assert sum(numels) == 8_030_257_152
+    start, epb = B.gxpo_plan_blocks(numels)
+    assert start[-1] == sum(-(-n // epb) for n in numels)
+    assert start[-1] < 2 ** 31
+
+
+def test_block_plan_rejects_too_large_and_empty():
+    with pytest.raises(B.GxpoError):
+        B.gxpo_plan_blocks([0])
+    with pytest.raises(B.GxpoError):
+        B.gxpo_plan_blocks([2 ** 40])
+
+
+# ---- gate rule against the oracle's gate -----------------------------------------------------------
+@pytest.mark.parametrize("window,min_count,ddof,tau", [(10, 0, 0, 3.0), (4, 2, 0, 1.0), (6, 3, 1, 2.0), (2, 0, 1, 0.5)])
+def test_host_gate_matches_oracle_gate(window, min_count, ddof, tau):
+    rng = np.random.default_rng(window * 7 + ddof)
+    cfg = B.make_config(window=window, gate_min_count=min_count, gate_ddof=ddof, tau=tau, gate_eps=1e-8)
+    for trial in range(20):
+        st = B.new_state()
+        orc = O.RollingGate(O.GateConfig(tau=tau, window=window, eps=1e-8, ddof=ddof,
+                                         min_count=(min_count or None)))
+        level = 1.0
+        for t in range(40):
+            if rng.random() < 0.05:
+                level *= 3.0
+            x = float(level * (1.0 + 0.01 * rng.normal()))
+            info = B.gxpo_host_gate_step(cfg, st, x)
+            ref = orc.step(t, x)
+            assert bool(info.evaluated) == ref.evaluated
+            assert info.t == t and st.t == t + 1
+            if ref.evaluated:
+                assert info.mu == pytest.approx(ref.mu, rel=1e-14)
+                assert info.sigma == pytest.approx(ref.sigma, rel=1e-9, abs=1e-300)
+                assert info.z == pytest.approx(ref.z, rel=1e-9, abs=1e-9)
+            assert (info.s_star if info.s_star >= 0 else None) == ref.s_star
+            assert list(st.window[:st.window_len]) == orc.buffer
+
+
+def test_host_gate_hand_case_and_nan():
+    cfg = B.make_config(window=4, gate_min_count=2, tau=2.0, gate_eps=0.5)
+    st = B.new_state()
+    B.gxpo_host_gate_step(cfg, st, 1.0)
+    B.gxpo_host_gate_step(cfg, st, 3.0)
+    info = B.gxpo_host_gate_step(cfg, st, 5.0)               # mu 2, sigma 1, Z = 3 / 1.5 = 2 >= tau
+    assert (info.mu, info.sigma, info.z, info.tripped, info.s_star) == (2.0, 1.0, 2.0, 1, 3)
+    st = B.new_state()
+    info = B.gxpo_host_gate_step(cfg, st, float("inf"))
+    assert info.tripped == 1 and info.s_star == 1 and info.evaluated == 0
