@@ -1,0 +1,295 @@
+#!/usr/bin/env python3
+"""GXPO active-step throughput on one MI355X.
+
+One "step" is one whole active step of the update engine over every parameter:
+gxpo_fast_steps(0), gxpo_fast_steps(1), gxpo_extrapolate (second fast step fused
+in), gxpo_slow_step (+ sum of squares) and gxpo_gate.  The three gradient buffers
+are produced once, before the timed region, by the synthetic trainer at the
+points the algorithm asks for them (theta, theta^{t,1}, theta~) and are then
+reused: computing gradients is the trainer's work, not the engine's.
+
+Prints ONE JSON line (see the design doc for the fields).  `--workload` selects a
+parity-test configuration instead of the default one for ad-hoc measurements.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--waves-per-block", type=int, default=0)
+    ap.add_argument("--unfused", action="store_true", help="run the second fast step and the extrapolation as two passes")
+    ap.add_argument("--same-phase", action="store_true", help="plain torch allocations instead of the phased HBM layout")
+    ap.add_argument("--arena", action="store_true", help="carve all buffers from one allocation")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 26, help="elements of the workload the oracle is timed on")
+    return ap.parse_args()
+
+
+def workload_spec(name: str):
+    from paper_2605_06755_amd import synth
+    if name == "c1":
+        return dict(label="plain-GD quadratic surrogate, 1,048,576 fp32 params, GD eta=0.1, K=4",
+                    layout=[("flat", 1 << 20)], optimizer="gd", grad_dtype="f32", copy=False, seed=0,
+                    cfg=dict(K=4, alpha=1.0, delta=0.0, lr=0.1), surrogate=True)
+    if name == "c2":
+        return dict(label="Qwen2.5-1.5B-sized flat fp32 buffer, P=1.54e9, AdamW, K=8, alpha=0.5, tau=3, w=10",
+                    layout=[("flat", synth.QWEN25_1P5B_PARAMS)], optimizer="adamw", grad_dtype="f32", copy=False, seed=1,
+                    cfg=dict(K=8, alpha=0.5, delta=1.75e-3, lr=1e-6))
+    if name == "c3":
+        return dict(label="Qwen2.5-7B-sized flat fp32 buffer, P=7.6e9, AdamW, bf16 model copy rewritten 3x per step",
+                    layout=[("flat", synth.QWEN25_7B_PARAMS)], optimizer="adamw", grad_dtype="f32", copy=True, seed=2,
+                    cfg=dict(K=8, alpha=0.5, delta=1.75e-3, lr=1e-6))
+    if name == "c4":
+        return dict(label="Llama-3.1-8B ragged layout, 290 tensors, P=8.03e9, bf16 grads, fp32 state",
+                    layout=synth.llama31_8b_layout(), optimizer="adamw", grad_dtype="bf16", copy=False, seed=3,
+                    cfg=dict(K=8, alpha=0.5, delta=1.75e-3, lr=1e-6))
+    if name == "c5":
+        return dict(label="gate-transition buffer, flat fp32, P=3.2e9, AdamW; active and fallback steps",
+                    layout=[("flat", synth.GATE_STRESS_PARAMS)], optimizer="adamw", grad_dtype="f32", copy=False, seed=4,
+                    cfg=dict(K=8, alpha=0.5, delta=1.75e-3, lr=1e-6))
+    raise ValueError(name)
+
+
+def bytes_per_param(spec, fused: bool):
+    """Algorithmic HBM bytes per parameter of each pass (reads + writes of every
+    operand exactly once)."""
+    g = 4 if spec["grad_dtype"] == "f32" else 2
+    mv = 8 if spec["optimizer"] == "adamw" else 0          # m and v, read; the same again written
+    c = 2 if spec["copy"] else 0
+    step = 4 + mv + g + 4 + mv                                # theta, m, v, g in; theta, m, v out
+    out = {"fast_step_1": step + c, "slow_step": step + c, "fallback_step": step + c}
+    if fused:
+        out["fused_step2_extrapolate"] = 4 + mv + g + g + 4 + 4 + mv + c       # theta1,m,v,g1,g0,theta0 in; theta~,m,v out
+    else:
+        out["fast_step_2"] = step
+        out["extrapolate"] = 4 + 4 + g + g + 4 + c
+    return out
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU only (asked for --gpus {args.gpus}); "
+              "sharding is described in DESIGN.md, not implemented", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the GXPO engine has no CPU path", file=sys.stderr)
+        sys.exit(2)
+    from paper_2605_06755_amd import binding as B
+    from paper_2605_06755_amd import layout as layout_mod
+    from paper_2605_06755_amd import synth
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    spec = workload_spec(args.workload)
+    fused = not args.unfused
+    layout = spec["layout"]
+    numels = [n for _, n in layout]
+    P = sum(numels)
+    padded = synth.padded_numel(layout, 4)
+    adam = spec["optimizer"] == "adamw"
+    gdt = torch.float32 if spec["grad_dtype"] == "f32" else torch.bfloat16
+
+    # ---- device buffers (caller-owned), in the layout paper_2605_06755_amd/layout.py describes ---------
+    if args.same_phase:
+        flat = {"theta": torch.empty(padded, dtype=torch.float32, device=dev),
+                "theta_probe": torch.empty(padded, dtype=torch.float32, device=dev)}
+        if adam:
+            flat["m"] = torch.zeros(padded, dtype=torch.float32, device=dev)
+            flat["v"] = torch.zeros(padded, dtype=torch.float32, device=dev)
+        if spec["copy"]:
+            flat["model_copy"] = torch.empty(padded, dtype=torch.bfloat16, device=dev)
+        gflat = [torch.empty(padded, dtype=gdt, device=dev) for _ in range(3)]
+    else:
+        flat, gflat = layout_mod.alloc_engine_state(padded, dev, adam=adam, model_copy=spec["copy"], grad_dtype=gdt,
+                                                    arena=args.arena)
+    print("base addresses:", {k: hex(v.data_ptr()) for k, v in flat.items()}, [hex(g.data_ptr()) for g in gflat], file=sys.stderr)
+    views = {k: synth.split_like(v, layout, 4) for k, v in flat.items()}
+    g0, g1, gs = (synth.split_like(g, layout, 4) for g in gflat)
+    tensors = [{k: views[k][i] for k in views} for i in range(len(numels))]
+
+    if spec.get("surrogate"):
+        quad = synth.ChunkedQuadratic(padded, spec["seed"], 0.0, h_dist="uniform", h_lo=0.1, h_hi=1.0, theta_std=1.0, device=dev)
+    else:
+        quad = synth.ChunkedQuadratic(padded, spec["seed"], 0.05, device=dev)
+    quad.init_theta(flat["theta"])
+
+    cfg = B.make_config(optimizer=spec["optimizer"], grad_dtype=spec["grad_dtype"], fuse_step2=fused, copy_mask=7,
+                        window=10, tau=3.0, waves_per_block=args.waves_per_block, weight_decay=0.01, **spec["cfg"])
+    ctx = B.gxpo_init(cfg, tensors)
+
+    # ---- one live step: gradients evaluated where Algorithm 1 asks for them ----------------------------
+    cpu_inputs = None
+    S = min(args.cpu_sample, numels[0])
+    if not args.no_cpu_baseline:
+        cpu_inputs = {"theta": views["theta"][0][:S].cpu()}
+    quad.grad(flat["theta"], 0, gflat[0])
+    B.gxpo_fast_steps(ctx, 0, g0)
+    quad.grad(flat["theta_probe"], 0, gflat[1])
+    B.gxpo_fast_steps(ctx, 1, g1)
+    B.gxpo_extrapolate(ctx, g0, g1)
+    quad.grad(flat["theta"], 0, gflat[2])
+    B.gxpo_slow_step(ctx, gs)
+    live_info = B.gxpo_gate(ctx)
+    if cpu_inputs is not None:
+        cpu_inputs.update(g0=g0[0][:S].cpu(), g1=g1[0][:S].cpu(), gs=gs[0][:S].cpu())
+
+    def active_step(events=None):
+        calls = (("fast_step_1", lambda: B.gxpo_fast_steps(ctx, 0, g0)),
+                 ("fast_step_2", lambda: B.gxpo_fast_steps(ctx, 1, g1)),
+                 ("fused_step2_extrapolate" if fused else "extrapolate", lambda: B.gxpo_extrapolate(ctx, g0, g1)),
+                 ("slow_step", lambda: B.gxpo_slow_step(ctx, gs)))
+        for name, fn in calls:
+            if events is None or (fused and name == "fast_step_2"):
+                fn()
+                continue
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            events.setdefault(name, []).append((a, b))
+        return B.gxpo_gate(ctx)
+
+    for _ in range(args.warmup):
+        active_step()
+    torch.cuda.synchronize()
+    events = {}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        info = active_step(events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kernel_ms = {k: sum(a.elapsed_time(b) for a, b in v) / len(v) for k, v in events.items()}
+    bpp = bytes_per_param(spec, fused)
+    step_bytes = sum(bpp[k] for k in kernel_ms) * P
+    kernels = {k: {"ms": round(ms, 4), "bytes_per_param": bpp[k], "gbps": round(bpp[k] * P / ms / 1e6, 1)}
+               for k, ms in kernel_ms.items()}
+    dominant = max(kernel_ms, key=lambda k: bpp[k])
+    achieved = bpp[dominant] * P / kernel_ms[dominant] / 1e6
+
+    # ---- plain copy on the same box, same access pattern (context for the roofline fraction) ------------
+    n_copy = min(padded, 1 << 30)
+    for _ in range(2):
+        B.gxpo_stream_copy(flat["theta_probe"][:n_copy], flat["theta"][:n_copy])
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(10):
+        B.gxpo_stream_copy(flat["theta_probe"][:n_copy], flat["theta"][:n_copy])
+    b.record()
+    torch.cuda.synchronize()
+    copy_gbps = 8.0 * n_copy * 10 / a.elapsed_time(b) / 1e6
+
+    # ---- fallback-phase throughput (reported for the gate-transition workload) ---------------------------
+    fallback = None
+    if args.workload == "c5":
+        st = B.gxpo_get_state(ctx)
+        st.s_star = st.t
+        B.gxpo_set_state(ctx, st)
+        for _ in range(args.warmup):
+            B.gxpo_fallback_step(ctx, g0)
+        torch.cuda.synchronize()
+        tf0 = time.perf_counter()
+        for _ in range(args.steps):
+            B.gxpo_fallback_step(ctx, g0)
+        torch.cuda.synchronize()
+        fms = (time.perf_counter() - tf0) * 1e3 / args.steps
+        fallback = {"ms_per_step": round(fms, 4), "gparams_per_s": round(P / fms / 1e6, 2),
+                    "gbps": round(bpp["fallback_step"] * P / fms / 1e6, 1),
+                    "frac_of_peak": round(bpp["fallback_step"] * P / fms / 1e6 / HBM_PEAK_GBPS, 4)}
+
+    # ---- traffic measured with hardware counters, if a summary for this workload is committed ---------------
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{dominant}_{args.workload}.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    # ---- the oracle on the host cores, bounded sample ------------------------------------------------------------
+    cpu_baseline = None
+    if cpu_inputs is not None:
+        cpu_baseline = time_oracle(spec, cfg, cpu_inputs, S)
+
+    out = {
+        "metric": "GXPO active-step Gparams/s and achieved HBM GB/s (% of peak) on 1 MI355X",
+        "value": round(P / ms_per_step / 1e6, 3),
+        "unit": "Gparams/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"configs[{int(args.workload[1]) - 1}]: {spec['label']}", "params": P,
+                   "tensors": len(numels), "grad_dtype": spec["grad_dtype"], "fused_step2": fused,
+                   "waves_per_block": args.waves_per_block or 1, "hbm_layout": "same-phase" if args.same_phase else "moments +32KiB mod 64KiB", "bytes_per_param_per_step": sum(bpp[k] for k in kernel_ms)},
+        "hbm_gbps_step": round(step_bytes / ms_per_step / 1e6, 1),
+        "hbm_frac_of_peak_step": round(step_bytes / ms_per_step / 1e6 / HBM_PEAK_GBPS, 4),
+        "copy_kernel_gbps": round(copy_gbps, 1),
+        "kernels": kernels,
+        "gate": {"norm": info.norm, "z": None if math.isnan(info.z) else info.z, "tripped": bool(info.tripped),
+                 "live_step_norm": live_info.norm},
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic},
+        "cpu_baseline": cpu_baseline,
+    }
+    if fallback:
+        out["fallback_step"] = fallback
+    print(json.dumps(out))
+
+
+def time_oracle(spec, cfg, inputs, S):
+    """The fp64 oracle, as it stands, on the first S elements of the same
+    buffers: one active step (five calls), repeated until ~10 s have passed."""
+    import torch
+    from oracle import gxpo_oracle as O
+    oc = O.GXPOConfig(
+        optim=O.OptimConfig(spec["optimizer"], lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.adam_eps,
+                            weight_decay=cfg.weight_decay),
+        K=cfg.K, alpha=cfg.alpha, delta=cfg.delta, r_max=cfg.r_max,
+        gate=O.GateConfig(tau=cfg.tau, window=cfg.window, eps=cfg.gate_eps))
+    f = lambda t: t.to(dtype=torch.float64).numpy()
+    orc = O.GXPOOracle(oc, [f(inputs["theta"])])
+    g0, g1, gs = [f(inputs["g0"])], [f(inputs["g1"])], [f(inputs["gs"])]
+    steps, t0 = 0, time.perf_counter()
+    while True:
+        orc.fast_step_1(g0)
+        orc.fast_step_2(g1)
+        orc.extrapolate(g0, g1)
+        orc.slow_step(gs)
+        orc.gate_step()
+        steps += 1
+        el = time.perf_counter() - t0
+        if el >= 10.0 or steps >= 8:
+            break
+    return {"value": round(S * steps / el / 1e9, 5), "unit": "Gparams/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {S} parameters of the same buffers, {steps} active step(s) of the fp64 C oracle "
+                      f"(fast step x2, extrapolate, slow step + norm, gate), {el:.1f} s, single thread"}
+
+
+if __name__ == "__main__":
+    main()

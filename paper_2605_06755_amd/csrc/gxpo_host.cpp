@@ -68,7 +68,10 @@ struct gxpo_ctx {
     gxpo_state st{};
     mutable std::string err;
 
-    Layout layout() const { return Layout{d_tab, d_blk_start, d_coarse, n, n_blocks}; }
+    Layout layout() const {
+        const gxpo_tensor &x = tensors[0];
+        return Layout{d_tab, d_blk_start, d_coarse, n, n_blocks, TensorRec{x.theta, x.theta_probe, x.m, x.v, x.model_copy, x.numel}};
+    }
 };
 
 namespace {
@@ -202,7 +205,7 @@ int check_call(gxpo_ctx *ctx, const void *const *grads, const char *name) {
 }
 
 // Make the device pointer table of `role` hold `grads`; returns the device table.
-int stage_grads(gxpo_ctx *ctx, int role, const void *const *grads, hipStream_t stream, const void *const **d_out) {
+int stage_grads(gxpo_ctx *ctx, int role, const void *const *grads, hipStream_t stream, GradArg *d_out) {
     const uint32_t n = ctx->n;
     const uint32_t gbytes = ctx->cfg.grad_dtype == GXPO_GRAD_F32 ? 4u : 2u;
     const uintptr_t align = ctx->cfg.grad_dtype == GXPO_GRAD_F32 ? 16u : 8u;
@@ -229,7 +232,7 @@ int stage_grads(gxpo_ctx *ctx, int role, const void *const *grads, hipStream_t s
         ctx->stage_used[slot] = true;
         sh.assign(grads, grads + n);
     }
-    *d_out = d_tab;
+    *d_out = GradArg{d_tab, grads[0]};
     return GXPO_OK;
 }
 
@@ -458,7 +461,7 @@ int gxpo_fast_steps(gxpo_ctx *ctx, int which, const void *const *grads, void *st
     for (uint32_t t = 0; t < ctx->n; ++t)
         if (!ctx->tensors[t].theta_probe) return fail(ctx, GXPO_ERR_INVALID_ARG, "tensor %u has no theta_probe: active phase unavailable", t);
     hipStream_t s = (hipStream_t)stream;
-    const void *const *d_g = nullptr;
+    GradArg d_g{};
     rc = stage_grads(ctx, which == 0 ? kRoleG0 : kRoleG1, grads, s, &d_g);
     if (rc != GXPO_OK) return rc;
     const int64_t step_no = st.optim_steps + 1;
@@ -489,7 +492,7 @@ int gxpo_extrapolate(gxpo_ctx *ctx, const void *const *g0, const void *const *g1
         for (uint32_t t = 0; t < ctx->n; ++t)
             if (g1[t] != ctx->pending_g1[t])
                 return fail(ctx, GXPO_ERR_INVALID_ARG, "gxpo_extrapolate: g1 of tensor %u differs from the one given to gxpo_fast_steps(1)", t);
-    const void *const *d_g0 = nullptr, *const *d_g1 = nullptr;
+    GradArg d_g0{}, d_g1{};
     rc = stage_grads(ctx, kRoleG0, g0, s, &d_g0);
     if (rc == GXPO_OK) rc = stage_grads(ctx, kRoleG1, g1, s, &d_g1);
     if (rc != GXPO_OK) return rc;
@@ -512,7 +515,7 @@ int gxpo_slow_step(gxpo_ctx *ctx, const void *const *g_slow, void *stream) {
     gxpo_state &st = ctx->st;
     if (st.phase != GXPO_PHASE_REPOSITIONED) return fail(ctx, GXPO_ERR_BAD_STATE, "gxpo_slow_step called in phase %u", st.phase);
     hipStream_t s = (hipStream_t)stream;
-    const void *const *d_g = nullptr;
+    GradArg d_g{};
     rc = stage_grads(ctx, kRoleSlow, g_slow, s, &d_g);
     if (rc != GXPO_OK) return rc;
     const int64_t step_no = st.optim_steps + 1;
@@ -555,7 +558,7 @@ int gxpo_fallback_step(gxpo_ctx *ctx, const void *const *g0, void *stream) {
     if (st.phase != GXPO_PHASE_IDLE) return fail(ctx, GXPO_ERR_BAD_STATE, "gxpo_fallback_step called in phase %u", st.phase);
     if (!is_fallback_phase(st)) return fail(ctx, GXPO_ERR_BAD_STATE, "gxpo_fallback_step: the gate has not tripped (t = %lld)", (long long)st.t);
     hipStream_t s = (hipStream_t)stream;
-    const void *const *d_g = nullptr;
+    GradArg d_g{};
     rc = stage_grads(ctx, kRoleG0, g0, s, &d_g);
     if (rc != GXPO_OK) return rc;
     const int64_t step_no = st.optim_steps + 1;

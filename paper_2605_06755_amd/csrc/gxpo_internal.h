@@ -33,6 +33,14 @@ struct Layout {
     const uint32_t *coarse;
     uint32_t n_tensors;
     uint32_t n_blocks;
+    TensorRec single;       // copy of tab[0]; used instead of the tables when n_tensors == 1
+};
+
+// One gradient list as a kernel argument: the device pointer table, plus the
+// pointer itself when there is a single tensor (saves a dependent load).
+struct GradArg {
+    const void *const *table;
+    const void *single;
 };
 
 // OptimStep constants, derived in double on the host, rounded once to fp32.
@@ -63,15 +71,15 @@ enum { kSrcTheta = 0, kSrcProbe = 1 };
 
 // All launchers enqueue on `stream` and return the launch status.
 hipError_t launch_step(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype,
-                       const void *const *d_grads, const StepParams &p,
+                       const GradArg &d_grads, const StepParams &p,
                        int src, int dst, int write_copy, double *d_partial, hipStream_t stream);
 
 hipError_t launch_extrapolate(const Layout &L, uint32_t wpb, int grad_dtype,
-                              const void *const *d_g0, const void *const *d_g1,
+                              const GradArg &d_g0, const GradArg &d_g1,
                               const ExtrapParams &e, int write_copy, hipStream_t stream);
 
 hipError_t launch_fused_step2_extrapolate(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype,
-                                          const void *const *d_g0, const void *const *d_g1,
+                                          const GradArg &d_g0, const GradArg &d_g1,
                                           const StepParams &p, const ExtrapParams &e,
                                           int write_copy, hipStream_t stream);
 

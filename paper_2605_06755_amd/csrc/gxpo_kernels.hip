@@ -14,7 +14,8 @@
 //    hardware range check makes the ragged last block of a tensor safe:
 //    out-of-range lanes load 0 and their stores are dropped.
 //  * the block -> (tensor, offset) map is two or three scalar loads (coarse
-//    index + short scan), skipped entirely for a single flat tensor.
+//    index + short scan); a single flat tensor skips it and takes every
+//    pointer straight from the kernel arguments.
 //
 // Arithmetic is fp32 with the optimizer constants prepared in double on the
 // host; only the sum of squares of g_slow is accumulated in fp64.
@@ -107,6 +108,9 @@ template <int GDT> __device__ __forceinline__ __amdgpu_buffer_rsrc_t grad_rsrc(c
     if (GDT == 0) return span_rsrc((const float *)g + e0, cnt * 4u);
     return span_rsrc((const unsigned short *)g + e0, cnt * 2u);
 }
+__device__ __forceinline__ const void *grad_ptr(const GradArg &g, const Layout &L, uint32_t tensor) {
+    return L.n_tensors > 1 ? g.table[tensor] : g.single;
+}
 template <int GDT> __device__ __forceinline__ f32x4 load_grad(__amdgpu_buffer_rsrc_t r, uint32_t elem, bool full) {
     if (GDT == 0) return load_f32(r, elem, full);
     return load_bf16(r, elem, full);
@@ -131,8 +135,14 @@ template <int WPB> __device__ __forceinline__ Span locate(const Layout &L) {
     }
     Span s;
     s.tensor = t;
-    s.rec = L.tab[t];
-    s.e0 = (uint64_t)(b - L.blk_start[t]) * kBlockElems;
+    uint32_t first_block = 0;
+    if (L.n_tensors > 1) {
+        s.rec = L.tab[t];
+        first_block = L.blk_start[t];
+    } else {
+        s.rec = L.single;                          // straight from the kernel arguments
+    }
+    s.e0 = (uint64_t)(b - first_block) * kBlockElems;
     const uint64_t rem = s.rec.numel - s.e0;
     s.cnt = rem < kBlockElems ? (uint32_t)rem : kBlockElems;
     s.full = s.cnt == kBlockElems;
@@ -194,7 +204,7 @@ __device__ __forceinline__ double wave_sum(double x) {
 // (theta -> theta).  28 B/param with fp32 gradients (16 read, 12 written).
 // ============================================================================
 template <int WPB, int OPT, int GDT>
-__global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, const void *const *__restrict__ grads, StepParams p,
+__global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, GradArg grads, StepParams p,
                                                        int src, int dst, int write_copy, double *__restrict__ partial) {
     const Span s = locate<WPB>(L);
     const uint32_t elem = threadIdx.x * kLaneElems;
@@ -203,7 +213,7 @@ __global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, const void *c
     float *dst_ptr = (dst == kSrcProbe ? s.rec.probe : s.rec.theta) + s.e0;
     const auto r_src = span_rsrc(src_ptr, bytes);
     const auto r_dst = span_rsrc(dst_ptr, bytes);
-    const auto r_g = grad_rsrc<GDT>(grads[s.tensor], s.e0, s.cnt);
+    const auto r_g = grad_rsrc<GDT>(grad_ptr(grads, L, s.tensor), s.e0, s.cnt);
 
     f32x4 th = load_f32(r_src, elem, s.full);
     f32x4 g = load_grad<GDT>(r_g, elem, s.full);
@@ -259,15 +269,15 @@ __global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, const void *c
 // 20 B/param with fp32 gradients (16 read, 4 written).
 // ============================================================================
 template <int WPB, int GDT>
-__global__ __launch_bounds__(64 * WPB) void k_extrapolate(Layout L, const void *const *__restrict__ g0s,
-                                                        const void *const *__restrict__ g1s, ExtrapParams e, int write_copy) {
+__global__ __launch_bounds__(64 * WPB) void k_extrapolate(Layout L, GradArg g0s, GradArg g1s, ExtrapParams e,
+                                                        int write_copy) {
     const Span s = locate<WPB>(L);
     const uint32_t elem = threadIdx.x * kLaneElems;
     const uint32_t bytes = s.cnt * 4u;
     const auto r_th = span_rsrc(s.rec.theta + s.e0, bytes);
     const auto r_pr = span_rsrc(s.rec.probe + s.e0, bytes);
-    const auto r_g0 = grad_rsrc<GDT>(g0s[s.tensor], s.e0, s.cnt);
-    const auto r_g1 = grad_rsrc<GDT>(g1s[s.tensor], s.e0, s.cnt);
+    const auto r_g0 = grad_rsrc<GDT>(grad_ptr(g0s, L, s.tensor), s.e0, s.cnt);
+    const auto r_g1 = grad_rsrc<GDT>(grad_ptr(g1s, L, s.tensor), s.e0, s.cnt);
     f32x4 th0 = load_f32(r_th, elem, s.full);
     f32x4 th2 = load_f32(r_pr, elem, s.full);
     f32x4 g0 = load_grad<GDT>(r_g0, elem, s.full);
@@ -293,16 +303,15 @@ __global__ __launch_bounds__(64 * WPB) void k_extrapolate(Layout L, const void *
 // instead of 28 + 20.
 // ============================================================================
 template <int WPB, int OPT, int GDT>
-__global__ __launch_bounds__(64 * WPB) void k_fused_step2_extrapolate(Layout L, const void *const *__restrict__ g0s,
-                                                                    const void *const *__restrict__ g1s, StepParams p,
+__global__ __launch_bounds__(64 * WPB) void k_fused_step2_extrapolate(Layout L, GradArg g0s, GradArg g1s, StepParams p,
                                                                     ExtrapParams e, int write_copy) {
     const Span s = locate<WPB>(L);
     const uint32_t elem = threadIdx.x * kLaneElems;
     const uint32_t bytes = s.cnt * 4u;
     const auto r_th = span_rsrc(s.rec.theta + s.e0, bytes);
     const auto r_pr = span_rsrc(s.rec.probe + s.e0, bytes);
-    const auto r_g0 = grad_rsrc<GDT>(g0s[s.tensor], s.e0, s.cnt);
-    const auto r_g1 = grad_rsrc<GDT>(g1s[s.tensor], s.e0, s.cnt);
+    const auto r_g0 = grad_rsrc<GDT>(grad_ptr(g0s, L, s.tensor), s.e0, s.cnt);
+    const auto r_g1 = grad_rsrc<GDT>(grad_ptr(g1s, L, s.tensor), s.e0, s.cnt);
     f32x4 th1 = load_f32(r_pr, elem, s.full);
     f32x4 g1 = load_grad<GDT>(r_g1, elem, s.full);
     f32x4 m = {0, 0, 0, 0}, v = {0, 0, 0, 0};
@@ -392,7 +401,7 @@ __global__ __launch_bounds__(64) void k_stream_copy(const float *__restrict__ sr
 }
 
 template <int WPB>
-hipError_t step_wpb(const Layout &L, int optimizer, int grad_dtype, const void *const *g, const StepParams &p, int src, int dst,
+hipError_t step_wpb(const Layout &L, int optimizer, int grad_dtype, const GradArg &g, const StepParams &p, int src, int dst,
                     int write_copy, double *partial, hipStream_t st) {
     const dim3 grid(L.n_blocks), block(64 * WPB);
     if (optimizer == 0 && grad_dtype == 0) k_optim_step<WPB, 0, 0><<<grid, block, 0, st>>>(L, g, p, src, dst, write_copy, partial);
@@ -403,7 +412,7 @@ hipError_t step_wpb(const Layout &L, int optimizer, int grad_dtype, const void *
 }
 
 template <int WPB>
-hipError_t extrap_wpb(const Layout &L, int grad_dtype, const void *const *g0, const void *const *g1, const ExtrapParams &e,
+hipError_t extrap_wpb(const Layout &L, int grad_dtype, const GradArg &g0, const GradArg &g1, const ExtrapParams &e,
                       int write_copy, hipStream_t st) {
     const dim3 grid(L.n_blocks), block(64 * WPB);
     if (grad_dtype == 0) k_extrapolate<WPB, 0><<<grid, block, 0, st>>>(L, g0, g1, e, write_copy);
@@ -412,7 +421,7 @@ hipError_t extrap_wpb(const Layout &L, int grad_dtype, const void *const *g0, co
 }
 
 template <int WPB>
-hipError_t fused_wpb(const Layout &L, int optimizer, int grad_dtype, const void *const *g0, const void *const *g1,
+hipError_t fused_wpb(const Layout &L, int optimizer, int grad_dtype, const GradArg &g0, const GradArg &g1,
                      const StepParams &p, const ExtrapParams &e, int write_copy, hipStream_t st) {
     const dim3 grid(L.n_blocks), block(64 * WPB);
     if (optimizer == 0 && grad_dtype == 0) k_fused_step2_extrapolate<WPB, 0, 0><<<grid, block, 0, st>>>(L, g0, g1, p, e, write_copy);
@@ -424,7 +433,7 @@ hipError_t fused_wpb(const Layout &L, int optimizer, int grad_dtype, const void 
 
 }  // namespace
 
-hipError_t launch_step(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype, const void *const *d_grads,
+hipError_t launch_step(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype, const GradArg &d_grads,
                        const StepParams &p, int src, int dst, int write_copy, double *d_partial, hipStream_t stream) {
     switch (wpb) {
         case 1: return step_wpb<1>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_copy, d_partial, stream);
@@ -434,7 +443,7 @@ hipError_t launch_step(const Layout &L, uint32_t wpb, int optimizer, int grad_dt
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_extrapolate(const Layout &L, uint32_t wpb, int grad_dtype, const void *const *d_g0, const void *const *d_g1,
+hipError_t launch_extrapolate(const Layout &L, uint32_t wpb, int grad_dtype, const GradArg &d_g0, const GradArg &d_g1,
                               const ExtrapParams &e, int write_copy, hipStream_t stream) {
     switch (wpb) {
         case 1: return extrap_wpb<1>(L, grad_dtype, d_g0, d_g1, e, write_copy, stream);
@@ -444,8 +453,8 @@ hipError_t launch_extrapolate(const Layout &L, uint32_t wpb, int grad_dtype, con
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_fused_step2_extrapolate(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype, const void *const *d_g0,
-                                          const void *const *d_g1, const StepParams &p, const ExtrapParams &e, int write_copy,
+hipError_t launch_fused_step2_extrapolate(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype, const GradArg &d_g0,
+                                          const GradArg &d_g1, const StepParams &p, const ExtrapParams &e, int write_copy,
                                           hipStream_t stream) {
     switch (wpb) {
         case 1: return fused_wpb<1>(L, optimizer, grad_dtype, d_g0, d_g1, p, e, write_copy, stream);

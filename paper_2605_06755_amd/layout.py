@@ -1,0 +1,78 @@
+"""Where the caller should put the engine's streams in HBM.
+
+Every pass of the engine reads and writes several parameter-sized arrays at the
+same element offset at the same time (theta, theta_probe, m, v and one or two
+gradient buffers).  On MI355X the achieved bandwidth of such a pass depends on
+how the base addresses of those arrays relate modulo 64 KiB: when all of them
+share one phase the memory system serves them ~7 % slower than when about half
+of the traffic sits 32 KiB out of phase with the other half (measured: 77 %
+against 83.6 % of the 8 TB/s peak for the AdamW passes; the design doc has the table).
+
+The rule used here: parameters, the probe buffer and gradients keep phase 0,
+the AdamW moments m and v are placed 32 KiB (mod 64 KiB) away from them.  The
+engine itself accepts any 16-byte aligned pointer; this module is allocation
+plumbing for callers that want the fast layout.
+"""
+from __future__ import annotations
+
+import torch
+
+PHASE_PERIOD_BYTES = 64 * 1024
+MOMENT_PHASE_BYTES = 32 * 1024
+
+
+def alloc_phased(numel: int, dtype, device, phase_bytes: int = 0, fill=None) -> torch.Tensor:
+    """A contiguous 1-D tensor of `numel` elements whose first byte sits at
+    `phase_bytes` modulo 64 KiB.  Over-allocates by at most 64 KiB."""
+    es = torch.empty((), dtype=dtype).element_size()
+    assert PHASE_PERIOD_BYTES % es == 0 and phase_bytes % es == 0
+    slack = PHASE_PERIOD_BYTES // es
+    raw = torch.empty(numel + slack, dtype=dtype, device=device)
+    shift = (phase_bytes - raw.data_ptr()) % PHASE_PERIOD_BYTES
+    out = raw[shift // es: shift // es + numel]
+    assert out.data_ptr() % PHASE_PERIOD_BYTES == phase_bytes % PHASE_PERIOD_BYTES
+    if fill is not None:
+        out.fill_(fill)
+    return out
+
+
+def alloc_engine_state(numel: int, device, *, adam: bool = True, model_copy: bool = False, grad_dtype=torch.float32,
+                       n_grad_buffers: int = 3, arena: bool = False):
+    """Flat buffers for one engine context in the fast layout: a dict with
+    theta, theta_probe, (m, v), (model_copy) and a list of gradient buffers."""
+    if arena:
+        return _alloc_arena(numel, device, adam, model_copy, grad_dtype, n_grad_buffers)
+    out = {"theta": alloc_phased(numel, torch.float32, device, 0),
+           "theta_probe": alloc_phased(numel, torch.float32, device, 0)}
+    if adam:
+        out["m"] = alloc_phased(numel, torch.float32, device, MOMENT_PHASE_BYTES, fill=0.0)
+        out["v"] = alloc_phased(numel, torch.float32, device, MOMENT_PHASE_BYTES, fill=0.0)
+    if model_copy:
+        out["model_copy"] = alloc_phased(numel, torch.bfloat16, device, 0)
+    grads = [alloc_phased(numel, grad_dtype, device, 0) for _ in range(n_grad_buffers)]
+    return out, grads
+
+
+def _alloc_arena(numel, device, adam, model_copy, grad_dtype, n_grad_buffers):
+    """Everything carved from ONE allocation at a 2 MiB-multiple pitch."""
+    two_mb = 2 << 20
+    pitch = -(-(numel * 4) // two_mb) * two_mb + two_mb
+    names = ["theta", "theta_probe"] + (["m", "v"] if adam else []) + (["model_copy"] if model_copy else [])
+    n_arr = len(names) + n_grad_buffers
+    raw = torch.empty(pitch * n_arr + two_mb, dtype=torch.uint8, device=device)
+    start = (-raw.data_ptr()) % two_mb
+    out, grads = {}, []
+    for k in range(n_arr):
+        name = names[k] if k < len(names) else None
+        phase = MOMENT_PHASE_BYTES if name in ("m", "v") else 0
+        dt = torch.float32 if name in ("theta", "theta_probe", "m", "v") else (torch.bfloat16 if name == "model_copy" else grad_dtype)
+        es = torch.empty((), dtype=dt).element_size()
+        lo = start + k * pitch + phase
+        t = raw[lo: lo + numel * es].view(dt)
+        if name in ("m", "v"):
+            t.zero_()
+        if name:
+            out[name] = t
+        else:
+            grads.append(t)
+    return out, grads

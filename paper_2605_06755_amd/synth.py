@@ -161,3 +161,50 @@ def split_like(flat: torch.Tensor, layout: List[Tuple[str, int]], align_elems: i
 
 def padded_numel(layout: List[Tuple[str, int]], align_elems: int = 4) -> int:
     return sum(-(-n // align_elems) * align_elems for _, n in layout)
+
+
+# ---------------------------------------------------------------------------
+# the same noisy quadratic for buffers too large to keep h, theta_star and the
+# noise resident: everything is regenerated chunk by chunk from counters
+# ---------------------------------------------------------------------------
+class ChunkedQuadratic:
+    """policy_problem() / surrogate-style data over a flat buffer of `numel`
+    elements, produced in chunks of `chunk` elements.  Chunk c of h,
+    theta_star, theta_0 comes from a generator seeded with (seed, c); chunk c of
+    the noise of training step t from one seeded with (seed, t, c).  Any chunk
+    can therefore be regenerated on its own, on the GPU for the engine or for a
+    slice the oracle checks."""
+
+    def __init__(self, numel: int, seed: int, sigma: float = 0.05, *, h_dist="loguniform", h_lo=1e-3, h_hi=1.0,
+                 theta_std=0.02, chunk: int = 1 << 27, device="cuda"):
+        self.numel, self.seed, self.sigma, self.chunk, self.device = numel, seed, sigma, chunk, device
+        self.h_dist, self.h_lo, self.h_hi, self.theta_std = h_dist, h_lo, h_hi, theta_std
+
+    def n_chunks(self) -> int:
+        return -(-self.numel // self.chunk)
+
+    def chunk_range(self, c: int) -> Tuple[int, int]:
+        lo = c * self.chunk
+        return lo, min(self.numel, lo + self.chunk)
+
+    def chunk_problem(self, c: int) -> QuadraticProblem:
+        lo, hi = self.chunk_range(c)
+        return make_quadratic(hi - lo, self.seed * 7919 + 104729 * c + 1, h_dist=self.h_dist, h_lo=self.h_lo,
+                              h_hi=self.h_hi, theta_std=self.theta_std, sigma=self.sigma, device=self.device)
+
+    def chunk_noise(self, step: int, c: int) -> torch.Tensor:
+        lo, hi = self.chunk_range(c)
+        gen = _gen(self.device, (self.seed + 1) * 1_000_003 + step * 15_485_863 + c)
+        return torch.randn(hi - lo, generator=gen, device=self.device, dtype=torch.float32)
+
+    def init_theta(self, out: torch.Tensor) -> None:
+        for c in range(self.n_chunks()):
+            lo, hi = self.chunk_range(c)
+            out[lo:hi].copy_(self.chunk_problem(c).theta_0)
+
+    def grad(self, theta: torch.Tensor, step: int, out: torch.Tensor, sigma: float | None = None) -> None:
+        """out <- h * (theta - theta_star) + sigma * xi_step, rounded to out.dtype."""
+        for c in range(self.n_chunks()):
+            lo, hi = self.chunk_range(c)
+            p = self.chunk_problem(c)
+            out[lo:hi].copy_(quadratic_grad(p, theta[lo:hi], self.chunk_noise(step, c), sigma, out_dtype=out.dtype))
