@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--unfused", action="store_true", help="run the second fast step and the extrapolation as two passes")
     ap.add_argument("--same-phase", action="store_true", help="plain torch allocations instead of the phased HBM layout")
     ap.add_argument("--arena", action="store_true", help="carve all buffers from one allocation")
+    ap.add_argument("--no-probe", action="store_true",
+                    help="workloads with a bf16 model copy: deliver theta^{t,1} through the copy only (no fp32 theta_probe)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1 << 26, help="elements of the workload the oracle is timed on")
     return ap.parse_args()
@@ -74,10 +76,14 @@ def bytes_per_param(spec, fused: bool):
     mv = 8 if spec["optimizer"] == "adamw" else 0          # m and v, read; the same again written
     c = 2 if spec["copy"] else 0
     step = 4 + mv + g + 4 + mv                                # theta, m, v, g in; theta, m, v out
-    out = {"fast_step_1": step + c, "slow_step": step + c, "fallback_step": step + c}
+    out = {"slow_step": step + c, "fallback_step": step + c}
     if fused:
-        out["fused_step2_extrapolate"] = 4 + mv + g + g + 4 + 4 + mv + c       # theta1,m,v,g1,g0,theta0 in; theta~,m,v out
+        # probe pass: theta, m, v, g0 in; theta^{t,1} out (fp32 unless only the bf16 copy is wanted)
+        out["fast_step_1"] = 4 + mv + g + (0 if spec.get("no_probe") else 4) + c
+        # fused pass: theta, m, v, g0, g1 in; theta~, m, v out
+        out["fused_steps_extrapolate"] = 4 + mv + g + g + 4 + mv + c
     else:
+        out["fast_step_1"] = step + c
         out["fast_step_2"] = step
         out["extrapolate"] = 4 + 4 + g + g + 4 + c
     return out
@@ -102,6 +108,11 @@ def main():
     torch.cuda.set_device(dev)
     spec = workload_spec(args.workload)
     fused = not args.unfused
+    if args.no_probe:
+        if not (spec["copy"] and fused):
+            print("bench.py: --no-probe needs a workload with a bf16 model copy and the fused schedule", file=sys.stderr)
+            sys.exit(2)
+        spec["no_probe"] = True
     layout = spec["layout"]
     numels = [n for _, n in layout]
     P = sum(numels)
@@ -125,7 +136,8 @@ def main():
     print("base addresses:", {k: hex(v.data_ptr()) for k, v in flat.items()}, [hex(g.data_ptr()) for g in gflat], file=sys.stderr)
     views = {k: synth.split_like(v, layout, 4) for k, v in flat.items()}
     g0, g1, gs = (synth.split_like(g, layout, 4) for g in gflat)
-    tensors = [{k: views[k][i] for k in views} for i in range(len(numels))]
+    tensors = [{k: views[k][i] for k in views if not (spec.get("no_probe") and k == "theta_probe")}
+               for i in range(len(numels))]
 
     if spec.get("surrogate"):
         quad = synth.ChunkedQuadratic(padded, spec["seed"], 0.0, h_dist="uniform", h_lo=0.1, h_hi=1.0, theta_std=1.0, device=dev)
@@ -141,7 +153,7 @@ def main():
     S = min(args.cpu_sample, numels[0])
     quad.grad(flat["theta"], 0, gflat[0])
     B.gxpo_fast_steps(ctx, 0, g0)
-    quad.grad(flat["theta_probe"], 0, gflat[1])
+    quad.grad(flat["model_copy"].float() if spec.get("no_probe") else flat["theta_probe"], 0, gflat[1])
     B.gxpo_fast_steps(ctx, 1, g1)
     B.gxpo_extrapolate(ctx, g0, g1)
     quad.grad(flat["theta"], 0, gflat[2])
@@ -151,7 +163,7 @@ def main():
     def active_step(events=None):
         calls = (("fast_step_1", lambda: B.gxpo_fast_steps(ctx, 0, g0)),
                  ("fast_step_2", lambda: B.gxpo_fast_steps(ctx, 1, g1)),
-                 ("fused_step2_extrapolate" if fused else "extrapolate", lambda: B.gxpo_extrapolate(ctx, g0, g1)),
+                 ("fused_steps_extrapolate" if fused else "extrapolate", lambda: B.gxpo_extrapolate(ctx, g0, g1)),
                  ("slow_step", lambda: B.gxpo_slow_step(ctx, gs)))
         for name, fn in calls:
             if events is None or (fused and name == "fast_step_2"):

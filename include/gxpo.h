@@ -19,8 +19,8 @@
  *     g0 = grad L(theta)                       caller, backward pass 1
  *     gxpo_fast_steps(ctx, 0, g0, stream)      theta_probe <- OptimStep(theta, g0)
  *     g1 = grad L(theta_probe)                 caller, backward pass 2
- *     gxpo_fast_steps(ctx, 1, g1, stream)      theta_probe <- OptimStep(theta_probe, g1)
- *     gxpo_extrapolate(ctx, g0, g1, stream)    theta <- theta + alpha*scale*(theta_probe - theta)
+ *     gxpo_fast_steps(ctx, 1, g1, stream)      theta^{t,2} <- OptimStep(theta_probe, g1)
+ *     gxpo_extrapolate(ctx, g0, g1, stream)    theta <- theta + alpha*scale*(theta^{t,2} - theta)
  *     gs = grad L(theta)                       caller, backward pass 3 (theta is now theta~)
  *     gxpo_slow_step(ctx, gs, stream)          theta <- OptimStep(theta, gs);  sum gs^2
  *     gxpo_gate(ctx, &info, stream)            z-score test, may set s* = t + 1;  t <- t + 1
@@ -90,11 +90,16 @@ typedef struct gxpo_tensor {
     uint64_t numel;
     float *theta;        /* fp32 master weights.  Holds theta^t when a step starts, theta~^t after
                             gxpo_extrapolate, theta^{t+1} after gxpo_slow_step / gxpo_fallback_step. */
-    float *theta_probe;  /* fp32 scratch of the same size: theta^{t,1} after gxpo_fast_steps(0),
-                            theta^{t,2} after gxpo_fast_steps(1) when fuse_step2 == 0.  Contents
-                            are undefined between training steps.  May be NULL only if the context
-                            is never used in the active phase (see gxpo_set_state). */
-    float *m, *v;        /* AdamW first / second moment, fp32.  Must be NULL for GXPO_OPT_GD. */
+    float *theta_probe;  /* fp32 buffer of the same size, written for the trainer: theta^{t,1} after
+                            gxpo_fast_steps(0); also theta^{t,2} after gxpo_fast_steps(1) when
+                            fuse_step2 == 0.  With fuse_step2 the engine never reads it back.
+                            Contents are undefined between training steps.  May be NULL if the
+                            context only ever runs fallback steps, or if fuse_step2 is set and
+                            theta^{t,1} is delivered through model_copy (GXPO_COPY_AT_PROBE). */
+    float *m, *v;        /* AdamW first / second moment, fp32.  Must be NULL for GXPO_OPT_GD.
+                            Valid for the caller to read only between training steps: with
+                            fuse_step2 both fast steps' moment updates are applied together by
+                            gxpo_extrapolate (the first fast step is previewed, then replayed). */
     void  *model_copy;   /* optional bf16 [numel] copy the trainer's forward/backward reads; NULL = none */
 } gxpo_tensor;
 
@@ -106,9 +111,12 @@ typedef struct gxpo_config {
     uint32_t optimizer;       /* GXPO_OPT_*   : OptimStep of Algorithm 1 */
     uint32_t grad_dtype;      /* GXPO_GRAD_*  : element type of every gradient buffer */
     uint32_t K;               /* virtual lookahead depth, >= 2 (K = 2 makes scale == 1) */
-    uint32_t fuse_step2;      /* 1: gxpo_fast_steps(1) only records g1 and gxpo_extrapolate runs the
-                                 second fast step and the extrapolation as one pass (theta^{t,2} is
-                                 never stored).  0: each call runs its own pass. */
+    uint32_t fuse_step2;      /* 1: gxpo_fast_steps(0) writes theta^{t,1} but leaves m, v alone,
+                                 gxpo_fast_steps(1) only records g1, and gxpo_extrapolate replays
+                                 the first fast step, takes the second and extrapolates in one pass
+                                 (theta^{t,2} is never stored; the replay repeats the probe pass's
+                                 fp32 operations, so theta^{t,1}, m, v are bit for bit what storing
+                                 them would have given).  0: each call runs its own pass. */
     uint32_t copy_mask;       /* GXPO_COPY_AT_* bits; ignored for tensors without model_copy */
     uint32_t window;          /* w: number of past norms the gate statistics use, 2..GXPO_MAX_WINDOW */
     uint32_t gate_min_count;  /* gate is evaluated once the buffer holds this many norms; 0 = window */
@@ -164,7 +172,8 @@ void gxpo_destroy(gxpo_ctx *ctx);
  * The optimizer state (m, v, step counter) advances on both and is not rolled
  * back later (Section 2.3, paragraph after Eq. (9)).  theta is left untouched.
  * The gradients of which == 0 must stay unmodified until gxpo_extrapolate has
- * executed; with fuse_step2 the same holds for the gradients of which == 1. */
+ * executed; with fuse_step2 the same holds for the gradients of which == 1, and
+ * gxpo_extrapolate must be given the same two gradient lists. */
 int gxpo_fast_steps(gxpo_ctx *ctx, int which, const void *const *grads, void *stream);
 
 /* Active set, retention ratio r = g1/g0, scale = S_K(r)/S_2(r) (1 off the

@@ -62,8 +62,10 @@ struct gxpo_ctx {
     bool stage_used[kStageSlots]{};
     int next_slot = 0;
     std::vector<const void *> shadow[kGradRoles];
+    std::vector<const void *> pending_g0;    // fuse_step2: the gradients the probe pass used
     std::vector<const void *> pending_g1;    // fuse_step2: recorded by gxpo_fast_steps(1)
-    int64_t pending_step2 = 0;               // optimizer step number of the deferred second fast step
+    int64_t pending_step1 = 0;               // optimizer step numbers of the two fast steps the
+    int64_t pending_step2 = 0;               //   fused pass applies
 
     gxpo_state st{};
     mutable std::string err;
@@ -458,22 +460,34 @@ int gxpo_fast_steps(gxpo_ctx *ctx, int which, const void *const *grads, void *st
     if (is_fallback_phase(st)) return fail(ctx, GXPO_ERR_BAD_STATE, "gxpo_fast_steps: the gate has tripped (s* = %lld), use gxpo_fallback_step", (long long)st.s_star);
     const uint32_t want = which == 0 ? GXPO_PHASE_IDLE : GXPO_PHASE_FAST1;
     if (st.phase != want) return fail(ctx, GXPO_ERR_BAD_STATE, "gxpo_fast_steps(%d) called in phase %u", which, st.phase);
-    for (uint32_t t = 0; t < ctx->n; ++t)
-        if (!ctx->tensors[t].theta_probe) return fail(ctx, GXPO_ERR_INVALID_ARG, "tensor %u has no theta_probe: active phase unavailable", t);
+    const bool fused = ctx->cfg.fuse_step2 != 0;
+    const bool copy_at_probe = (ctx->cfg.copy_mask & GXPO_COPY_AT_PROBE) != 0;
+    for (uint32_t t = 0; t < ctx->n; ++t) {
+        const gxpo_tensor &x = ctx->tensors[t];
+        if (!x.theta_probe && !(fused && copy_at_probe && x.model_copy))
+            return fail(ctx, GXPO_ERR_INVALID_ARG,
+                        "tensor %u has no theta_probe: the active phase needs it unless fuse_step2 is set and theta^{t,1} goes to model_copy", t);
+    }
     hipStream_t s = (hipStream_t)stream;
     GradArg d_g{};
     rc = stage_grads(ctx, which == 0 ? kRoleG0 : kRoleG1, grads, s, &d_g);
     if (rc != GXPO_OK) return rc;
     const int64_t step_no = st.optim_steps + 1;
-    if (which == 1 && ctx->cfg.fuse_step2) {
+    if (which == 1 && fused) {
         ctx->pending_g1.assign(grads, grads + ctx->n);
         ctx->pending_step2 = step_no;
     } else {
         const StepParams p = make_step_params(ctx->cfg, step_no);
         const int src = which == 0 ? kSrcTheta : kSrcProbe;
-        const int wc = which == 0 ? ((ctx->cfg.copy_mask & GXPO_COPY_AT_PROBE) ? 1 : 0) : 0;
-        GXPO_HIP(ctx, launch_step(ctx->layout(), ctx->wpb, (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, src, kSrcProbe, wc,
-                                  nullptr, s));
+        const int wc = (which == 0 && copy_at_probe) ? 1 : 0;
+        // fused schedule: the probe pass only previews the step, the moments are advanced by gxpo_extrapolate
+        const int write_moments = fused ? 0 : 1;
+        GXPO_HIP(ctx, launch_step(ctx->layout(), ctx->wpb, (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, src, kSrcProbe,
+                                  write_moments, wc, nullptr, s));
+        if (fused) {
+            ctx->pending_g0.assign(grads, grads + ctx->n);
+            ctx->pending_step1 = step_no;
+        }
     }
     st.optim_steps = step_no;
     st.backward_passes += 1;
@@ -489,9 +503,12 @@ int gxpo_extrapolate(gxpo_ctx *ctx, const void *const *g0, const void *const *g1
     if (st.phase != GXPO_PHASE_FAST2) return fail(ctx, GXPO_ERR_BAD_STATE, "gxpo_extrapolate called in phase %u", st.phase);
     hipStream_t s = (hipStream_t)stream;
     if (ctx->cfg.fuse_step2)
-        for (uint32_t t = 0; t < ctx->n; ++t)
+        for (uint32_t t = 0; t < ctx->n; ++t) {
+            if (g0[t] != ctx->pending_g0[t])
+                return fail(ctx, GXPO_ERR_INVALID_ARG, "gxpo_extrapolate: g0 of tensor %u differs from the one given to gxpo_fast_steps(0)", t);
             if (g1[t] != ctx->pending_g1[t])
                 return fail(ctx, GXPO_ERR_INVALID_ARG, "gxpo_extrapolate: g1 of tensor %u differs from the one given to gxpo_fast_steps(1)", t);
+        }
     GradArg d_g0{}, d_g1{};
     rc = stage_grads(ctx, kRoleG0, g0, s, &d_g0);
     if (rc == GXPO_OK) rc = stage_grads(ctx, kRoleG1, g1, s, &d_g1);
@@ -499,9 +516,10 @@ int gxpo_extrapolate(gxpo_ctx *ctx, const void *const *g0, const void *const *g1
     const ExtrapParams e = make_extrap_params(ctx->cfg);
     const int wc = (ctx->cfg.copy_mask & GXPO_COPY_AT_TILDE) ? 1 : 0;
     if (ctx->cfg.fuse_step2) {
-        const StepParams p = make_step_params(ctx->cfg, ctx->pending_step2);
-        GXPO_HIP(ctx, launch_fused_step2_extrapolate(ctx->layout(), ctx->wpb, (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g0, d_g1,
-                                                     p, e, wc, s));
+        const StepParams p1 = make_step_params(ctx->cfg, ctx->pending_step1);
+        const StepParams p2 = make_step_params(ctx->cfg, ctx->pending_step2);
+        GXPO_HIP(ctx, launch_fused_steps_extrapolate(ctx->layout(), ctx->wpb, (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g0, d_g1,
+                                                     p1, p2, e, wc, s));
     } else {
         GXPO_HIP(ctx, launch_extrapolate(ctx->layout(), ctx->wpb, (int)ctx->cfg.grad_dtype, d_g0, d_g1, e, wc, s));
     }
@@ -521,7 +539,7 @@ int gxpo_slow_step(gxpo_ctx *ctx, const void *const *g_slow, void *stream) {
     const int64_t step_no = st.optim_steps + 1;
     const StepParams p = make_step_params(ctx->cfg, step_no);
     const int wc = (ctx->cfg.copy_mask & GXPO_COPY_AT_FINAL) ? 1 : 0;
-    GXPO_HIP(ctx, launch_step(ctx->layout(), ctx->wpb, (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, kSrcTheta, kSrcTheta, wc,
+    GXPO_HIP(ctx, launch_step(ctx->layout(), ctx->wpb, (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, kSrcTheta, kSrcTheta, 1, wc,
                               ctx->d_partial, s));
     GXPO_HIP(ctx, launch_finalize(ctx->d_partial, ctx->d_seg, ctx->n_segs, ctx->d_tensor_seg_start, ctx->n, ctx->d_seg_sum,
                                   ctx->d_result, s));
@@ -564,7 +582,7 @@ int gxpo_fallback_step(gxpo_ctx *ctx, const void *const *g0, void *stream) {
     const int64_t step_no = st.optim_steps + 1;
     const StepParams p = make_step_params(ctx->cfg, step_no);
     const int wc = (ctx->cfg.copy_mask & GXPO_COPY_AT_FINAL) ? 1 : 0;
-    GXPO_HIP(ctx, launch_step(ctx->layout(), ctx->wpb, (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, kSrcTheta, kSrcTheta, wc,
+    GXPO_HIP(ctx, launch_step(ctx->layout(), ctx->wpb, (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, kSrcTheta, kSrcTheta, 1, wc,
                               nullptr, s));
     st.optim_steps = step_no;
     st.backward_passes += 1;

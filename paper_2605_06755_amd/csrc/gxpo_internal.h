@@ -72,15 +72,16 @@ enum { kSrcTheta = 0, kSrcProbe = 1 };
 // All launchers enqueue on `stream` and return the launch status.
 hipError_t launch_step(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype,
                        const GradArg &d_grads, const StepParams &p,
-                       int src, int dst, int write_copy, double *d_partial, hipStream_t stream);
+                       int src, int dst, int write_moments, int write_copy, double *d_partial, hipStream_t stream);
 
 hipError_t launch_extrapolate(const Layout &L, uint32_t wpb, int grad_dtype,
                               const GradArg &d_g0, const GradArg &d_g1,
                               const ExtrapParams &e, int write_copy, hipStream_t stream);
 
-hipError_t launch_fused_step2_extrapolate(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype,
+// p1 / p2: constants of the first / second fast step (both are applied here).
+hipError_t launch_fused_steps_extrapolate(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype,
                                           const GradArg &d_g0, const GradArg &d_g1,
-                                          const StepParams &p, const ExtrapParams &e,
+                                          const StepParams &p1, const StepParams &p2, const ExtrapParams &e,
                                           int write_copy, hipStream_t stream);
 
 // result[0] = sum over all tensors, result[1 + t] = sum over tensor t.

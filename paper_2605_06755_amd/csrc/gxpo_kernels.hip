@@ -202,17 +202,21 @@ __device__ __forceinline__ double wave_sum(double x) {
 // OptimStep pass: fast step 1 (theta -> probe), unfused fast step 2
 // (probe -> probe), slow step (theta -> theta, + sum of squares), fallback step
 // (theta -> theta).  28 B/param with fp32 gradients (16 read, 12 written).
+//
+// As the probe of the fused schedule (write_moments == 0) it only previews the
+// step: theta^{t,1} is written for the trainer, the advanced moments are
+// dropped because the fused pass recomputes them from the same inputs
+// (20 B/param: 16 read, 4 written; 18 when only the bf16 copy is written).
 // ============================================================================
 template <int WPB, int OPT, int GDT>
-__global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, GradArg grads, StepParams p,
-                                                       int src, int dst, int write_copy, double *__restrict__ partial) {
+__global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, GradArg grads, StepParams p, int src, int dst,
+                                                       int write_moments, int write_copy, double *__restrict__ partial) {
     const Span s = locate<WPB>(L);
     const uint32_t elem = threadIdx.x * kLaneElems;
     const uint32_t bytes = s.cnt * 4u;
     const float *src_ptr = (src == kSrcProbe ? s.rec.probe : s.rec.theta) + s.e0;
-    float *dst_ptr = (dst == kSrcProbe ? s.rec.probe : s.rec.theta) + s.e0;
+    float *dst_base = dst == kSrcProbe ? s.rec.probe : s.rec.theta;      // a NULL probe: nobody wants fp32 theta^{t,1}
     const auto r_src = span_rsrc(src_ptr, bytes);
-    const auto r_dst = span_rsrc(dst_ptr, bytes);
     const auto r_g = grad_rsrc<GDT>(grad_ptr(grads, L, s.tensor), s.e0, s.cnt);
 
     f32x4 th = load_f32(r_src, elem, s.full);
@@ -232,8 +236,8 @@ __global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, GradArg grads
         m[k] = mk;
         v[k] = vk;
     }
-    store_f32(r_dst, elem, s.full, th);
-    if (OPT == 1) {
+    if (dst_base) store_f32(span_rsrc(dst_base + s.e0, bytes), elem, s.full, th);
+    if (OPT == 1 && write_moments) {
         store_f32(r_m, elem, s.full, m);
         store_f32(r_v, elem, s.full, v);
     }
@@ -295,25 +299,31 @@ __global__ __launch_bounds__(64 * WPB) void k_extrapolate(Layout L, GradArg g0s,
 }
 
 // ============================================================================
-// Fused: second fast step + extrapolate + reposition.  theta^{t,2} lives only
-// in registers; the two-step displacement is formed as
-//     (theta^{t,1} - theta^t) - update_2
-// i.e. from the exact difference of the two stored iterates, not from a
-// rounded theta^{t,2}.  36 B/param with fp32 gradients (24 read, 12 written)
-// instead of 28 + 20.
+// Fused: both fast steps' state update + extrapolate + reposition.
+//
+// The first fast step was only previewed by the probe pass (theta^{t,1} went
+// to the trainer, nothing else was stored).  This pass replays it from the
+// same inputs (theta^t, m, v, g0 and the step-1 constants give bit-identical
+// theta^{t,1}, m, v, because the same fp32 operations run in the same order),
+// takes the second fast step on top, and extrapolates.  theta^{t,1},
+// theta^{t,2}, r and scale live only in registers; the two-step displacement
+// is formed as (theta^{t,1} - theta^t) - update_2, i.e. from the exact
+// difference of two fp32 iterates, not from a rounded theta^{t,2}.
+// Recomputing costs ALU time the pass does not have to wait for; it saves the
+// write and re-read of m, v (16 B) and the re-read of theta^{t,1} (4 B):
+// 32 B/param with fp32 gradients (20 read, 12 written).
 // ============================================================================
 template <int WPB, int OPT, int GDT>
-__global__ __launch_bounds__(64 * WPB) void k_fused_step2_extrapolate(Layout L, GradArg g0s, GradArg g1s, StepParams p,
-                                                                    ExtrapParams e, int write_copy) {
+__global__ __launch_bounds__(64 * WPB) void k_fused_steps_extrapolate(Layout L, GradArg g0s, GradArg g1s, StepParams p1,
+                                                                    StepParams p2, ExtrapParams e, int write_copy) {
     const Span s = locate<WPB>(L);
     const uint32_t elem = threadIdx.x * kLaneElems;
     const uint32_t bytes = s.cnt * 4u;
     const auto r_th = span_rsrc(s.rec.theta + s.e0, bytes);
-    const auto r_pr = span_rsrc(s.rec.probe + s.e0, bytes);
     const auto r_g0 = grad_rsrc<GDT>(grad_ptr(g0s, L, s.tensor), s.e0, s.cnt);
     const auto r_g1 = grad_rsrc<GDT>(grad_ptr(g1s, L, s.tensor), s.e0, s.cnt);
-    f32x4 th1 = load_f32(r_pr, elem, s.full);
-    f32x4 g1 = load_grad<GDT>(r_g1, elem, s.full);
+    f32x4 th0 = load_f32(r_th, elem, s.full);
+    f32x4 g0 = load_grad<GDT>(r_g0, elem, s.full);
     f32x4 m = {0, 0, 0, 0}, v = {0, 0, 0, 0};
     __amdgpu_buffer_rsrc_t r_m, r_v;
     if (OPT == 1) {
@@ -322,15 +332,15 @@ __global__ __launch_bounds__(64 * WPB) void k_fused_step2_extrapolate(Layout L, 
         m = load_f32(r_m, elem, s.full);
         v = load_f32(r_v, elem, s.full);
     }
-    f32x4 th0 = load_f32(r_th, elem, s.full);
-    f32x4 g0 = load_grad<GDT>(r_g0, elem, s.full);
+    f32x4 g1 = load_grad<GDT>(r_g1, elem, s.full);
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         float mk = m[k], vk = v[k];
-        const float upd2 = optim_update<OPT>(th1[k], mk, vk, g1[k], p);
+        const float th1 = th0[k] - optim_update<OPT>(th0[k], mk, vk, g0[k], p1);    // theta^{t,1}, as the probe pass stored it
+        const float upd2 = optim_update<OPT>(th1, mk, vk, g1[k], p2);
         m[k] = mk;
         v[k] = vk;
-        const float disp2 = (th1[k] - th0[k]) - upd2;            // theta^{t,2} - theta^t
+        const float disp2 = (th1 - th0[k]) - upd2;                // theta^{t,2} - theta^t
         const float scale = extrap_scale(g0[k], g1[k], e);
         th0[k] = fmaf(e.alpha * scale, disp2, th0[k]);
     }
@@ -402,12 +412,12 @@ __global__ __launch_bounds__(64) void k_stream_copy(const float *__restrict__ sr
 
 template <int WPB>
 hipError_t step_wpb(const Layout &L, int optimizer, int grad_dtype, const GradArg &g, const StepParams &p, int src, int dst,
-                    int write_copy, double *partial, hipStream_t st) {
+                    int write_moments, int write_copy, double *partial, hipStream_t st) {
     const dim3 grid(L.n_blocks), block(64 * WPB);
-    if (optimizer == 0 && grad_dtype == 0) k_optim_step<WPB, 0, 0><<<grid, block, 0, st>>>(L, g, p, src, dst, write_copy, partial);
-    else if (optimizer == 0) k_optim_step<WPB, 0, 1><<<grid, block, 0, st>>>(L, g, p, src, dst, write_copy, partial);
-    else if (grad_dtype == 0) k_optim_step<WPB, 1, 0><<<grid, block, 0, st>>>(L, g, p, src, dst, write_copy, partial);
-    else k_optim_step<WPB, 1, 1><<<grid, block, 0, st>>>(L, g, p, src, dst, write_copy, partial);
+    if (optimizer == 0 && grad_dtype == 0) k_optim_step<WPB, 0, 0><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial);
+    else if (optimizer == 0) k_optim_step<WPB, 0, 1><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial);
+    else if (grad_dtype == 0) k_optim_step<WPB, 1, 0><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial);
+    else k_optim_step<WPB, 1, 1><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial);
     return hipGetLastError();
 }
 
@@ -422,23 +432,24 @@ hipError_t extrap_wpb(const Layout &L, int grad_dtype, const GradArg &g0, const 
 
 template <int WPB>
 hipError_t fused_wpb(const Layout &L, int optimizer, int grad_dtype, const GradArg &g0, const GradArg &g1,
-                     const StepParams &p, const ExtrapParams &e, int write_copy, hipStream_t st) {
+                     const StepParams &p1, const StepParams &p2, const ExtrapParams &e, int write_copy, hipStream_t st) {
     const dim3 grid(L.n_blocks), block(64 * WPB);
-    if (optimizer == 0 && grad_dtype == 0) k_fused_step2_extrapolate<WPB, 0, 0><<<grid, block, 0, st>>>(L, g0, g1, p, e, write_copy);
-    else if (optimizer == 0) k_fused_step2_extrapolate<WPB, 0, 1><<<grid, block, 0, st>>>(L, g0, g1, p, e, write_copy);
-    else if (grad_dtype == 0) k_fused_step2_extrapolate<WPB, 1, 0><<<grid, block, 0, st>>>(L, g0, g1, p, e, write_copy);
-    else k_fused_step2_extrapolate<WPB, 1, 1><<<grid, block, 0, st>>>(L, g0, g1, p, e, write_copy);
+    if (optimizer == 0 && grad_dtype == 0) k_fused_steps_extrapolate<WPB, 0, 0><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy);
+    else if (optimizer == 0) k_fused_steps_extrapolate<WPB, 0, 1><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy);
+    else if (grad_dtype == 0) k_fused_steps_extrapolate<WPB, 1, 0><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy);
+    else k_fused_steps_extrapolate<WPB, 1, 1><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy);
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_step(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype, const GradArg &d_grads,
-                       const StepParams &p, int src, int dst, int write_copy, double *d_partial, hipStream_t stream) {
+                       const StepParams &p, int src, int dst, int write_moments, int write_copy, double *d_partial,
+                       hipStream_t stream) {
     switch (wpb) {
-        case 1: return step_wpb<1>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_copy, d_partial, stream);
-        case 2: return step_wpb<2>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_copy, d_partial, stream);
-        case 4: return step_wpb<4>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_copy, d_partial, stream);
+        case 1: return step_wpb<1>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_moments, write_copy, d_partial, stream);
+        case 2: return step_wpb<2>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_moments, write_copy, d_partial, stream);
+        case 4: return step_wpb<4>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_moments, write_copy, d_partial, stream);
     }
     return hipErrorInvalidValue;
 }
@@ -453,13 +464,13 @@ hipError_t launch_extrapolate(const Layout &L, uint32_t wpb, int grad_dtype, con
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_fused_step2_extrapolate(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype, const GradArg &d_g0,
-                                          const GradArg &d_g1, const StepParams &p, const ExtrapParams &e, int write_copy,
-                                          hipStream_t stream) {
+hipError_t launch_fused_steps_extrapolate(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype, const GradArg &d_g0,
+                                          const GradArg &d_g1, const StepParams &p1, const StepParams &p2,
+                                          const ExtrapParams &e, int write_copy, hipStream_t stream) {
     switch (wpb) {
-        case 1: return fused_wpb<1>(L, optimizer, grad_dtype, d_g0, d_g1, p, e, write_copy, stream);
-        case 2: return fused_wpb<2>(L, optimizer, grad_dtype, d_g0, d_g1, p, e, write_copy, stream);
-        case 4: return fused_wpb<4>(L, optimizer, grad_dtype, d_g0, d_g1, p, e, write_copy, stream);
+        case 1: return fused_wpb<1>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, stream);
+        case 2: return fused_wpb<2>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, stream);
+        case 4: return fused_wpb<4>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, stream);
     }
     return hipErrorInvalidValue;
 }
