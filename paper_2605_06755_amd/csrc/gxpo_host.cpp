@@ -428,7 +428,7 @@ int gxpo_init(gxpo_ctx **out, const gxpo_config *cfg, const gxpo_tensor *tensors
     if (rc == GXPO_OK) rc = dev_alloc(ctx, &ctx->d_blk_start, (size_t)n_tensors + 1);
     if (rc == GXPO_OK) rc = dev_alloc(ctx, &ctx->d_coarse, coarse.size());
     if (rc == GXPO_OK) rc = dev_alloc(ctx, &ctx->d_grads, (size_t)kGradRoles * n_tensors);
-    if (rc == GXPO_OK) rc = dev_alloc(ctx, &ctx->d_partial, ctx->n_blocks);
+    if (rc == GXPO_OK) rc = dev_alloc(ctx, &ctx->d_partial, (size_t)8 * partial_stride(ctx->n_blocks));
     if (rc == GXPO_OK) rc = dev_alloc(ctx, &ctx->d_seg, segs.size());
     if (rc == GXPO_OK) rc = dev_alloc(ctx, &ctx->d_tensor_seg_start, (size_t)n_tensors + 1);
     if (rc == GXPO_OK) rc = dev_alloc(ctx, &ctx->d_seg_sum, segs.size());
@@ -541,8 +541,8 @@ int gxpo_slow_step(gxpo_ctx *ctx, const void *const *g_slow, void *stream) {
     const int wc = (ctx->cfg.copy_mask & GXPO_COPY_AT_FINAL) ? 1 : 0;
     GXPO_HIP(ctx, launch_step(ctx->layout(), ctx->wpb, (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, kSrcTheta, kSrcTheta, 1, wc,
                               ctx->d_partial, s));
-    GXPO_HIP(ctx, launch_finalize(ctx->d_partial, ctx->d_seg, ctx->n_segs, ctx->d_tensor_seg_start, ctx->n, ctx->d_seg_sum,
-                                  ctx->d_result, s));
+    GXPO_HIP(ctx, launch_finalize(ctx->d_partial, ctx->n_blocks, ctx->d_seg, ctx->n_segs, ctx->d_tensor_seg_start, ctx->n,
+                                  ctx->d_seg_sum, ctx->d_result, s));
     ctx->have_norms = true;
     st.optim_steps = step_no;
     st.backward_passes += 1;

@@ -36,6 +36,13 @@ struct Layout {
     TensorRec single;       // copy of tab[0]; used instead of the tables when n_tensors == 1
 };
 
+// Per-block partial sums are stored XCD-major: blocks are handed to the 8 XCDs
+// round-robin, so block b's partial goes to slot (b % 8) * stride + b / 8 and
+// each XCD's L2 sees its own partials as one dense, growing run of doubles
+// (full-line write-backs instead of eight XCDs each writing 8 bytes of a line).
+__host__ __device__ inline uint32_t partial_stride(uint32_t n_blocks) { return (n_blocks + 7u) >> 3; }
+__host__ __device__ inline uint32_t partial_slot(uint32_t block, uint32_t stride) { return (block & 7u) * stride + (block >> 3); }
+
 // One gradient list as a kernel argument: the device pointer table, plus the
 // pointer itself when there is a single tensor (saves a dependent load).
 struct GradArg {
@@ -85,7 +92,7 @@ hipError_t launch_fused_steps_extrapolate(const Layout &L, uint32_t wpb, int opt
                                           int write_copy, hipStream_t stream);
 
 // result[0] = sum over all tensors, result[1 + t] = sum over tensor t.
-hipError_t launch_finalize(const double *d_partial, const SegRec *d_seg, uint32_t n_segs,
+hipError_t launch_finalize(const double *d_partial, uint32_t n_blocks, const SegRec *d_seg, uint32_t n_segs,
                            const uint32_t *d_tensor_seg_start, uint32_t n_tensors,
                            double *d_seg_sum, double *d_result, hipStream_t stream);
 

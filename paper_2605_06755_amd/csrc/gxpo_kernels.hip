@@ -251,8 +251,9 @@ __global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, GradArg grads
 #pragma unroll
         for (int k = 0; k < 4; ++k) acc = fma((double)g[k], (double)g[k], acc);
         acc = wave_sum(acc);
+        const uint32_t slot = partial_slot(blockIdx.x, partial_stride(L.n_blocks));
         if (WPB == 1) {
-            if (threadIdx.x == 0) partial[blockIdx.x] = acc;
+            if (threadIdx.x == 0) partial[slot] = acc;
         } else {
             __shared__ double wave_part[WPB];
             if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = acc;
@@ -261,7 +262,7 @@ __global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, GradArg grads
                 double total = 0.0;
 #pragma unroll
                 for (int w = 0; w < WPB; ++w) total += wave_part[w];
-                partial[blockIdx.x] = total;
+                partial[slot] = total;
             }
         }
     }
@@ -358,16 +359,17 @@ __global__ __launch_bounds__(64 * WPB) void k_fused_steps_extrapolate(Layout L, 
 // ============================================================================
 // Fixed-order reduction of the per-block partial sums.
 // Stage 1: one block per run of <= kSegPartials partials of one tensor.
-// Stage 2: one block; thread t adds the run sums of tensor t in order, thread 0
-// then adds the tensor sums in index order.
+// Stage 2: one block; a wavefront adds the run sums of a tensor (lane-strided,
+// then a butterfly), wavefront 0 then adds the tensor sums the same way.  The
+// order of every addition is fixed by the shapes alone.
 // ============================================================================
 constexpr int kFinalThreads = 256;
 
-__global__ __launch_bounds__(kFinalThreads) void k_reduce_runs(const double *__restrict__ partial, const SegRec *__restrict__ seg,
-                                                             double *__restrict__ seg_sum) {
+__global__ __launch_bounds__(kFinalThreads) void k_reduce_runs(const double *__restrict__ partial, uint32_t stride,
+                                                             const SegRec *__restrict__ seg, double *__restrict__ seg_sum) {
     const SegRec sr = seg[blockIdx.x];
     double acc = 0.0;
-    for (uint32_t i = threadIdx.x; i < sr.count; i += kFinalThreads) acc += partial[sr.first + i];
+    for (uint32_t i = threadIdx.x; i < sr.count; i += kFinalThreads) acc += partial[partial_slot(sr.first + i, stride)];
     acc = wave_sum(acc);
     __shared__ double wave_part[kFinalThreads / 64];
     if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = acc;
@@ -383,16 +385,20 @@ __global__ __launch_bounds__(kFinalThreads) void k_reduce_runs(const double *__r
 __global__ __launch_bounds__(kFinalThreads) void k_reduce_tensors(const double *__restrict__ seg_sum,
                                                                 const uint32_t *__restrict__ tensor_seg_start, uint32_t n_tensors,
                                                                 double *__restrict__ result) {
-    for (uint32_t t = threadIdx.x; t < n_tensors; t += kFinalThreads) {
+    // one wavefront per tensor at a time: lane l adds runs l, l + 64, ... in order, then a butterfly
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (uint32_t t = wave; t < n_tensors; t += kFinalThreads / 64) {
         double acc = 0.0;
-        for (uint32_t i = tensor_seg_start[t]; i < tensor_seg_start[t + 1]; ++i) acc += seg_sum[i];
-        result[1 + t] = acc;
+        for (uint32_t i = tensor_seg_start[t] + lane; i < tensor_seg_start[t + 1]; i += 64) acc += seg_sum[i];
+        acc = wave_sum(acc);
+        if (lane == 0) result[1 + t] = acc;
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
+    if (wave == 0) {
         double total = 0.0;
-        for (uint32_t t = 0; t < n_tensors; ++t) total += result[1 + t];
-        result[0] = total;
+        for (uint32_t t = lane; t < n_tensors; t += 64) total += result[1 + t];
+        total = wave_sum(total);
+        if (lane == 0) result[0] = total;
     }
 }
 
@@ -475,9 +481,10 @@ hipError_t launch_fused_steps_extrapolate(const Layout &L, uint32_t wpb, int opt
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_finalize(const double *d_partial, const SegRec *d_seg, uint32_t n_segs, const uint32_t *d_tensor_seg_start,
-                           uint32_t n_tensors, double *d_seg_sum, double *d_result, hipStream_t stream) {
-    k_reduce_runs<<<dim3(n_segs), dim3(kFinalThreads), 0, stream>>>(d_partial, d_seg, d_seg_sum);
+hipError_t launch_finalize(const double *d_partial, uint32_t n_blocks, const SegRec *d_seg, uint32_t n_segs,
+                           const uint32_t *d_tensor_seg_start, uint32_t n_tensors, double *d_seg_sum, double *d_result,
+                           hipStream_t stream) {
+    k_reduce_runs<<<dim3(n_segs), dim3(kFinalThreads), 0, stream>>>(d_partial, partial_stride(n_blocks), d_seg, d_seg_sum);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     k_reduce_tensors<<<dim3(1), dim3(kFinalThreads), 0, stream>>>(d_seg_sum, d_tensor_seg_start, n_tensors, d_result);
