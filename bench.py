@@ -37,6 +37,7 @@ def parse_args():
     ap.add_argument("--unfused", action="store_true", help="run the second fast step and the extrapolation as two passes")
     ap.add_argument("--same-phase", action="store_true", help="plain torch allocations instead of the phased HBM layout")
     ap.add_argument("--arena", action="store_true", help="carve all buffers from one allocation")
+    ap.add_argument("--phases", default="", help="experiment: KiB phases (mod 64) of theta,theta_probe,m,v,g0,g1,g2[,model_copy]")
     ap.add_argument("--no-probe", action="store_true",
                     help="workloads with a bf16 model copy: deliver theta^{t,1} through the copy only (no fp32 theta_probe)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -120,6 +121,10 @@ def main():
     adam = spec["optimizer"] == "adamw"
     gdt = torch.float32 if spec["grad_dtype"] == "f32" else torch.bfloat16
 
+    phases = None
+    if args.phases:
+        names = ["theta", "theta_probe", "m", "v", "g0", "g1", "g2", "model_copy"]
+        phases = {n: int(x) for n, x in zip(names, args.phases.split(","))}
     # ---- device buffers (caller-owned), in the layout paper_2605_06755_amd/layout.py describes ---------
     if args.same_phase:
         flat = {"theta": torch.empty(padded, dtype=torch.float32, device=dev),
@@ -132,7 +137,7 @@ def main():
         gflat = [torch.empty(padded, dtype=gdt, device=dev) for _ in range(3)]
     else:
         flat, gflat = layout_mod.alloc_engine_state(padded, dev, adam=adam, model_copy=spec["copy"], grad_dtype=gdt,
-                                                    arena=args.arena)
+                                                    arena=args.arena, phases_kib=phases)
     print("base addresses:", {k: hex(v.data_ptr()) for k, v in flat.items()}, [hex(g.data_ptr()) for g in gflat], file=sys.stderr)
     views = {k: synth.split_like(v, layout, 4) for k, v in flat.items()}
     g0, g1, gs = (synth.split_like(g, layout, 4) for g in gflat)

@@ -108,17 +108,29 @@ double gxpo_oracle_geometric_sum(double x, int n)
  *    whose ratio is unusable is to keep the observed two-probe displacement
  *    (Remark "Ratio safeguards in practice"), so r == -1 gives scale = 1.
  * ---------------------------------------------------------------------- */
-double gxpo_oracle_scale(double g0, double g1, int K, double delta, double r_max)
+/* The retention ratio as the rule uses it: returns 0 when the coordinate is off
+ * the active set (then *r_out is untouched), 1 otherwise with *r_out = g1/g0
+ * after the optional clamp. */
+static int retention_ratio(double g0, double g1, double delta, double r_max, double *r_out)
 {
     const double delta32 = (double)(float)delta;
     if (!(fabs(g0) > delta32))
-        return 1.0;
+        return 0;
     double r = g1 / g0;
     if (isfinite(r_max)) {
         const double R = (double)(float)r_max;
         if (r > R) r = R;
         if (r < -R) r = -R;
     }
+    *r_out = r;
+    return 1;
+}
+
+double gxpo_oracle_scale(double g0, double g1, int K, double delta, double r_max)
+{
+    double r;
+    if (!retention_ratio(g0, g1, delta, r_max, &r))
+        return 1.0;
     if (r == -1.0)
         return 1.0;
     return gxpo_oracle_geometric_sum(r, K) / gxpo_oracle_geometric_sum(r, 2);
@@ -165,6 +177,53 @@ double gxpo_oracle_sum_squares(int64_t n, const double *g)
     for (int64_t i = 0; i < n; ++i)
         acc += (long double)g[i] * (long double)g[i];
     return (double)acc;
+}
+
+/* ------------------------------------------------------------------------
+ * Mechanism diagnostics of one active step: the quantities of the paper's
+ * appendix table "Active-phase GXPO diagnostics" (gradient norms,
+ * cos(g0, g_slow), retention ratio mean and deviation over the active set,
+ * ||Delta_K|| / ||Delta_2||, mean scale, inactive fraction), for one tensor.
+ * Plain two-pass definitions, accumulated in long double.
+ *
+ * READINGS (the table gives names, not formulas): the retention statistics and
+ * the mean scale run over the active set {|g0| > delta} and use r after the
+ * optional clamp; the deviation is the population deviation;
+ * Delta_2 = theta^{t,2} - theta^t, Delta_K = theta^{t,K} - theta^t.
+ *
+ * out[0] sum g0^2      out[1] sum g1^2       out[2] sum g_slow^2
+ * out[3] sum g0*g_slow out[4] active count   out[5] sum_active r
+ * out[6] sum_active (r - mean_r)^2           out[7] sum_active scale
+ * out[8] sum Delta_2^2 out[9] sum Delta_K^2
+ * mean_r (the mean over the active set of ALL tensors) is passed in for the
+ * second pass; call once with NAN to get out[4], out[5], then again.
+ * ---------------------------------------------------------------------- */
+void gxpo_oracle_diagnostic_sums(int64_t n, const double *theta_0, const double *theta_2,
+                                 const double *g0, const double *g1, const double *g_slow,
+                                 int K, double delta, double r_max, double mean_r, double *out)
+{
+    long double a[10] = {0};
+    for (int64_t i = 0; i < n; ++i) {
+        a[0] += (long double)g0[i] * g0[i];
+        a[1] += (long double)g1[i] * g1[i];
+        a[2] += (long double)g_slow[i] * g_slow[i];
+        a[3] += (long double)g0[i] * g_slow[i];
+        double r;
+        double scale = gxpo_oracle_scale(g0[i], g1[i], K, delta, r_max);
+        if (retention_ratio(g0[i], g1[i], delta, r_max, &r)) {
+            a[4] += 1.0L;
+            a[5] += r;
+            if (!isnan(mean_r))
+                a[6] += ((long double)r - mean_r) * ((long double)r - mean_r);
+            a[7] += scale;
+        }
+        const double d2 = theta_2[i] - theta_0[i];
+        const double dK = d2 * scale;
+        a[8] += (long double)d2 * d2;
+        a[9] += (long double)dK * dK;
+    }
+    for (int j = 0; j < 10; ++j)
+        out[j] = (double)a[j];
 }
 
 /* ------------------------------------------------------------------------

@@ -78,6 +78,9 @@ def _load():
         ctypes.c_double, ctypes.c_double, _dp, _dp, _dp]
     lib.gxpo_oracle_sum_squares.restype = ctypes.c_double
     lib.gxpo_oracle_sum_squares.argtypes = [ctypes.c_int64, _dp]
+    lib.gxpo_oracle_diagnostic_sums.restype = None
+    lib.gxpo_oracle_diagnostic_sums.argtypes = [
+        ctypes.c_int64, _dp, _dp, _dp, _dp, _dp, ctypes.c_int, ctypes.c_double, ctypes.c_double, ctypes.c_double, _dp]
     lib.gxpo_oracle_bf16_bits.restype = ctypes.c_uint16
     lib.gxpo_oracle_bf16_bits.argtypes = [ctypes.c_float]
     lib.gxpo_oracle_bf16_round_array.restype = None
@@ -157,6 +160,37 @@ def extrapolate(theta_0, theta_2, g0, g1, K: int, alpha: float, delta: float,
 def sum_squares(g) -> float:
     g = _f64(g).ravel()
     return _load().gxpo_oracle_sum_squares(g.size, _p(g))
+
+
+def diagnostics(theta_0s, theta_2s, g0s, g1s, g_slows, K: int, delta: float, r_max: float = math.inf) -> dict:
+    """Mechanism diagnostics of one active step over a list of tensors (the
+    quantities of the paper's appendix table of active-phase diagnostics)."""
+    lib = _load()
+    arrs = [[_f64(a).ravel() for a in lst] for lst in (theta_0s, theta_2s, g0s, g1s, g_slows)]
+
+    def sums(mean_r):
+        tot = np.zeros(10)
+        for th0, th2, a, b, c in zip(*arrs):
+            out = np.zeros(10)
+            lib.gxpo_oracle_diagnostic_sums(th0.size, _p(th0), _p(th2), _p(a), _p(b), _p(c), int(K), float(delta),
+                                            float(r_max), float(mean_r), _p(out))
+            tot += out
+        return tot
+    first = sums(float("nan"))
+    n_total = sum(a.size for a in arrs[0])
+    n_act = first[4]
+    mean_r = first[5] / n_act if n_act else float("nan")
+    s = sums(mean_r) if n_act else first
+    ng0, ng1, ngs = math.sqrt(s[0]), math.sqrt(s[1]), math.sqrt(s[2])
+    return {
+        "norm_g0": ng0, "norm_g1": ng1, "norm_g_slow": ngs,
+        "cos_g0_g_slow": s[3] / (ng0 * ngs) if ng0 > 0 and ngs > 0 else float("nan"),
+        "retention_mean": mean_r,
+        "retention_std": math.sqrt(s[6] / n_act) if n_act else float("nan"),
+        "scale_mean": s[7] / n_act if n_act else float("nan"),
+        "inactive_fraction": 1.0 - n_act / n_total,
+        "displacement_ratio": math.sqrt(s[9] / s[8]) if s[8] > 0 else float("nan"),
+    }
 
 
 def bf16_round_bits(x32: np.ndarray) -> np.ndarray:
@@ -295,6 +329,7 @@ class GXPOOracle:
         self.theta_tilde = None
         self.scale = None
         self._sumsq = None
+        self._g0 = self._g1 = self._g_slow = None
 
     # -- phase ----------------------------------------------------------------
     @property
@@ -332,6 +367,8 @@ class GXPOOracle:
     def extrapolate(self, g0, g1):
         """Active set, ratio, scale, theta^{t,K}, theta~^t."""
         c = self.cfg
+        self._g0 = [_f64(g).ravel() for g in g0]
+        self._g1 = [_f64(g).ravel() for g in g1]
         self.scale, self.theta_K, self.theta_tilde = [], [], []
         for th0, th2, a, b in zip(self._theta_0, self._theta_2, g0, g1):
             s, tk, tt = extrapolate(th0, th2, a, b, c.K, c.alpha, c.delta, c.r_max)
@@ -344,8 +381,14 @@ class GXPOOracle:
         """theta^{t+1} = OptimStep(theta~^t, g_slow); records sum g_slow^2 per tensor."""
         self.backward_passes += 1
         self._sumsq = [sum_squares(g) for g in g_slow]
+        self._g_slow = [_f64(g).ravel() for g in g_slow]
         self.theta = self._optim_all(self.theta_tilde, g_slow)
         return self.theta
+
+    def diagnostics(self) -> dict:
+        """Mechanism diagnostics of the step whose slow correction just ran."""
+        c = self.cfg
+        return diagnostics(self._theta_0, self._theta_2, self._g0, self._g1, self._g_slow, c.K, c.delta, c.r_max)
 
     def tensor_norms(self):
         return [math.sqrt(s) for s in self._sumsq]

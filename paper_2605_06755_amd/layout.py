@@ -37,19 +37,23 @@ def alloc_phased(numel: int, dtype, device, phase_bytes: int = 0, fill=None) -> 
 
 
 def alloc_engine_state(numel: int, device, *, adam: bool = True, model_copy: bool = False, grad_dtype=torch.float32,
-                       n_grad_buffers: int = 3, arena: bool = False):
+                       n_grad_buffers: int = 3, arena: bool = False, phases_kib=None):
     """Flat buffers for one engine context in the fast layout: a dict with
-    theta, theta_probe, (m, v), (model_copy) and a list of gradient buffers."""
+    theta, theta_probe, (m, v), (model_copy) and a list of gradient buffers.
+    `phases_kib` overrides the placement for experiments: a dict name -> KiB
+    (names theta, theta_probe, m, v, model_copy, g0, g1, g2)."""
     if arena:
         return _alloc_arena(numel, device, adam, model_copy, grad_dtype, n_grad_buffers)
-    out = {"theta": alloc_phased(numel, torch.float32, device, 0),
-           "theta_probe": alloc_phased(numel, torch.float32, device, 0)}
+    ph = {"theta": 0, "theta_probe": 0, "m": MOMENT_PHASE_BYTES // 1024, "v": MOMENT_PHASE_BYTES // 1024, "model_copy": 0}
+    ph.update(phases_kib or {})
+    out = {"theta": alloc_phased(numel, torch.float32, device, ph["theta"] * 1024),
+           "theta_probe": alloc_phased(numel, torch.float32, device, ph["theta_probe"] * 1024)}
     if adam:
-        out["m"] = alloc_phased(numel, torch.float32, device, MOMENT_PHASE_BYTES, fill=0.0)
-        out["v"] = alloc_phased(numel, torch.float32, device, MOMENT_PHASE_BYTES, fill=0.0)
+        out["m"] = alloc_phased(numel, torch.float32, device, ph["m"] * 1024, fill=0.0)
+        out["v"] = alloc_phased(numel, torch.float32, device, ph["v"] * 1024, fill=0.0)
     if model_copy:
-        out["model_copy"] = alloc_phased(numel, torch.bfloat16, device, 0)
-    grads = [alloc_phased(numel, grad_dtype, device, 0) for _ in range(n_grad_buffers)]
+        out["model_copy"] = alloc_phased(numel, torch.bfloat16, device, ph["model_copy"] * 1024)
+    grads = [alloc_phased(numel, grad_dtype, device, ph.get(f"g{i}", 0) * 1024) for i in range(n_grad_buffers)]
     return out, grads
 
 

@@ -495,3 +495,55 @@ def test_bf16_rounding_matches_library():
     np.testing.assert_array_equal(got, want)
     np.testing.assert_array_equal(O.bf16_bits_to_f64(got),
                                   torch.from_numpy(x).to(torch.bfloat16).double().numpy())
+
+
+# ---------------------------------------------------------------------------
+# 7. Mechanism diagnostics (appendix table of active-phase diagnostics): against
+#    numpy definitions on random data and closed forms on the diagonal surrogate
+# ---------------------------------------------------------------------------
+def test_diagnostics_match_numpy_definitions():
+    rng = np.random.default_rng(12)
+    sizes = [300, 17, 1000]
+    mk = lambda: [rng.normal(size=n) for n in sizes]
+    th0, th2, g0, g1, gs = mk(), mk(), mk(), mk(), mk()
+    g0[0][::7] = 1e-5                                    # some inactive coordinates
+    K, delta, r_max = 5, 1e-3, 3.0
+    d = O.diagnostics(th0, th2, g0, g1, gs, K, delta, r_max)
+    cat = lambda l: np.concatenate(l)
+    G0, G1, GS, T0, T2 = cat(g0), cat(g1), cat(gs), cat(th0), cat(th2)
+    act = np.abs(G0) > float(np.float32(delta))
+    r = np.clip(G1[act] / G0[act], -r_max, r_max)
+    scale = np.ones_like(G0)
+    scale[act] = np.array([O.scale_factor(a, b, K, delta, r_max) for a, b in zip(G0[act], G1[act])])
+    assert d["norm_g0"] == pytest.approx(np.linalg.norm(G0), rel=1e-13)
+    assert d["norm_g1"] == pytest.approx(np.linalg.norm(G1), rel=1e-13)
+    assert d["norm_g_slow"] == pytest.approx(np.linalg.norm(GS), rel=1e-13)
+    assert d["cos_g0_g_slow"] == pytest.approx(np.dot(G0, GS) / np.linalg.norm(G0) / np.linalg.norm(GS), rel=1e-11)
+    assert d["retention_mean"] == pytest.approx(np.mean(r), rel=1e-12)
+    assert d["retention_std"] == pytest.approx(np.std(r), rel=1e-12)
+    assert d["scale_mean"] == pytest.approx(np.mean(scale[act]), rel=1e-12)
+    assert d["inactive_fraction"] == pytest.approx(1 - act.mean(), rel=1e-12)
+    assert d["inactive_fraction"] > 0.02
+    assert d["displacement_ratio"] == pytest.approx(np.linalg.norm((T2 - T0) * scale) / np.linalg.norm(T2 - T0), rel=1e-12)
+
+
+def test_diagnostics_closed_forms_on_the_diagonal_surrogate():
+    """Plain GD on the diagonal quadratic: r_i = 1 - eta h_i exactly, so every statistic has a
+    closed form; with alpha = 1 the corrective gradient is rho^K g0 coordinate-wise."""
+    h, ts, th0 = surrogate_numpy()
+    eta, K = 0.1, 4
+    orc = O.GXPOOracle(gd_config(K, 1.0, eta), [th0])
+    orc.train_step(lambda ths: [h * (ths[0] - ts)])
+    d = orc.diagnostics()
+    rho = 1 - eta * h
+    g0 = h * (th0 - ts)
+    S = lambda n: sum(rho ** j for j in range(n))
+    assert d["retention_mean"] == pytest.approx(np.mean(rho), rel=1e-12)
+    assert d["retention_std"] == pytest.approx(np.std(rho), rel=1e-10)
+    assert d["scale_mean"] == pytest.approx(np.mean(S(K) / S(2)), rel=1e-12)
+    assert d["inactive_fraction"] == 0.0
+    assert d["displacement_ratio"] == pytest.approx(np.linalg.norm(g0 * S(K)) / np.linalg.norm(g0 * S(2)), rel=1e-11)
+    assert d["norm_g1"] == pytest.approx(np.linalg.norm(rho * g0), rel=1e-12)
+    gK = rho ** K * g0
+    assert d["norm_g_slow"] == pytest.approx(np.linalg.norm(gK), rel=1e-11)
+    assert d["cos_g0_g_slow"] == pytest.approx(np.dot(g0, gK) / np.linalg.norm(g0) / np.linalg.norm(gK), rel=1e-11)
