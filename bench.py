@@ -40,6 +40,7 @@ def parse_args():
     ap.add_argument("--phases", default="", help="experiment: KiB phases (mod 64) of theta,theta_probe,m,v,g0,g1,g2[,model_copy]")
     ap.add_argument("--no-probe", action="store_true",
                     help="workloads with a bf16 model copy: deliver theta^{t,1} through the copy only (no fp32 theta_probe)")
+    ap.add_argument("--diagnostics", action="store_true", help="also accumulate the mechanism diagnostics in the passes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1 << 26, help="elements of the workload the oracle is timed on")
     return ap.parse_args()
@@ -151,7 +152,8 @@ def main():
     quad.init_theta(flat["theta"])
 
     cfg = B.make_config(optimizer=spec["optimizer"], grad_dtype=spec["grad_dtype"], fuse_step2=fused, copy_mask=7,
-                        window=10, tau=3.0, waves_per_block=args.waves_per_block, weight_decay=0.01, **spec["cfg"])
+                        window=10, tau=3.0, waves_per_block=args.waves_per_block, weight_decay=0.01,
+                        diagnostics=args.diagnostics, **spec["cfg"])
     ctx = B.gxpo_init(cfg, tensors)
 
     # ---- one live step: gradients evaluated where Algorithm 1 asks for them ----------------------------
@@ -193,6 +195,8 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     kernel_ms = {k: sum(a.elapsed_time(b) for a, b in v) / len(v) for k, v in events.items()}
     bpp = bytes_per_param(spec, fused)
+    if args.diagnostics:
+        bpp["slow_step"] += 4 if spec["grad_dtype"] == "f32" else 2          # g0 read again for <g0, g_slow>
     step_bytes = sum(bpp[k] for k in kernel_ms) * P
     kernels = {k: {"ms": round(ms, 4), "bytes_per_param": bpp[k], "gbps": round(bpp[k] * P / ms / 1e6, 1)}
                for k, ms in kernel_ms.items()}
@@ -275,6 +279,9 @@ def main():
     }
     if fallback:
         out["fallback_step"] = fallback
+    if args.diagnostics:
+        d = B.gxpo_get_diagnostics(ctx)
+        out["diagnostics"] = {k: getattr(d, k) for k, _ in d._fields_}
     print(json.dumps(out))
 
 

@@ -122,6 +122,10 @@ typedef struct gxpo_config {
     uint32_t gate_min_count;  /* gate is evaluated once the buffer holds this many norms; 0 = window */
     uint32_t gate_ddof;       /* 0 population / 1 sample standard deviation */
     uint32_t waves_per_block; /* launch shape: 0 = library default, else 1, 2 or 4 */
+    uint32_t diagnostics;     /* 1: also accumulate the mechanism diagnostics (gxpo_get_diagnostics) inside
+                                 the extrapolation pass and the slow step; g0 is then re-read by the slow
+                                 step (+4 or +2 bytes per parameter) and must stay intact until it has run */
+    uint32_t reserved;        /* 0 */
     double lr, beta1, beta2, adam_eps, weight_decay;   /* OptimStep (AdamW: decoupled weight decay) */
     double alpha;             /* reposition strength in [0, 1]                  (Eq. (9))            */
     double delta;             /* active set is |g0_i| > delta, compared in fp32 (Section 2.2)        */
@@ -139,6 +143,20 @@ typedef struct gxpo_gate_info {
     int64_t s_star;      /* first fallback step index, -1 while still +infinity */
     int64_t t;           /* index of the training step this record belongs to */
 } gxpo_gate_info;
+
+/* What the paper logs about one active step to check that the method runs in
+ * its intended regime (appendix table of active-phase diagnostics).  Retention
+ * statistics and the mean scale run over the active set {|g0| > delta} and use
+ * the ratio after the r_max clamp; the deviation is the population deviation. */
+typedef struct gxpo_diagnostics {
+    double  norm_g0, norm_g1, norm_g_slow;
+    double  cos_g0_g_slow;        /* NaN if g_slow was handed in in g0's own buffers */
+    double  retention_mean, retention_std;
+    double  scale_mean;
+    double  inactive_fraction;
+    double  displacement_ratio;   /* ||theta^{t,K} - theta^t||_2 / ||theta^{t,2} - theta^t||_2 */
+    int64_t t;                    /* the training step these belong to */
+} gxpo_diagnostics;
 
 /* The small host-side state of a context; enough to checkpoint / resume. */
 typedef struct gxpo_state {
@@ -203,6 +221,10 @@ int gxpo_fallback_step(gxpo_ctx *ctx, const void *const *g0, void *stream);
 /* Per-tensor ||g_slow||_2 of the most recent gxpo_slow_step into a host array
  * of n_tensors doubles.  Waits for `stream`. */
 int gxpo_tensor_norms(gxpo_ctx *ctx, double *out_host, void *stream);
+
+/* Diagnostics of the most recent active step (config.diagnostics must be 1 and
+ * a slow step must have run).  Waits for `stream`. */
+int gxpo_get_diagnostics(gxpo_ctx *ctx, gxpo_diagnostics *out_host, void *stream);
 
 /* Copy the host-side state out / in (phase must be IDLE for set).  Setting
  * s_star <= t puts the context into the fallback phase. */

@@ -42,7 +42,7 @@ GXPO_MAX_WINDOW = 256
 
 EXPORTED_SYMBOLS = [
     "gxpo_init", "gxpo_destroy", "gxpo_fast_steps", "gxpo_extrapolate", "gxpo_slow_step", "gxpo_gate",
-    "gxpo_fallback_step", "gxpo_tensor_norms", "gxpo_get_state", "gxpo_set_state", "gxpo_last_error",
+    "gxpo_fallback_step", "gxpo_tensor_norms", "gxpo_get_diagnostics", "gxpo_get_state", "gxpo_set_state", "gxpo_last_error",
     "gxpo_validate_config", "gxpo_host_gate_step", "gxpo_plan_blocks", "gxpo_stream_copy",
 ]
 
@@ -57,7 +57,7 @@ class gxpo_config(ctypes.Structure):
     _fields_ = [("struct_size", ctypes.c_uint32), ("optimizer", ctypes.c_uint32), ("grad_dtype", ctypes.c_uint32),
                 ("K", ctypes.c_uint32), ("fuse_step2", ctypes.c_uint32), ("copy_mask", ctypes.c_uint32),
                 ("window", ctypes.c_uint32), ("gate_min_count", ctypes.c_uint32), ("gate_ddof", ctypes.c_uint32),
-                ("waves_per_block", ctypes.c_uint32),
+                ("waves_per_block", ctypes.c_uint32), ("diagnostics", ctypes.c_uint32), ("reserved", ctypes.c_uint32),
                 ("lr", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
                 ("adam_eps", ctypes.c_double), ("weight_decay", ctypes.c_double),
                 ("alpha", ctypes.c_double), ("delta", ctypes.c_double), ("r_max", ctypes.c_double),
@@ -68,6 +68,13 @@ class gxpo_gate_info(ctypes.Structure):
     _fields_ = [("norm", ctypes.c_double), ("mu", ctypes.c_double), ("sigma", ctypes.c_double), ("z", ctypes.c_double),
                 ("evaluated", ctypes.c_int32), ("tripped", ctypes.c_int32), ("s_star", ctypes.c_int64),
                 ("t", ctypes.c_int64)]
+
+
+class gxpo_diagnostics(ctypes.Structure):
+    _fields_ = [("norm_g0", ctypes.c_double), ("norm_g1", ctypes.c_double), ("norm_g_slow", ctypes.c_double),
+                ("cos_g0_g_slow", ctypes.c_double), ("retention_mean", ctypes.c_double), ("retention_std", ctypes.c_double),
+                ("scale_mean", ctypes.c_double), ("inactive_fraction", ctypes.c_double),
+                ("displacement_ratio", ctypes.c_double), ("t", ctypes.c_int64)]
 
 
 class gxpo_state(ctypes.Structure):
@@ -96,6 +103,8 @@ _lib.gxpo_fallback_step.restype = ctypes.c_int
 _lib.gxpo_fallback_step.argtypes = [_ctx_p, _ptr_list, ctypes.c_void_p]
 _lib.gxpo_tensor_norms.restype = ctypes.c_int
 _lib.gxpo_tensor_norms.argtypes = [_ctx_p, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+_lib.gxpo_get_diagnostics.restype = ctypes.c_int
+_lib.gxpo_get_diagnostics.argtypes = [_ctx_p, ctypes.POINTER(gxpo_diagnostics), ctypes.c_void_p]
 _lib.gxpo_get_state.restype = ctypes.c_int
 _lib.gxpo_get_state.argtypes = [_ctx_p, ctypes.POINTER(gxpo_state)]
 _lib.gxpo_set_state.restype = ctypes.c_int
@@ -122,7 +131,7 @@ class GxpoError(RuntimeError):
 
 
 def make_config(*, optimizer="adamw", grad_dtype="f32", K=8, fuse_step2=True, copy_mask=7, window=10,
-                gate_min_count=0, gate_ddof=0, waves_per_block=0, lr=1e-6, beta1=0.9, beta2=0.999,
+                gate_min_count=0, gate_ddof=0, waves_per_block=0, diagnostics=False, lr=1e-6, beta1=0.9, beta2=0.999,
                 adam_eps=1e-8, weight_decay=0.01, alpha=0.5, delta=1e-8, r_max=math.inf, tau=3.0,
                 gate_eps=1e-8) -> gxpo_config:
     c = gxpo_config()
@@ -131,6 +140,7 @@ def make_config(*, optimizer="adamw", grad_dtype="f32", K=8, fuse_step2=True, co
     c.grad_dtype = {"f32": GXPO_GRAD_F32, "bf16": GXPO_GRAD_BF16}.get(grad_dtype, grad_dtype)
     c.K, c.fuse_step2, c.copy_mask = int(K), int(bool(fuse_step2)), int(copy_mask)
     c.window, c.gate_min_count, c.gate_ddof, c.waves_per_block = int(window), int(gate_min_count), int(gate_ddof), int(waves_per_block)
+    c.diagnostics, c.reserved = int(diagnostics), 0
     c.lr, c.beta1, c.beta2, c.adam_eps, c.weight_decay = lr, beta1, beta2, adam_eps, weight_decay
     c.alpha, c.delta, c.r_max, c.tau, c.gate_eps = alpha, delta, r_max, tau, gate_eps
     return c
@@ -238,6 +248,12 @@ def gxpo_tensor_norms(ctx: Context, stream=None) -> List[float]:
     out = (ctypes.c_double * ctx.n_tensors)()
     ctx._check(_lib.gxpo_tensor_norms(ctx.handle, out, _stream_ptr(stream)))
     return list(out)
+
+
+def gxpo_get_diagnostics(ctx: Context, stream=None) -> gxpo_diagnostics:
+    d = gxpo_diagnostics()
+    ctx._check(_lib.gxpo_get_diagnostics(ctx.handle, ctypes.byref(d), _stream_ptr(stream)))
+    return d
 
 
 def gxpo_get_state(ctx: Context) -> gxpo_state:

@@ -55,6 +55,9 @@ struct gxpo_ctx {
     double *h_result = nullptr;              // pinned, [1 + n]
     uint32_t n_blocks = 0, n_segs = 0;
     bool have_norms = false;
+    bool have_diag = false, cos_valid = false;
+    int64_t diag_t = -1;
+    uint32_t n_acc = 1;                      // accumulators the workspace holds (1, or kNumAcc with diagnostics)
 
     // gradient pointer staging
     const void **h_stage = nullptr;          // pinned, [kStageSlots][n]
@@ -113,6 +116,8 @@ int check_config(const gxpo_config *c, std::string &msg) {
     if (c->gate_ddof > 1) return bad("gate_ddof must be 0 or 1");
     if (c->waves_per_block != 0 && c->waves_per_block != 1 && c->waves_per_block != 2 && c->waves_per_block != 4)
         return bad("waves_per_block must be 0, 1, 2 or 4");
+    if (c->diagnostics > 1) return bad("diagnostics must be 0 or 1");
+    if (c->reserved != 0) return bad("reserved must be 0");
     if (!(c->lr > 0.0) || !std::isfinite(c->lr)) return bad("lr must be finite and > 0");
     if (c->optimizer == GXPO_OPT_ADAMW) {
         if (!(c->beta1 >= 0.0 && c->beta1 < 1.0)) return bad("beta1 must be in [0, 1)");
@@ -389,6 +394,7 @@ int gxpo_init(gxpo_ctx **out, const gxpo_config *cfg, const gxpo_tensor *tensors
     ctx->cfg = *cfg;
     ctx->n = n_tensors;
     ctx->wpb = wpb;
+    ctx->n_acc = cfg->diagnostics ? (uint32_t)kNumAcc : 1u;
     ctx->device = device;
     ctx->tensors.assign(tensors, tensors + n_tensors);
     ctx->blk_start = blk_start;
@@ -428,13 +434,13 @@ int gxpo_init(gxpo_ctx **out, const gxpo_config *cfg, const gxpo_tensor *tensors
     if (rc == GXPO_OK) rc = dev_alloc(ctx, &ctx->d_blk_start, (size_t)n_tensors + 1);
     if (rc == GXPO_OK) rc = dev_alloc(ctx, &ctx->d_coarse, coarse.size());
     if (rc == GXPO_OK) rc = dev_alloc(ctx, &ctx->d_grads, (size_t)kGradRoles * n_tensors);
-    if (rc == GXPO_OK) rc = dev_alloc(ctx, &ctx->d_partial, (size_t)8 * partial_stride(ctx->n_blocks));
+    if (rc == GXPO_OK) rc = dev_alloc(ctx, &ctx->d_partial, (size_t)ctx->n_acc * partial_pitch(ctx->n_blocks));
     if (rc == GXPO_OK) rc = dev_alloc(ctx, &ctx->d_seg, segs.size());
     if (rc == GXPO_OK) rc = dev_alloc(ctx, &ctx->d_tensor_seg_start, (size_t)n_tensors + 1);
-    if (rc == GXPO_OK) rc = dev_alloc(ctx, &ctx->d_seg_sum, segs.size());
-    if (rc == GXPO_OK) rc = dev_alloc(ctx, &ctx->d_result, (size_t)n_tensors + 1);
+    if (rc == GXPO_OK) rc = dev_alloc(ctx, &ctx->d_seg_sum, (size_t)ctx->n_acc * segs.size());
+    if (rc == GXPO_OK) rc = dev_alloc(ctx, &ctx->d_result, (size_t)ctx->n_acc * ((size_t)n_tensors + 1));
     if (rc != GXPO_OK) { release(ctx); return rc; }
-    he = hipHostMalloc((void **)&ctx->h_result, sizeof(double) * ((size_t)n_tensors + 1), hipHostMallocDefault);
+    he = hipHostMalloc((void **)&ctx->h_result, sizeof(double) * ctx->n_acc * ((size_t)n_tensors + 1), hipHostMallocDefault);
     if (he == hipSuccess) he = hipHostMalloc((void **)&ctx->h_stage, sizeof(void *) * (size_t)kStageSlots * n_tensors, hipHostMallocDefault);
     for (int i = 0; he == hipSuccess && i < kStageSlots; ++i) he = hipEventCreateWithFlags(&ctx->stage_event[i], hipEventDisableTiming);
     if (he == hipSuccess) he = up(ctx->d_tab, tab.data(), sizeof(TensorRec) * n_tensors);
@@ -443,7 +449,7 @@ int gxpo_init(gxpo_ctx **out, const gxpo_config *cfg, const gxpo_tensor *tensors
     if (he == hipSuccess) he = up(ctx->d_seg, segs.data(), sizeof(SegRec) * segs.size());
     if (he == hipSuccess) he = up(ctx->d_tensor_seg_start, tensor_seg_start.data(), sizeof(uint32_t) * (n_tensors + 1));
     if (he == hipSuccess) he = hipMemset(ctx->d_grads, 0, sizeof(void *) * kGradRoles * n_tensors);
-    if (he == hipSuccess) he = hipMemset(ctx->d_result, 0, sizeof(double) * (n_tensors + 1));
+    if (he == hipSuccess) he = hipMemset(ctx->d_result, 0, sizeof(double) * ctx->n_acc * (n_tensors + 1));
     if (he == hipSuccess) he = hipDeviceSynchronize();
     if (he != hipSuccess) { release(ctx); return fail_hip(nullptr, he, "gxpo_init device set-up"); }
     *out = ctx;
@@ -483,7 +489,7 @@ int gxpo_fast_steps(gxpo_ctx *ctx, int which, const void *const *grads, void *st
         // fused schedule: the probe pass only previews the step, the moments are advanced by gxpo_extrapolate
         const int write_moments = fused ? 0 : 1;
         GXPO_HIP(ctx, launch_step(ctx->layout(), ctx->wpb, (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, src, kSrcProbe,
-                                  write_moments, wc, nullptr, s));
+                                  write_moments, wc, nullptr, GradArg{}, s));
         if (fused) {
             ctx->pending_g0.assign(grads, grads + ctx->n);
             ctx->pending_step1 = step_no;
@@ -515,14 +521,18 @@ int gxpo_extrapolate(gxpo_ctx *ctx, const void *const *g0, const void *const *g1
     if (rc != GXPO_OK) return rc;
     const ExtrapParams e = make_extrap_params(ctx->cfg);
     const int wc = (ctx->cfg.copy_mask & GXPO_COPY_AT_TILDE) ? 1 : 0;
+    double *diag = ctx->cfg.diagnostics ? ctx->d_partial : nullptr;
     if (ctx->cfg.fuse_step2) {
         const StepParams p1 = make_step_params(ctx->cfg, ctx->pending_step1);
         const StepParams p2 = make_step_params(ctx->cfg, ctx->pending_step2);
         GXPO_HIP(ctx, launch_fused_steps_extrapolate(ctx->layout(), ctx->wpb, (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g0, d_g1,
-                                                     p1, p2, e, wc, s));
+                                                     p1, p2, e, wc, diag, s));
     } else {
-        GXPO_HIP(ctx, launch_extrapolate(ctx->layout(), ctx->wpb, (int)ctx->cfg.grad_dtype, d_g0, d_g1, e, wc, s));
+        GXPO_HIP(ctx, launch_extrapolate(ctx->layout(), ctx->wpb, (int)ctx->cfg.grad_dtype, d_g0, d_g1, e, wc, diag, s));
     }
+    if (diag)
+        GXPO_HIP(ctx, launch_finalize(ctx->d_partial, ctx->n_blocks, ctx->d_seg, ctx->n_segs, ctx->d_tensor_seg_start, ctx->n,
+                                      ctx->d_seg_sum, ctx->d_result, kAccG0Sq, kNumExtrapAcc, s));
     st.phase = GXPO_PHASE_REPOSITIONED;
     return GXPO_OK;
 }
@@ -539,19 +549,31 @@ int gxpo_slow_step(gxpo_ctx *ctx, const void *const *g_slow, void *stream) {
     const int64_t step_no = st.optim_steps + 1;
     const StepParams p = make_step_params(ctx->cfg, step_no);
     const int wc = (ctx->cfg.copy_mask & GXPO_COPY_AT_FINAL) ? 1 : 0;
+    // diagnostics: <g0, g_slow> needs g0 once more; its pointers are still staged from the extrapolation pass
+    GradArg dot{};
+    bool cos_valid = false;
+    if (ctx->cfg.diagnostics) {
+        cos_valid = true;
+        for (uint32_t t = 0; t < ctx->n; ++t)
+            if (g_slow[t] == ctx->shadow[kRoleG0][t]) cos_valid = false;      // g0 has been overwritten by g_slow
+        if (cos_valid) dot = GradArg{ctx->d_grads + (size_t)kRoleG0 * ctx->n, ctx->shadow[kRoleG0][0]};
+    }
     GXPO_HIP(ctx, launch_step(ctx->layout(), ctx->wpb, (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, kSrcTheta, kSrcTheta, 1, wc,
-                              ctx->d_partial, s));
+                              ctx->d_partial, dot, s));
     GXPO_HIP(ctx, launch_finalize(ctx->d_partial, ctx->n_blocks, ctx->d_seg, ctx->n_segs, ctx->d_tensor_seg_start, ctx->n,
-                                  ctx->d_seg_sum, ctx->d_result, s));
+                                  ctx->d_seg_sum, ctx->d_result, kAccSlowSq, cos_valid ? 2 : 1, s));
     ctx->have_norms = true;
+    ctx->have_diag = ctx->cfg.diagnostics != 0;
+    ctx->cos_valid = cos_valid;
+    ctx->diag_t = st.t;
     st.optim_steps = step_no;
     st.backward_passes += 1;
     st.phase = GXPO_PHASE_SLOW_DONE;
     return GXPO_OK;
 }
 
-static int fetch_result(gxpo_ctx *ctx, hipStream_t s) {
-    GXPO_HIP(ctx, hipMemcpyAsync(ctx->h_result, ctx->d_result, sizeof(double) * ((size_t)ctx->n + 1), hipMemcpyDeviceToHost, s));
+static int fetch_result(gxpo_ctx *ctx, hipStream_t s, uint32_t n_acc = 1) {
+    GXPO_HIP(ctx, hipMemcpyAsync(ctx->h_result, ctx->d_result, sizeof(double) * n_acc * ((size_t)ctx->n + 1), hipMemcpyDeviceToHost, s));
     GXPO_HIP(ctx, hipStreamSynchronize(s));
     return GXPO_OK;
 }
@@ -583,7 +605,7 @@ int gxpo_fallback_step(gxpo_ctx *ctx, const void *const *g0, void *stream) {
     const StepParams p = make_step_params(ctx->cfg, step_no);
     const int wc = (ctx->cfg.copy_mask & GXPO_COPY_AT_FINAL) ? 1 : 0;
     GXPO_HIP(ctx, launch_step(ctx->layout(), ctx->wpb, (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, kSrcTheta, kSrcTheta, 1, wc,
-                              nullptr, s));
+                              nullptr, GradArg{}, s));
     st.optim_steps = step_no;
     st.backward_passes += 1;
     st.t += 1;
@@ -597,6 +619,40 @@ int gxpo_tensor_norms(gxpo_ctx *ctx, double *out_host, void *stream) {
     int rc = fetch_result(ctx, (hipStream_t)stream);
     if (rc != GXPO_OK) return rc;
     for (uint32_t t = 0; t < ctx->n; ++t) out_host[t] = std::sqrt(ctx->h_result[1 + t]);
+    return GXPO_OK;
+}
+
+int gxpo_get_diagnostics(gxpo_ctx *ctx, gxpo_diagnostics *out, void *stream) {
+    if (!ctx) return GXPO_ERR_INVALID_ARG;
+    if (!out) return fail(ctx, GXPO_ERR_INVALID_ARG, "gxpo_get_diagnostics: out is NULL");
+    if (!ctx->cfg.diagnostics) return fail(ctx, GXPO_ERR_BAD_STATE, "gxpo_get_diagnostics: the context was created without diagnostics");
+    if (!ctx->have_diag) return fail(ctx, GXPO_ERR_BAD_STATE, "gxpo_get_diagnostics: no active step has completed its slow step yet");
+    int rc = fetch_result(ctx, (hipStream_t)stream, kNumAcc);
+    if (rc != GXPO_OK) return rc;
+    const size_t pitch = (size_t)ctx->n + 1;
+    auto total = [&](int acc) { return ctx->h_result[(size_t)acc * pitch]; };
+    const double nan = std::numeric_limits<double>::quiet_NaN();
+    double n_total = 0.0;
+    for (const gxpo_tensor &x : ctx->tensors) n_total += (double)x.numel;
+    const double n_act = total(kAccActive);
+    gxpo_diagnostics d{};
+    d.norm_g0 = std::sqrt(total(kAccG0Sq));
+    d.norm_g1 = std::sqrt(total(kAccG1Sq));
+    d.norm_g_slow = std::sqrt(total(kAccSlowSq));
+    d.cos_g0_g_slow = (ctx->cos_valid && d.norm_g0 > 0.0 && d.norm_g_slow > 0.0) ? total(kAccG0Slow) / (d.norm_g0 * d.norm_g_slow) : nan;
+    if (n_act > 0.0) {
+        const double mean_shifted = total(kAccR) / n_act;             // mean of r - 1
+        const double var = total(kAccR2) / n_act - mean_shifted * mean_shifted;
+        d.retention_mean = 1.0 + mean_shifted;
+        d.retention_std = std::sqrt(var > 0.0 ? var : 0.0);
+        d.scale_mean = total(kAccScale) / n_act;
+    } else {
+        d.retention_mean = d.retention_std = d.scale_mean = nan;
+    }
+    d.inactive_fraction = 1.0 - n_act / n_total;
+    d.displacement_ratio = total(kAccD2) > 0.0 ? std::sqrt(total(kAccDK) / total(kAccD2)) : nan;
+    d.t = ctx->diag_t;
+    *out = d;
     return GXPO_OK;
 }
 

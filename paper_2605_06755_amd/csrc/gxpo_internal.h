@@ -76,25 +76,50 @@ struct SegRec {             // a run of per-block partials inside one tensor
 
 enum { kSrcTheta = 0, kSrcProbe = 1 };
 
+// Reduction accumulators.  Each owns one XCD-major array of per-block partials,
+// `partial_pitch(n_blocks)` doubles apart.  Only kAccSlowSq exists unless the
+// context was created with diagnostics.
+enum {
+    kAccSlowSq = 0,    // sum g_slow^2                      (slow step)
+    kAccG0Slow = 1,    // sum g0 * g_slow                   (slow step, diagnostics)
+    kAccG0Sq = 2,      // sum g0^2                          (extrapolation pass, diagnostics; so are all below)
+    kAccG1Sq = 3,      // sum g1^2
+    kAccActive = 4,    // number of active coordinates
+    kAccR = 5,         // sum over the active set of (r - 1)
+    kAccR2 = 6,        // sum over the active set of (r - 1)^2
+    kAccScale = 7,     // sum over the active set of scale
+    kAccD2 = 8,        // sum (theta^{t,2} - theta^t)^2
+    kAccDK = 9,        // sum (theta^{t,K} - theta^t)^2
+    kNumAcc = 10
+};
+constexpr int kNumExtrapAcc = kNumAcc - kAccG0Sq;
+__host__ __device__ inline size_t partial_pitch(uint32_t n_blocks) { return (size_t)8 * ((n_blocks + 7u) >> 3); }
+
 // All launchers enqueue on `stream` and return the launch status.
+// d_partial: nullptr = no reduction; otherwise sum g^2 goes to accumulator kAccSlowSq and, when
+// d_g0_for_dot holds a list, sum g0*g to kAccG0Slow.
 hipError_t launch_step(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype,
                        const GradArg &d_grads, const StepParams &p,
-                       int src, int dst, int write_moments, int write_copy, double *d_partial, hipStream_t stream);
+                       int src, int dst, int write_moments, int write_copy, double *d_partial,
+                       const GradArg &d_g0_for_dot, hipStream_t stream);
 
+// d_diag_partial (both extrapolation launchers): nullptr, or the partial arrays; then the pass
+// also fills accumulators kAccG0Sq .. kAccDK.
 hipError_t launch_extrapolate(const Layout &L, uint32_t wpb, int grad_dtype,
                               const GradArg &d_g0, const GradArg &d_g1,
-                              const ExtrapParams &e, int write_copy, hipStream_t stream);
+                              const ExtrapParams &e, int write_copy, double *d_diag_partial, hipStream_t stream);
 
 // p1 / p2: constants of the first / second fast step (both are applied here).
 hipError_t launch_fused_steps_extrapolate(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype,
                                           const GradArg &d_g0, const GradArg &d_g1,
                                           const StepParams &p1, const StepParams &p2, const ExtrapParams &e,
-                                          int write_copy, hipStream_t stream);
+                                          int write_copy, double *d_diag_partial, hipStream_t stream);
 
-// result[0] = sum over all tensors, result[1 + t] = sum over tensor t.
+// Reduces accumulators [first_acc, first_acc + n_acc).  For accumulator a:
+// result[a * (1 + n_tensors)] = sum over all tensors, result[a * (1 + n_tensors) + 1 + t] = tensor t.
 hipError_t launch_finalize(const double *d_partial, uint32_t n_blocks, const SegRec *d_seg, uint32_t n_segs,
                            const uint32_t *d_tensor_seg_start, uint32_t n_tensors,
-                           double *d_seg_sum, double *d_result, hipStream_t stream);
+                           double *d_seg_sum, double *d_result, int first_acc, int n_acc, hipStream_t stream);
 
 hipError_t launch_stream_copy(void *dst, const void *src, uint64_t bytes, hipStream_t stream);
 

@@ -171,7 +171,13 @@ __device__ __forceinline__ float optim_update(float theta, float &m, float &v, f
 // g0 + g1 is rounded once from exact inputs, so the pole at r = -1 is approached
 // with full relative accuracy.  Off the active set, and at r == -1 where S_2
 // vanishes, the observed displacement is kept (scale = 1).
-__device__ __forceinline__ float extrap_scale(float g0, float g1, const ExtrapParams &e) {
+struct ScaleInfo {
+    float scale;     // the factor applied to the observed displacement
+    float r;         // retention ratio after the clamp (meaningful only when active)
+    bool active;     // |g0| > delta
+};
+
+__device__ __forceinline__ ScaleInfo extrap_scale_info(float g0, float g1, const ExtrapParams &e) {
     const float r = g1 / g0;
     const float rc = fminf(fmaxf(r, -e.r_max), e.r_max);
     const float x = rc * rc;
@@ -188,14 +194,65 @@ __device__ __forceinline__ float extrap_scale(float g0, float g1, const ExtrapPa
         const float den = clamped ? 1.0f + rc : g0 + g1;
         scale = fmaf(power, num / den, series);
     }
-    const bool use = (fabsf(g0) > e.delta) && (rc != -1.0f);
-    return use ? scale : 1.0f;
+    const bool active = fabsf(g0) > e.delta;
+    const bool use = active && (rc != -1.0f);
+    return ScaleInfo{use ? scale : 1.0f, rc, active};
 }
+
 
 __device__ __forceinline__ double wave_sum(double x) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
     return x;
+}
+
+// Adds the N per-lane values over the block and stores them as this block's
+// partials of accumulators first_acc .. first_acc + N - 1 (fixed order: lane
+// butterfly, then wavefronts in index order).
+template <int WPB, int N>
+__device__ __forceinline__ void store_block_sums(double (&acc)[N], double *__restrict__ partial, int first_acc, uint32_t n_blocks) {
+    const size_t pitch = partial_pitch(n_blocks);
+    const uint32_t slot = partial_slot(blockIdx.x, partial_stride(n_blocks));
+#pragma unroll
+    for (int a = 0; a < N; ++a) acc[a] = wave_sum(acc[a]);
+    if (WPB == 1) {
+        if (threadIdx.x == 0) {
+#pragma unroll
+            for (int a = 0; a < N; ++a) partial[(size_t)(first_acc + a) * pitch + slot] = acc[a];
+        }
+    } else {
+        __shared__ double wave_part[N][WPB];
+        if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+            for (int a = 0; a < N; ++a) wave_part[a][threadIdx.x >> 6] = acc[a];
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+#pragma unroll
+            for (int a = 0; a < N; ++a) {
+                double total = 0.0;
+#pragma unroll
+                for (int w = 0; w < WPB; ++w) total += wave_part[a][w];
+                partial[(size_t)(first_acc + a) * pitch + slot] = total;
+            }
+        }
+    }
+}
+
+// Per-lane contribution of one coordinate to the extrapolation-pass diagnostics.
+__device__ __forceinline__ void add_extrap_diag(double (&acc)[kNumExtrapAcc], float g0, float g1, const ScaleInfo &si, float disp2) {
+    acc[kAccG0Sq - kAccG0Sq] = fma((double)g0, (double)g0, acc[kAccG0Sq - kAccG0Sq]);
+    acc[kAccG1Sq - kAccG0Sq] = fma((double)g1, (double)g1, acc[kAccG1Sq - kAccG0Sq]);
+    if (si.active) {
+        const double rm1 = (double)(si.r - 1.0f);        // centred on the common case r ~ 1: no cancellation in the variance
+        acc[kAccActive - kAccG0Sq] += 1.0;
+        acc[kAccR - kAccG0Sq] += rm1;
+        acc[kAccR2 - kAccG0Sq] = fma(rm1, rm1, acc[kAccR2 - kAccG0Sq]);
+        acc[kAccScale - kAccG0Sq] += (double)si.scale;
+    }
+    const double d2 = (double)disp2, dK = (double)(si.scale * disp2);
+    acc[kAccD2 - kAccG0Sq] = fma(d2, d2, acc[kAccD2 - kAccG0Sq]);
+    acc[kAccDK - kAccG0Sq] = fma(dK, dK, acc[kAccDK - kAccG0Sq]);
 }
 
 // ============================================================================
@@ -210,7 +267,8 @@ __device__ __forceinline__ double wave_sum(double x) {
 // ============================================================================
 template <int WPB, int OPT, int GDT>
 __global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, GradArg grads, StepParams p, int src, int dst,
-                                                       int write_moments, int write_copy, double *__restrict__ partial) {
+                                                       int write_moments, int write_copy, double *__restrict__ partial,
+                                                       GradArg dot_with) {
     const Span s = locate<WPB>(L);
     const uint32_t elem = threadIdx.x * kLaneElems;
     const uint32_t bytes = s.cnt * 4u;
@@ -247,23 +305,19 @@ __global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, GradArg grads
     }
     if (partial) {
         // out-of-range lanes loaded g = 0 and add nothing
-        double acc = 0.0;
+        double acc[2] = {0.0, 0.0};
 #pragma unroll
-        for (int k = 0; k < 4; ++k) acc = fma((double)g[k], (double)g[k], acc);
-        acc = wave_sum(acc);
-        const uint32_t slot = partial_slot(blockIdx.x, partial_stride(L.n_blocks));
-        if (WPB == 1) {
-            if (threadIdx.x == 0) partial[slot] = acc;
+        for (int k = 0; k < 4; ++k) acc[0] = fma((double)g[k], (double)g[k], acc[0]);
+        const void *other = dot_with.single;
+        if (L.n_tensors > 1) other = dot_with.table ? dot_with.table[s.tensor] : nullptr;
+        if (other) {        // diagnostics: <g0, g_slow>, g0 re-read (+4 B/param)
+            const f32x4 o = load_grad<GDT>(grad_rsrc<GDT>(other, s.e0, s.cnt), elem, s.full);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) acc[1] = fma((double)o[k], (double)g[k], acc[1]);
+            store_block_sums<WPB, 2>(acc, partial, kAccSlowSq, L.n_blocks);
         } else {
-            __shared__ double wave_part[WPB];
-            if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = acc;
-            __syncthreads();
-            if (threadIdx.x == 0) {
-                double total = 0.0;
-#pragma unroll
-                for (int w = 0; w < WPB; ++w) total += wave_part[w];
-                partial[slot] = total;
-            }
+            double only[1] = {acc[0]};
+            store_block_sums<WPB, 1>(only, partial, kAccSlowSq, L.n_blocks);
         }
     }
 }
@@ -273,9 +327,9 @@ __global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, GradArg grads
 //   theta <- theta + alpha * scale * (theta_probe - theta)
 // 20 B/param with fp32 gradients (16 read, 4 written).
 // ============================================================================
-template <int WPB, int GDT>
+template <int WPB, int GDT, bool DIAG>
 __global__ __launch_bounds__(64 * WPB) void k_extrapolate(Layout L, GradArg g0s, GradArg g1s, ExtrapParams e,
-                                                        int write_copy) {
+                                                        int write_copy, double *__restrict__ diag_partial) {
     const Span s = locate<WPB>(L);
     const uint32_t elem = threadIdx.x * kLaneElems;
     const uint32_t bytes = s.cnt * 4u;
@@ -287,16 +341,20 @@ __global__ __launch_bounds__(64 * WPB) void k_extrapolate(Layout L, GradArg g0s,
     f32x4 th2 = load_f32(r_pr, elem, s.full);
     f32x4 g0 = load_grad<GDT>(r_g0, elem, s.full);
     f32x4 g1 = load_grad<GDT>(r_g1, elem, s.full);
+    double diag[kNumExtrapAcc] = {};
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        const float scale = extrap_scale(g0[k], g1[k], e);
-        th0[k] = fmaf(e.alpha * scale, th2[k] - th0[k], th0[k]);
+        const ScaleInfo si = extrap_scale_info(g0[k], g1[k], e);
+        const float disp2 = th2[k] - th0[k];
+        if (DIAG) add_extrap_diag(diag, g0[k], g1[k], si, disp2);
+        th0[k] = fmaf(e.alpha * si.scale, disp2, th0[k]);
     }
     store_f32(r_th, elem, s.full, th0);
     if (write_copy && s.rec.copy) {
         const auto r_c = span_rsrc((unsigned short *)s.rec.copy + s.e0, s.cnt * 2u);
         store_bf16(r_c, elem, s.full, th0);
     }
+    if (DIAG) store_block_sums<WPB, kNumExtrapAcc>(diag, diag_partial, kAccG0Sq, L.n_blocks);
 }
 
 // ============================================================================
@@ -314,9 +372,10 @@ __global__ __launch_bounds__(64 * WPB) void k_extrapolate(Layout L, GradArg g0s,
 // write and re-read of m, v (16 B) and the re-read of theta^{t,1} (4 B):
 // 32 B/param with fp32 gradients (20 read, 12 written).
 // ============================================================================
-template <int WPB, int OPT, int GDT>
+template <int WPB, int OPT, int GDT, bool DIAG>
 __global__ __launch_bounds__(64 * WPB) void k_fused_steps_extrapolate(Layout L, GradArg g0s, GradArg g1s, StepParams p1,
-                                                                    StepParams p2, ExtrapParams e, int write_copy) {
+                                                                    StepParams p2, ExtrapParams e, int write_copy,
+                                                                    double *__restrict__ diag_partial) {
     const Span s = locate<WPB>(L);
     const uint32_t elem = threadIdx.x * kLaneElems;
     const uint32_t bytes = s.cnt * 4u;
@@ -334,6 +393,7 @@ __global__ __launch_bounds__(64 * WPB) void k_fused_steps_extrapolate(Layout L, 
         v = load_f32(r_v, elem, s.full);
     }
     f32x4 g1 = load_grad<GDT>(r_g1, elem, s.full);
+    double diag[kNumExtrapAcc] = {};
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         float mk = m[k], vk = v[k];
@@ -342,8 +402,9 @@ __global__ __launch_bounds__(64 * WPB) void k_fused_steps_extrapolate(Layout L, 
         m[k] = mk;
         v[k] = vk;
         const float disp2 = (th1 - th0[k]) - upd2;                // theta^{t,2} - theta^t
-        const float scale = extrap_scale(g0[k], g1[k], e);
-        th0[k] = fmaf(e.alpha * scale, disp2, th0[k]);
+        const ScaleInfo si = extrap_scale_info(g0[k], g1[k], e);
+        if (DIAG) add_extrap_diag(diag, g0[k], g1[k], si, disp2);
+        th0[k] = fmaf(e.alpha * si.scale, disp2, th0[k]);
     }
     store_f32(r_th, elem, s.full, th0);
     if (OPT == 1) {
@@ -354,6 +415,7 @@ __global__ __launch_bounds__(64 * WPB) void k_fused_steps_extrapolate(Layout L, 
         const auto r_c = span_rsrc((unsigned short *)s.rec.copy + s.e0, s.cnt * 2u);
         store_bf16(r_c, elem, s.full, th0);
     }
+    if (DIAG) store_block_sums<WPB, kNumExtrapAcc>(diag, diag_partial, kAccG0Sq, L.n_blocks);
 }
 
 // ============================================================================
@@ -365,8 +427,12 @@ __global__ __launch_bounds__(64 * WPB) void k_fused_steps_extrapolate(Layout L, 
 // ============================================================================
 constexpr int kFinalThreads = 256;
 
-__global__ __launch_bounds__(kFinalThreads) void k_reduce_runs(const double *__restrict__ partial, uint32_t stride,
-                                                             const SegRec *__restrict__ seg, double *__restrict__ seg_sum) {
+__global__ __launch_bounds__(kFinalThreads) void k_reduce_runs(const double *__restrict__ partial_all, uint32_t n_blocks, int first_acc,
+                                                             const SegRec *__restrict__ seg, double *__restrict__ seg_sum_all) {
+    // blockIdx.x: run, blockIdx.y: accumulator
+    const uint32_t stride = partial_stride(n_blocks);
+    const double *partial = partial_all + (size_t)(first_acc + blockIdx.y) * partial_pitch(n_blocks);
+    double *seg_sum = seg_sum_all + (size_t)(first_acc + blockIdx.y) * gridDim.x;
     const SegRec sr = seg[blockIdx.x];
     double acc = 0.0;
     for (uint32_t i = threadIdx.x; i < sr.count; i += kFinalThreads) acc += partial[partial_slot(sr.first + i, stride)];
@@ -382,9 +448,12 @@ __global__ __launch_bounds__(kFinalThreads) void k_reduce_runs(const double *__r
     }
 }
 
-__global__ __launch_bounds__(kFinalThreads) void k_reduce_tensors(const double *__restrict__ seg_sum,
+__global__ __launch_bounds__(kFinalThreads) void k_reduce_tensors(const double *__restrict__ seg_sum_all, uint32_t n_segs, int first_acc,
                                                                 const uint32_t *__restrict__ tensor_seg_start, uint32_t n_tensors,
-                                                                double *__restrict__ result) {
+                                                                double *__restrict__ result_all) {
+    // blockIdx.x: accumulator
+    const double *seg_sum = seg_sum_all + (size_t)(first_acc + blockIdx.x) * n_segs;
+    double *result = result_all + (size_t)(first_acc + blockIdx.x) * (1 + n_tensors);
     // one wavefront per tensor at a time: lane l adds runs l, l + 64, ... in order, then a butterfly
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     for (uint32_t t = wave; t < n_tensors; t += kFinalThreads / 64) {
@@ -418,32 +487,33 @@ __global__ __launch_bounds__(64) void k_stream_copy(const float *__restrict__ sr
 
 template <int WPB>
 hipError_t step_wpb(const Layout &L, int optimizer, int grad_dtype, const GradArg &g, const StepParams &p, int src, int dst,
-                    int write_moments, int write_copy, double *partial, hipStream_t st) {
+                    int write_moments, int write_copy, double *partial, const GradArg &dot, hipStream_t st) {
     const dim3 grid(L.n_blocks), block(64 * WPB);
-    if (optimizer == 0 && grad_dtype == 0) k_optim_step<WPB, 0, 0><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial);
-    else if (optimizer == 0) k_optim_step<WPB, 0, 1><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial);
-    else if (grad_dtype == 0) k_optim_step<WPB, 1, 0><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial);
-    else k_optim_step<WPB, 1, 1><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial);
+    if (optimizer == 0 && grad_dtype == 0) k_optim_step<WPB, 0, 0><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial, dot);
+    else if (optimizer == 0) k_optim_step<WPB, 0, 1><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial, dot);
+    else if (grad_dtype == 0) k_optim_step<WPB, 1, 0><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial, dot);
+    else k_optim_step<WPB, 1, 1><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial, dot);
     return hipGetLastError();
 }
 
-template <int WPB>
+template <int WPB, bool DIAG>
 hipError_t extrap_wpb(const Layout &L, int grad_dtype, const GradArg &g0, const GradArg &g1, const ExtrapParams &e,
-                      int write_copy, hipStream_t st) {
+                      int write_copy, double *diag, hipStream_t st) {
     const dim3 grid(L.n_blocks), block(64 * WPB);
-    if (grad_dtype == 0) k_extrapolate<WPB, 0><<<grid, block, 0, st>>>(L, g0, g1, e, write_copy);
-    else k_extrapolate<WPB, 1><<<grid, block, 0, st>>>(L, g0, g1, e, write_copy);
+    if (grad_dtype == 0) k_extrapolate<WPB, 0, DIAG><<<grid, block, 0, st>>>(L, g0, g1, e, write_copy, diag);
+    else k_extrapolate<WPB, 1, DIAG><<<grid, block, 0, st>>>(L, g0, g1, e, write_copy, diag);
     return hipGetLastError();
 }
 
-template <int WPB>
+template <int WPB, bool DIAG>
 hipError_t fused_wpb(const Layout &L, int optimizer, int grad_dtype, const GradArg &g0, const GradArg &g1,
-                     const StepParams &p1, const StepParams &p2, const ExtrapParams &e, int write_copy, hipStream_t st) {
+                     const StepParams &p1, const StepParams &p2, const ExtrapParams &e, int write_copy, double *diag,
+                     hipStream_t st) {
     const dim3 grid(L.n_blocks), block(64 * WPB);
-    if (optimizer == 0 && grad_dtype == 0) k_fused_steps_extrapolate<WPB, 0, 0><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy);
-    else if (optimizer == 0) k_fused_steps_extrapolate<WPB, 0, 1><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy);
-    else if (grad_dtype == 0) k_fused_steps_extrapolate<WPB, 1, 0><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy);
-    else k_fused_steps_extrapolate<WPB, 1, 1><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy);
+    if (optimizer == 0 && grad_dtype == 0) k_fused_steps_extrapolate<WPB, 0, 0, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag);
+    else if (optimizer == 0) k_fused_steps_extrapolate<WPB, 0, 1, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag);
+    else if (grad_dtype == 0) k_fused_steps_extrapolate<WPB, 1, 0, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag);
+    else k_fused_steps_extrapolate<WPB, 1, 1, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag);
     return hipGetLastError();
 }
 
@@ -451,43 +521,52 @@ hipError_t fused_wpb(const Layout &L, int optimizer, int grad_dtype, const GradA
 
 hipError_t launch_step(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype, const GradArg &d_grads,
                        const StepParams &p, int src, int dst, int write_moments, int write_copy, double *d_partial,
-                       hipStream_t stream) {
+                       const GradArg &d_g0_for_dot, hipStream_t stream) {
     switch (wpb) {
-        case 1: return step_wpb<1>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_moments, write_copy, d_partial, stream);
-        case 2: return step_wpb<2>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_moments, write_copy, d_partial, stream);
-        case 4: return step_wpb<4>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_moments, write_copy, d_partial, stream);
+        case 1: return step_wpb<1>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_moments, write_copy, d_partial, d_g0_for_dot, stream);
+        case 2: return step_wpb<2>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_moments, write_copy, d_partial, d_g0_for_dot, stream);
+        case 4: return step_wpb<4>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_moments, write_copy, d_partial, d_g0_for_dot, stream);
     }
     return hipErrorInvalidValue;
 }
 
 hipError_t launch_extrapolate(const Layout &L, uint32_t wpb, int grad_dtype, const GradArg &d_g0, const GradArg &d_g1,
-                              const ExtrapParams &e, int write_copy, hipStream_t stream) {
+                              const ExtrapParams &e, int write_copy, double *d_diag_partial, hipStream_t stream) {
+    const bool diag = d_diag_partial != nullptr;
     switch (wpb) {
-        case 1: return extrap_wpb<1>(L, grad_dtype, d_g0, d_g1, e, write_copy, stream);
-        case 2: return extrap_wpb<2>(L, grad_dtype, d_g0, d_g1, e, write_copy, stream);
-        case 4: return extrap_wpb<4>(L, grad_dtype, d_g0, d_g1, e, write_copy, stream);
+        case 1: return diag ? extrap_wpb<1, true>(L, grad_dtype, d_g0, d_g1, e, write_copy, d_diag_partial, stream)
+                            : extrap_wpb<1, false>(L, grad_dtype, d_g0, d_g1, e, write_copy, nullptr, stream);
+        case 2: return diag ? extrap_wpb<2, true>(L, grad_dtype, d_g0, d_g1, e, write_copy, d_diag_partial, stream)
+                            : extrap_wpb<2, false>(L, grad_dtype, d_g0, d_g1, e, write_copy, nullptr, stream);
+        case 4: return diag ? extrap_wpb<4, true>(L, grad_dtype, d_g0, d_g1, e, write_copy, d_diag_partial, stream)
+                            : extrap_wpb<4, false>(L, grad_dtype, d_g0, d_g1, e, write_copy, nullptr, stream);
     }
     return hipErrorInvalidValue;
 }
 
 hipError_t launch_fused_steps_extrapolate(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype, const GradArg &d_g0,
                                           const GradArg &d_g1, const StepParams &p1, const StepParams &p2,
-                                          const ExtrapParams &e, int write_copy, hipStream_t stream) {
+                                          const ExtrapParams &e, int write_copy, double *d_diag_partial, hipStream_t stream) {
+    const bool diag = d_diag_partial != nullptr;
     switch (wpb) {
-        case 1: return fused_wpb<1>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, stream);
-        case 2: return fused_wpb<2>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, stream);
-        case 4: return fused_wpb<4>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, stream);
+        case 1: return diag ? fused_wpb<1, true>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, d_diag_partial, stream)
+                            : fused_wpb<1, false>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, nullptr, stream);
+        case 2: return diag ? fused_wpb<2, true>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, d_diag_partial, stream)
+                            : fused_wpb<2, false>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, nullptr, stream);
+        case 4: return diag ? fused_wpb<4, true>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, d_diag_partial, stream)
+                            : fused_wpb<4, false>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, nullptr, stream);
     }
     return hipErrorInvalidValue;
 }
 
 hipError_t launch_finalize(const double *d_partial, uint32_t n_blocks, const SegRec *d_seg, uint32_t n_segs,
                            const uint32_t *d_tensor_seg_start, uint32_t n_tensors, double *d_seg_sum, double *d_result,
-                           hipStream_t stream) {
-    k_reduce_runs<<<dim3(n_segs), dim3(kFinalThreads), 0, stream>>>(d_partial, partial_stride(n_blocks), d_seg, d_seg_sum);
+                           int first_acc, int n_acc, hipStream_t stream) {
+    k_reduce_runs<<<dim3(n_segs, n_acc), dim3(kFinalThreads), 0, stream>>>(d_partial, n_blocks, first_acc, d_seg, d_seg_sum);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    k_reduce_tensors<<<dim3(1), dim3(kFinalThreads), 0, stream>>>(d_seg_sum, d_tensor_seg_start, n_tensors, d_result);
+    k_reduce_tensors<<<dim3(n_acc), dim3(kFinalThreads), 0, stream>>>(d_seg_sum, n_segs, first_acc, d_tensor_seg_start, n_tensors,
+                                                                      d_result);
     return hipGetLastError();
 }
 

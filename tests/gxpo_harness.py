@@ -231,8 +231,29 @@ def lockstep_active_step(ctx: B.Context, dev: DeviceState, orc: O.GXPOOracle, gr
         assert abs(info.z - ref_info.z) <= 1e-6 * max(1.0, abs(ref_info.z)), f"{what}: Z {info.z!r} vs {ref_info.z!r}"
     assert bool(info.tripped) == ref_info.tripped
     assert (info.s_star if info.s_star >= 0 else None) == ref_info.s_star
+    if ctx.cfg.diagnostics:
+        check_diagnostics(B.gxpo_get_diagnostics(ctx), orc.diagnostics(), aliased=any(a.data_ptr() == b.data_ptr() for a, b in zip(g0b, gsb)),
+                          what=what)
     dev.check_canaries()
     return info, ref_info
+
+
+def check_diagnostics(got, ref: dict, aliased: bool, what: str = ""):
+    """Engine diagnostics against the oracle's.  The sums are fp64 on both sides; what differs
+    is that the engine forms r, scale and the displacements in fp32."""
+    def close(name, rel, abs_=0.0):
+        a, b = getattr(got, name), ref[name]
+        assert abs(a - b) <= rel * abs(b) + abs_, f"{what}: {name} {a!r} vs oracle {b!r}"
+    close("norm_g0", 1e-12); close("norm_g1", 1e-12); close("norm_g_slow", 1e-12)
+    if aliased:
+        assert math.isnan(got.cos_g0_g_slow), f"{what}: cosine must be NaN when g_slow overwrote g0"
+    else:
+        close("cos_g0_g_slow", 1e-10, 1e-12)
+    close("inactive_fraction", 1e-12, 1e-15)
+    close("retention_mean", 1e-6)
+    close("retention_std", 1e-4, 1e-9)
+    close("scale_mean", 1e-5)
+    close("displacement_ratio", 1e-4)
 
 
 class pytest_approx:

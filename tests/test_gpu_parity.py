@@ -212,6 +212,68 @@ def test_broad_retention_spread_with_clamp(K):
 
 
 # ---------------------------------------------------------------------------------------------
+# mechanism diagnostics (appendix table of active-phase diagnostics), fused into the passes
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("fused", [True, False])
+@pytest.mark.parametrize("grad_dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("wpb", [0, 4])
+def test_mechanism_diagnostics_policy_like(fused, grad_dtype, wpb):
+    numels = RAGGED
+    problem = synth.policy_problem(sum(numels), seed=21, sigma=0.05, device="cuda")
+    cfg = B.make_config(grad_dtype=grad_dtype, K=5, alpha=0.5, delta=1.75e-3, lr=1e-4, fuse_step2=fused, gate_min_count=2,
+                        waves_per_block=wpb, diagnostics=True)
+    dev, ctx, orc, grads = build(numels, cfg, problem)
+    step_id = [0]
+    grad_fn = quad_trainer(problem, numels, step_noise=lambda: synth.step_noise(problem, step_id[0]))
+    with pytest.raises(B.GxpoError):
+        B.gxpo_get_diagnostics(ctx)                      # nothing to report yet
+    for step in range(3):
+        step_id[0] = step
+        H.lockstep_active_step(ctx, dev, orc, grad_fn, grads, dtol=1e-4, fused=fused, what=f"diag step {step}")
+    d = B.gxpo_get_diagnostics(ctx)
+    assert d.t == 2 and 0.01 < d.inactive_fraction < 0.06 and 0.9 < d.cos_g0_g_slow <= 1.0
+    # the trainer may hand g_slow in in g0's buffers; the cosine is then reported as NaN
+    H.lockstep_active_step(ctx, dev, orc, grad_fn, (grads[0], grads[1], grads[0]), dtol=1e-4, fused=fused, what="aliased")
+
+
+def test_mechanism_diagnostics_broad_ratios_and_surrogate():
+    # broad, clamped ratios
+    numels = [60000, 333]
+    problem = synth.policy_problem(sum(numels), seed=22, sigma=0.05, device="cuda")
+    cfg = B.make_config(K=4, alpha=0.5, delta=1.75e-3, r_max=2.0, lr=1e-4, gate_min_count=2, diagnostics=True)
+    dev, ctx, orc, grads = build(numels, cfg, problem)
+    call = [0]
+
+    def noise():
+        call[0] += 1
+        return 0.5 * synth.step_noise(problem, 100) + math.sqrt(0.75) * synth.step_noise(problem, 200 + call[0])
+    H.lockstep_active_step(ctx, dev, orc, quad_trainer(problem, numels, step_noise=noise), grads, dtol=1e-4, fused=True, what="broad")
+    d = B.gxpo_get_diagnostics(ctx)
+    assert d.retention_std > 0.5
+    # plain-GD surrogate: every statistic has a closed form (r_i = 1 - eta h_i)
+    P, eta, K = 1 << 18, 0.1, 4
+    problem = synth.surrogate_problem(P, 0, device="cuda")
+    cfg = B.make_config(optimizer="gd", K=K, alpha=1.0, delta=0.0, lr=eta, diagnostics=True)
+    dev, ctx, orc, grads = build([P], cfg, problem)
+    H.lockstep_active_step(ctx, dev, orc, quad_trainer(problem, [P]), grads, dtol=1e-5, fused=True, what="surrogate diag")
+    d = B.gxpo_get_diagnostics(ctx)
+    rho = 1 - eta * H.f64(problem.h)
+    S = lambda n: sum(rho ** j for j in range(n))
+    assert d.retention_mean == pytest.approx(float(np.mean(rho)), rel=1e-6)
+    assert d.retention_std == pytest.approx(float(np.std(rho)), rel=1e-5)
+    assert d.scale_mean == pytest.approx(float(np.mean(S(K) / S(2))), rel=1e-6)
+    assert d.inactive_fraction == 0.0
+
+
+def test_diagnostics_are_refused_without_the_flag():
+    problem = synth.policy_problem(1000, seed=3, device="cuda")
+    dev, ctx, orc, grads = build([1000], B.make_config(), problem)
+    with pytest.raises(B.GxpoError) as e:
+        B.gxpo_get_diagnostics(ctx)
+    assert e.value.code == B.GXPO_ERR_BAD_STATE
+
+
+# ---------------------------------------------------------------------------------------------
 # gate transition and fallback (config 5 at reduced size)
 # ---------------------------------------------------------------------------------------------
 def test_gate_transition_free_running_and_fallback():
