@@ -32,7 +32,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "lora"])
     ap.add_argument("--waves-per-block", type=int, default=0)
     ap.add_argument("--unfused", action="store_true", help="run the second fast step and the extrapolation as two passes")
     ap.add_argument("--same-phase", action="store_true", help="plain torch allocations instead of the phased HBM layout")
@@ -68,6 +68,10 @@ def workload_spec(name: str):
         return dict(label="gate-transition buffer, flat fp32, P=3.2e9, AdamW; active and fallback steps",
                     layout=[("flat", synth.GATE_STRESS_PARAMS)], optimizer="adamw", grad_dtype="f32", copy=False, seed=4,
                     cfg=dict(K=8, alpha=0.5, delta=1.75e-3, lr=1e-6))
+    if name == "lora":
+        return dict(label="LoRA rank-128 adapters on q,k,v,o of a Qwen2.5-7B-shaped model: 224 small tensors, P=8.07e7",
+                    layout=synth.qwen25_7b_lora_layout(), optimizer="adamw", grad_dtype="f32", copy=False, seed=5,
+                    cfg=dict(K=10, alpha=0.5, delta=1.75e-3, lr=1e-6))
     raise ValueError(name)
 
 
@@ -167,6 +171,9 @@ def main():
     B.gxpo_slow_step(ctx, gs)
     live_info = B.gxpo_gate(ctx)
 
+    # the gradient buffers are the same every step: marshal their pointer lists once
+    g0, g1, gs = B.GradList(ctx, g0), B.GradList(ctx, g1), B.GradList(ctx, gs)
+
     def active_step(events=None):
         calls = (("fast_step_1", lambda: B.gxpo_fast_steps(ctx, 0, g0)),
                  ("fast_step_2", lambda: B.gxpo_fast_steps(ctx, 1, g1)),
@@ -247,8 +254,8 @@ def main():
     if not args.no_cpu_baseline:
         # sampled only now, after every GPU measurement: large device-to-host copies ahead of
         # the timed region were seen to cost the following kernels a few percent
-        cpu_inputs = {"theta": views["theta"][0][:S].cpu(), "g0": g0[0][:S].cpu(), "g1": g1[0][:S].cpu(),
-                      "gs": gs[0][:S].cpu()}
+        cpu_inputs = {"theta": views["theta"][0][:S].cpu(), "g0": g0.tensors[0][:S].cpu(), "g1": g1.tensors[0][:S].cpu(),
+                      "gs": gs.tensors[0][:S].cpu()}
         cpu_baseline = time_oracle(spec, cfg, cpu_inputs, S)
 
     out = {
@@ -264,7 +271,7 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"configs[{int(args.workload[1]) - 1}]: {spec['label']}", "params": P,
+        "config": {"workload": (f"configs[{int(args.workload[1]) - 1}]: " if args.workload[0] == "c" else "") + spec["label"], "params": P,
                    "tensors": len(numels), "grad_dtype": spec["grad_dtype"], "fused_step2": fused,
                    "waves_per_block": args.waves_per_block or 1, "hbm_layout": "same-phase" if args.same_phase else "moments +32KiB mod 64KiB", "bytes_per_param_per_step": sum(bpp[k] for k in kernel_ms)},
         "hbm_gbps_step": round(step_bytes / ms_per_step / 1e6, 1),

@@ -186,7 +186,12 @@ class Context:
         except Exception:
             pass
 
-    def _grad_list(self, grads: Sequence[torch.Tensor], role: str):
+    def _grad_list(self, grads, role: str):
+        if isinstance(grads, GradList):
+            if grads.ctx is not self:
+                raise ValueError("this GradList was prepared for another context")
+            self._last_grads[role] = grads
+            return grads.array
         if len(grads) != self.n_tensors:
             raise ValueError(f"expected {self.n_tensors} gradient tensors, got {len(grads)}")
         arr = (ctypes.c_void_p * self.n_tensors)(*[_dev_ptr(g, self._grad_dtype, n) for g, n in zip(grads, self._numels)])
@@ -196,6 +201,17 @@ class Context:
     def _check(self, rc: int):
         if rc != GXPO_OK:
             raise GxpoError(rc, _lib.gxpo_last_error(self.handle).decode())
+
+
+class GradList:
+    """A gradient list marshalled once (pointer array built and checked), for callers that
+    hand the same buffers in every step: with hundreds of small tensors, rebuilding the
+    pointer array in Python on every call costs more than the kernels."""
+
+    def __init__(self, ctx: Context, grads: Sequence[torch.Tensor]):
+        self.ctx = ctx
+        self.tensors = list(grads)
+        self.array = ctx._grad_list(self.tensors, "prepared")
 
 
 def gxpo_init(cfg: gxpo_config, tensors: Sequence[dict]) -> Context:

@@ -59,6 +59,19 @@ def llama31_8b_layout() -> List[Tuple[str, int]]:
     return out
 
 
+def qwen25_7b_lora_layout(rank: int = 128) -> List[Tuple[str, int]]:
+    """(name, numel) of rank-`rank` LoRA adapters on the q, k, v, o projections of a
+    Qwen2.5-7B-shaped model (hidden 3584, 28 layers, 28 query heads and 4 key/value heads
+    of dimension 128): 224 small tensors, 80,740,352 parameters at rank 128."""
+    hidden, kv = 3584, 4 * 128
+    out = []
+    for layer in range(28):
+        for proj, d_out in (("q", hidden), ("k", kv), ("v", kv), ("o", hidden)):
+            out.append((f"layers.{layer}.{proj}_proj.lora_A", rank * hidden))
+            out.append((f"layers.{layer}.{proj}_proj.lora_B", d_out * rank))
+    return out
+
+
 def scaled_layout(layout: List[Tuple[str, int]], divisor: int, multiple: int = 1) -> List[Tuple[str, int]]:
     """Same tensor list with every numel divided (floor, at least 1, then
     rounded down to `multiple` when that leaves something): keeps the ragged

@@ -73,7 +73,7 @@ def gather(flat, windows):
     return H.f64(flat[idx])
 
 
-def run_sampled_active_step(spec_layout, *, seed, grad_dtype, with_copy, n_random, step_index=0):
+def run_sampled_active_step(spec_layout, *, seed, grad_dtype, with_copy, n_random, step_index=0, K=8, alpha=0.5):
     dev = torch.device("cuda:0")
     numels = [n for _, n in spec_layout]
     padded = synth.padded_numel(spec_layout, 4)
@@ -83,7 +83,7 @@ def run_sampled_active_step(spec_layout, *, seed, grad_dtype, with_copy, n_rando
     g0, g1, gs = (synth.split_like(g, spec_layout, 4) for g in gflat)
     quad = synth.ChunkedQuadratic(padded, seed, 0.05, device=dev)
     quad.init_theta(flat["theta"])
-    cfg = B.make_config(grad_dtype=grad_dtype, K=8, alpha=0.5, delta=1.75e-3, lr=1e-6, weight_decay=0.01,
+    cfg = B.make_config(grad_dtype=grad_dtype, K=K, alpha=alpha, delta=1.75e-3, lr=1e-6, weight_decay=0.01,
                         tau=3.0, window=10, fuse_step2=True, copy_mask=7)
     ctx = B.gxpo_init(cfg, [{k: views[k][i] for k in views} for i in range(len(numels))])
     rng = np.random.default_rng(seed)
@@ -166,6 +166,15 @@ def test_config4_llama_8b_ragged_bf16_grads_full_size():
     layout = synth.llama31_8b_layout()
     assert len(layout) == 290 and sum(n for _, n in layout) == 8_030_257_152
     run_sampled_active_step(layout, seed=3, grad_dtype="bf16", with_copy=False, n_random=300)
+
+
+@pytest.mark.parametrize("K,alpha", [(3, 0.1), (5, 1.0), (10, 0.5)])
+def test_lora_shaped_many_small_tensors_paper_grid(K, alpha):
+    """224 rank-128 adapter tensors (the paper's Qwen2.5-7B runs train LoRA adapters on q, k, v, o),
+    at the paper's own lookahead depths and reposition strengths."""
+    layout = synth.qwen25_7b_lora_layout()
+    assert len(layout) == 224 and sum(n for _, n in layout) == 80_740_352
+    run_sampled_active_step(layout, seed=5, grad_dtype="f32", with_copy=False, n_random=200, K=K, alpha=alpha)
 
 
 def test_config5_gate_transition_full_size():

@@ -98,7 +98,7 @@ def test_adamw_ragged_lockstep(fused, grad_dtype, wpb):
 
 
 @pytest.mark.parametrize("K", [2, 3, 5, 10])
-@pytest.mark.parametrize("alpha", [0.0, 0.1, 1.0])
+@pytest.mark.parametrize("alpha", [0.0, 0.1, 0.5, 1.0])
 def test_paper_K_alpha_grid(K, alpha):
     numels = [70001, 513]
     problem = synth.policy_problem(sum(numels), seed=5, sigma=0.05, device="cuda")
