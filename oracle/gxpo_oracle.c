@@ -180,6 +180,21 @@ double gxpo_oracle_sum_squares(int64_t n, const double *g)
 }
 
 /* ------------------------------------------------------------------------
+ * Global-norm gradient clipping (Section 3.1 lists "gradient clipping at 1.0"
+ * among the training settings and says nothing more).  READING: the widely
+ * used rule -- every gradient handed to an OptimStep is multiplied by
+ *     c = min(1, max_norm / (||g||_2 + 1e-6)),
+ * the norm taken over all tensors of that gradient.  max_norm <= 0 disables it.
+ * ---------------------------------------------------------------------- */
+double gxpo_oracle_clip_coefficient(double total_norm, double max_norm)
+{
+    if (!(max_norm > 0.0))
+        return 1.0;
+    double c = max_norm / (total_norm + 1e-6);
+    return c < 1.0 ? c : 1.0;
+}
+
+/* ------------------------------------------------------------------------
  * Mechanism diagnostics of one active step: the quantities of the paper's
  * appendix table "Active-phase GXPO diagnostics" (gradient norms,
  * cos(g0, g_slow), retention ratio mean and deviation over the active set,

@@ -78,6 +78,8 @@ def _load():
         ctypes.c_double, ctypes.c_double, _dp, _dp, _dp]
     lib.gxpo_oracle_sum_squares.restype = ctypes.c_double
     lib.gxpo_oracle_sum_squares.argtypes = [ctypes.c_int64, _dp]
+    lib.gxpo_oracle_clip_coefficient.restype = ctypes.c_double
+    lib.gxpo_oracle_clip_coefficient.argtypes = [ctypes.c_double, ctypes.c_double]
     lib.gxpo_oracle_diagnostic_sums.restype = None
     lib.gxpo_oracle_diagnostic_sums.argtypes = [
         ctypes.c_int64, _dp, _dp, _dp, _dp, _dp, ctypes.c_int, ctypes.c_double, ctypes.c_double, ctypes.c_double, _dp]
@@ -160,6 +162,15 @@ def extrapolate(theta_0, theta_2, g0, g1, K: int, alpha: float, delta: float,
 def sum_squares(g) -> float:
     g = _f64(g).ravel()
     return _load().gxpo_oracle_sum_squares(g.size, _p(g))
+
+
+def clip_gradients(grads, max_norm: float):
+    """Global-norm clipping of one gradient (a list of tensors): returns
+    (clipped list, total norm before clipping, coefficient)."""
+    arrs = [_f64(g).ravel() for g in grads]
+    total = math.sqrt(math.fsum(sum_squares(a) for a in arrs))
+    c = _load().gxpo_oracle_clip_coefficient(total, float(max_norm))
+    return [a * c for a in arrs], total, c
 
 
 def diagnostics(theta_0s, theta_2s, g0s, g1s, g_slows, K: int, delta: float, r_max: float = math.inf) -> dict:
@@ -299,6 +310,7 @@ class GXPOConfig:
     alpha: float = 0.5
     delta: float = 1e-8
     r_max: float = math.inf
+    clip_norm: float = 0.0          # 0 = no clipping
     gate: GateConfig = field(default_factory=GateConfig)
 
 
@@ -355,20 +367,25 @@ class GXPOOracle:
         assert self.is_active()
         self.backward_passes += 1
         self._theta_0 = [t.copy() for t in self.theta]
-        self._theta_1 = self._optim_all(self._theta_0, g0)
+        self._g0_used, self.norm_g0_raw, _ = clip_gradients(g0, self.cfg.clip_norm)
+        self._theta_1 = self._optim_all(self._theta_0, self._g0_used)
         return self._theta_1
 
     def fast_step_2(self, g1):
         """theta^{t,2} = OptimStep(theta^{t,1}, g^{t,1})."""
         self.backward_passes += 1
-        self._theta_2 = self._optim_all(self._theta_1, g1)
+        self._g1_used, self.norm_g1_raw, _ = clip_gradients(g1, self.cfg.clip_norm)
+        self._theta_2 = self._optim_all(self._theta_1, self._g1_used)
         return self._theta_2
 
     def extrapolate(self, g0, g1):
-        """Active set, ratio, scale, theta^{t,K}, theta~^t."""
+        """Active set, ratio, scale, theta^{t,K}, theta~^t.  READING: with clipping the ratio
+        is formed from the gradients the two fast steps consumed, i.e. after clipping."""
         c = self.cfg
         self._g0 = [_f64(g).ravel() for g in g0]
         self._g1 = [_f64(g).ravel() for g in g1]
+        if c.clip_norm > 0:
+            g0, g1 = self._g0_used, self._g1_used
         self.scale, self.theta_K, self.theta_tilde = [], [], []
         for th0, th2, a, b in zip(self._theta_0, self._theta_2, g0, g1):
             s, tk, tt = extrapolate(th0, th2, a, b, c.K, c.alpha, c.delta, c.r_max)
@@ -380,9 +397,10 @@ class GXPOOracle:
     def slow_step(self, g_slow):
         """theta^{t+1} = OptimStep(theta~^t, g_slow); records sum g_slow^2 per tensor."""
         self.backward_passes += 1
-        self._sumsq = [sum_squares(g) for g in g_slow]
+        self._sumsq = [sum_squares(g) for g in g_slow]        # the gate sees the norm before clipping
         self._g_slow = [_f64(g).ravel() for g in g_slow]
-        self.theta = self._optim_all(self.theta_tilde, g_slow)
+        used, _, _ = clip_gradients(g_slow, self.cfg.clip_norm)
+        self.theta = self._optim_all(self.theta_tilde, used)
         return self.theta
 
     def diagnostics(self) -> dict:
@@ -405,7 +423,8 @@ class GXPOOracle:
         """theta^{t+1} = OptimStep(theta^t, g^{t,0}); single-pass GRPO update."""
         assert not self.is_active()
         self.backward_passes += 1
-        self.theta = self._optim_all(self.theta, g0)
+        used, _, _ = clip_gradients(g0, self.cfg.clip_norm)
+        self.theta = self._optim_all(self.theta, used)
         self.t += 1
         return self.theta
 

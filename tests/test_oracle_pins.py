@@ -547,3 +547,42 @@ def test_diagnostics_closed_forms_on_the_diagonal_surrogate():
     gK = rho ** K * g0
     assert d["norm_g_slow"] == pytest.approx(np.linalg.norm(gK), rel=1e-11)
     assert d["cos_g0_g_slow"] == pytest.approx(np.dot(g0, gK) / np.linalg.norm(g0) / np.linalg.norm(gK), rel=1e-11)
+
+
+# ---------------------------------------------------------------------------
+# 8. Global-norm gradient clipping against the library routine
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("max_norm,scale", [(1.0, 0.05), (1.0, 5.0), (0.3, 1.0)])
+def test_clipping_matches_library_clip_grad_norm(max_norm, scale):
+    rng = np.random.default_rng(13)
+    sizes = [40, 7, 300]
+    grads = [rng.normal(scale=scale, size=n) for n in sizes]
+    params = [torch.nn.Parameter(torch.zeros(n, dtype=torch.float64)) for n in sizes]
+    for p, g in zip(params, grads):
+        p.grad = torch.tensor(g)
+    total = torch.nn.utils.clip_grad_norm_(params, max_norm)
+    got, norm, c = O.clip_gradients(grads, max_norm)
+    assert norm == pytest.approx(float(total), rel=1e-13)
+    assert (c < 1.0) == (norm > max_norm)
+    for g, p in zip(got, params):
+        np.testing.assert_allclose(g, p.grad.numpy(), rtol=1e-12, atol=0)
+    # the clipped gradient has norm max_norm (up to the 1e-6 guard) when clipping is active
+    if c < 1.0:
+        assert np.sqrt(sum(np.sum(g * g) for g in got)) == pytest.approx(max_norm, rel=1e-5)
+    assert O.clip_gradients(grads, 0.0)[2] == 1.0
+
+
+def test_clipped_gxpo_step_is_the_unclipped_step_on_clipped_gradients():
+    """With clipping every OptimStep, the ratio included, sees c*g; the gate still sees ||g_slow||."""
+    rng = np.random.default_rng(14)
+    n, clip = 200, 1.0
+    th0 = rng.normal(scale=0.02, size=n)
+    g0, g1, gs = (rng.normal(scale=s, size=n) for s in (0.5, 0.02, 0.4))      # g0 and g_slow get clipped, g1 does not
+    mk = lambda c: O.GXPOOracle(O.GXPOConfig(optim=O.OptimConfig("adamw", lr=1e-3), K=5, alpha=0.5, delta=1e-4, clip_norm=c), [th0])
+    a, b = mk(clip), mk(0.0)
+    cg = lambda g: O.clip_gradients([g], clip)[0][0]
+    a.fast_step_1([g0]); a.fast_step_2([g1]); a.extrapolate([g0], [g1]); a.slow_step([gs]); ia = a.gate_step()
+    b.fast_step_1([cg(g0)]); b.fast_step_2([cg(g1)]); b.extrapolate([cg(g0)], [cg(g1)]); b.slow_step([cg(gs)]); b.gate_step()
+    np.testing.assert_array_equal(a.theta[0], b.theta[0])
+    np.testing.assert_array_equal(a.m[0], b.m[0])
+    assert ia.norm == pytest.approx(np.linalg.norm(gs), rel=1e-14) and ia.norm > clip
