@@ -40,6 +40,7 @@ def parse_args():
     ap.add_argument("--phases", default="", help="experiment: KiB phases (mod 64) of theta,theta_probe,m,v,g0,g1,g2[,model_copy]")
     ap.add_argument("--no-probe", action="store_true",
                     help="workloads with a bf16 model copy: deliver theta^{t,1} through the copy only (no fp32 theta_probe)")
+    ap.add_argument("--clip-norm", type=float, default=0.0, help="global-norm gradient clipping threshold (0 = off)")
     ap.add_argument("--diagnostics", action="store_true", help="also accumulate the mechanism diagnostics in the passes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1 << 26, help="elements of the workload the oracle is timed on")
@@ -157,7 +158,7 @@ def main():
 
     cfg = B.make_config(optimizer=spec["optimizer"], grad_dtype=spec["grad_dtype"], fuse_step2=fused, copy_mask=7,
                         window=10, tau=3.0, waves_per_block=args.waves_per_block, weight_decay=0.01,
-                        diagnostics=args.diagnostics, **spec["cfg"])
+                        diagnostics=args.diagnostics, clip_norm=args.clip_norm, **spec["cfg"])
     ctx = B.gxpo_init(cfg, tensors)
 
     # ---- one live step: gradients evaluated where Algorithm 1 asks for them ----------------------------
@@ -180,7 +181,7 @@ def main():
                  ("fused_steps_extrapolate" if fused else "extrapolate", lambda: B.gxpo_extrapolate(ctx, g0, g1)),
                  ("slow_step", lambda: B.gxpo_slow_step(ctx, gs)))
         for name, fn in calls:
-            if events is None or (fused and name == "fast_step_2"):
+            if events is None or (fused and name == "fast_step_2" and not args.clip_norm > 0):
                 fn()
                 continue
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -202,8 +203,15 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     kernel_ms = {k: sum(a.elapsed_time(b) for a, b in v) / len(v) for k, v in events.items()}
     bpp = bytes_per_param(spec, fused)
+    gbytes = 4 if spec["grad_dtype"] == "f32" else 2
     if args.diagnostics:
-        bpp["slow_step"] += 4 if spec["grad_dtype"] == "f32" else 2          # g0 read again for <g0, g_slow>
+        bpp["slow_step"] += gbytes                                            # g0 read again for <g0, g_slow>
+    if args.clip_norm > 0:
+        if fused:
+            bpp["fast_step_2"] = 0                                            # nothing but the norm pre-pass of g1 runs there
+        for k in ("fast_step_1", "fast_step_2", "slow_step", "fallback_step"):   # norm pre-pass: the gradient is read twice
+            if k in bpp:
+                bpp[k] += gbytes
     step_bytes = sum(bpp[k] for k in kernel_ms) * P
     kernels = {k: {"ms": round(ms, 4), "bytes_per_param": bpp[k], "gbps": round(bpp[k] * P / ms / 1e6, 1)}
                for k, ms in kernel_ms.items()}

@@ -130,6 +130,11 @@ typedef struct gxpo_config {
     double alpha;             /* reposition strength in [0, 1]                  (Eq. (9))            */
     double delta;             /* active set is |g0_i| > delta, compared in fp32 (Section 2.2)        */
     double r_max;             /* clamp of the retention ratio to [-r_max, r_max]; +inf = no clamp    */
+    double clip_norm;         /* global-norm gradient clipping (Section 3.1 trains with 1.0): every gradient
+                                 handed in is used as g * min(1, clip_norm / (||g||_2 + 1e-6)), the norm over
+                                 all tensors; the retention ratio is formed from the clipped gradients, the
+                                 gate and the diagnostics see the norms as handed in.  0 = off.  Costs one
+                                 extra read of each gradient (its norm has to be known before the pass). */
     double tau;               /* gate trips when Z_t >= tau                     (Section 2.3)        */
     double gate_eps;          /* epsilon in Z_t = (norm - mu) / (sigma + epsilon), > 0  (Eq. (10))   */
 } gxpo_config;

@@ -406,6 +406,11 @@ class GXPOOracle:
     def diagnostics(self) -> dict:
         """Mechanism diagnostics of the step whose slow correction just ran."""
         c = self.cfg
+        if c.clip_norm > 0:
+            # ratio statistics follow the gradients the fast steps consumed; norms are those handed in
+            d = diagnostics(self._theta_0, self._theta_2, self._g0_used, self._g1_used, self._g_slow, c.K, c.delta, c.r_max)
+            d["norm_g0"], d["norm_g1"] = self.norm_g0_raw, self.norm_g1_raw
+            return d
         return diagnostics(self._theta_0, self._theta_2, self._g0, self._g1, self._g_slow, c.K, c.delta, c.r_max)
 
     def tensor_norms(self):

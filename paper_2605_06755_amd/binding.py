@@ -61,7 +61,7 @@ class gxpo_config(ctypes.Structure):
                 ("lr", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
                 ("adam_eps", ctypes.c_double), ("weight_decay", ctypes.c_double),
                 ("alpha", ctypes.c_double), ("delta", ctypes.c_double), ("r_max", ctypes.c_double),
-                ("tau", ctypes.c_double), ("gate_eps", ctypes.c_double)]
+                ("clip_norm", ctypes.c_double), ("tau", ctypes.c_double), ("gate_eps", ctypes.c_double)]
 
 
 class gxpo_gate_info(ctypes.Structure):
@@ -132,7 +132,7 @@ class GxpoError(RuntimeError):
 
 def make_config(*, optimizer="adamw", grad_dtype="f32", K=8, fuse_step2=True, copy_mask=7, window=10,
                 gate_min_count=0, gate_ddof=0, waves_per_block=0, diagnostics=False, lr=1e-6, beta1=0.9, beta2=0.999,
-                adam_eps=1e-8, weight_decay=0.01, alpha=0.5, delta=1e-8, r_max=math.inf, tau=3.0,
+                adam_eps=1e-8, weight_decay=0.01, alpha=0.5, delta=1e-8, r_max=math.inf, clip_norm=0.0, tau=3.0,
                 gate_eps=1e-8) -> gxpo_config:
     c = gxpo_config()
     c.struct_size = ctypes.sizeof(gxpo_config)
@@ -142,7 +142,7 @@ def make_config(*, optimizer="adamw", grad_dtype="f32", K=8, fuse_step2=True, co
     c.window, c.gate_min_count, c.gate_ddof, c.waves_per_block = int(window), int(gate_min_count), int(gate_ddof), int(waves_per_block)
     c.diagnostics, c.reserved = int(diagnostics), 0
     c.lr, c.beta1, c.beta2, c.adam_eps, c.weight_decay = lr, beta1, beta2, adam_eps, weight_decay
-    c.alpha, c.delta, c.r_max, c.tau, c.gate_eps = alpha, delta, r_max, tau, gate_eps
+    c.alpha, c.delta, c.r_max, c.clip_norm, c.tau, c.gate_eps = alpha, delta, r_max, clip_norm, tau, gate_eps
     return c
 
 

@@ -51,7 +51,8 @@ struct gxpo_ctx {
     SegRec *d_seg = nullptr;
     uint32_t *d_tensor_seg_start = nullptr;
     double *d_seg_sum = nullptr;
-    double *d_result = nullptr;              // [1 + n]
+    double *d_result = nullptr;              // [n_acc][1 + n]
+    float *d_clip = nullptr;                 // clipping factors of g0, g1, g_slow (nullptr: clipping off)
     double *h_result = nullptr;              // pinned, [1 + n]
     uint32_t n_blocks = 0, n_segs = 0;
     bool have_norms = false;
@@ -128,6 +129,7 @@ int check_config(const gxpo_config *c, std::string &msg) {
     if (!(c->alpha >= 0.0 && c->alpha <= 1.0)) return bad("alpha must be in [0, 1]");
     if (!(c->delta >= 0.0)) return bad("delta must be >= 0 (+inf allowed)");
     if (!(c->r_max > 0.0)) return bad("r_max must be > 0 (+inf = no clamp)");
+    if (!(c->clip_norm >= 0.0) || !std::isfinite(c->clip_norm)) return bad("clip_norm must be finite and >= 0 (0 = off)");
     if (std::isnan(c->tau)) return bad("tau is NaN");
     if (!(c->gate_eps > 0.0) || !std::isfinite(c->gate_eps)) return bad("gate_eps must be finite and > 0");
     return GXPO_OK;
@@ -243,6 +245,16 @@ int stage_grads(gxpo_ctx *ctx, int role, const void *const *grads, hipStream_t s
     return GXPO_OK;
 }
 
+// Gradient clipping: norm of the staged gradient list -> its clipping factor on the device.
+int clip_prepass(gxpo_ctx *ctx, const GradArg &g, int acc, int clip_index, hipStream_t s) {
+    if (!ctx->d_clip) return GXPO_OK;
+    GXPO_HIP(ctx, launch_sumsq(ctx->layout(), ctx->wpb, (int)ctx->cfg.grad_dtype, g, ctx->d_partial, acc, s));
+    GXPO_HIP(ctx, launch_finalize(ctx->d_partial, ctx->n_blocks, ctx->d_seg, ctx->n_segs, ctx->d_tensor_seg_start, ctx->n,
+                                  ctx->d_seg_sum, ctx->d_result, acc, 1, s));
+    GXPO_HIP(ctx, launch_clip_coefficient(ctx->d_result, ctx->n, acc, ctx->cfg.clip_norm, ctx->d_clip, clip_index, s));
+    return GXPO_OK;
+}
+
 void release(gxpo_ctx *ctx) {
     if (!ctx) return;
     (void)hipDeviceSynchronize();
@@ -255,6 +267,7 @@ void release(gxpo_ctx *ctx) {
     (void)hipFree(ctx->d_tensor_seg_start);
     (void)hipFree(ctx->d_seg_sum);
     (void)hipFree(ctx->d_result);
+    (void)hipFree(ctx->d_clip);
     if (ctx->h_result) (void)hipHostFree(ctx->h_result);
     if (ctx->h_stage) (void)hipHostFree((void *)ctx->h_stage);
     for (int i = 0; i < kStageSlots; ++i)
@@ -394,7 +407,7 @@ int gxpo_init(gxpo_ctx **out, const gxpo_config *cfg, const gxpo_tensor *tensors
     ctx->cfg = *cfg;
     ctx->n = n_tensors;
     ctx->wpb = wpb;
-    ctx->n_acc = cfg->diagnostics ? (uint32_t)kNumAcc : 1u;
+    ctx->n_acc = (cfg->diagnostics || cfg->clip_norm > 0.0) ? (uint32_t)kNumAcc : 1u;
     ctx->device = device;
     ctx->tensors.assign(tensors, tensors + n_tensors);
     ctx->blk_start = blk_start;
@@ -439,6 +452,7 @@ int gxpo_init(gxpo_ctx **out, const gxpo_config *cfg, const gxpo_tensor *tensors
     if (rc == GXPO_OK) rc = dev_alloc(ctx, &ctx->d_tensor_seg_start, (size_t)n_tensors + 1);
     if (rc == GXPO_OK) rc = dev_alloc(ctx, &ctx->d_seg_sum, (size_t)ctx->n_acc * segs.size());
     if (rc == GXPO_OK) rc = dev_alloc(ctx, &ctx->d_result, (size_t)ctx->n_acc * ((size_t)n_tensors + 1));
+    if (rc == GXPO_OK && cfg->clip_norm > 0.0) rc = dev_alloc(ctx, &ctx->d_clip, 3);
     if (rc != GXPO_OK) { release(ctx); return rc; }
     he = hipHostMalloc((void **)&ctx->h_result, sizeof(double) * ctx->n_acc * ((size_t)n_tensors + 1), hipHostMallocDefault);
     if (he == hipSuccess) he = hipHostMalloc((void **)&ctx->h_stage, sizeof(void *) * (size_t)kStageSlots * n_tensors, hipHostMallocDefault);
@@ -479,6 +493,8 @@ int gxpo_fast_steps(gxpo_ctx *ctx, int which, const void *const *grads, void *st
     rc = stage_grads(ctx, which == 0 ? kRoleG0 : kRoleG1, grads, s, &d_g);
     if (rc != GXPO_OK) return rc;
     const int64_t step_no = st.optim_steps + 1;
+    rc = clip_prepass(ctx, d_g, which == 0 ? kAccClipG0 : kAccClipG1, which == 0 ? kClipG0 : kClipG1, s);
+    if (rc != GXPO_OK) return rc;
     if (which == 1 && fused) {
         ctx->pending_g1.assign(grads, grads + ctx->n);
         ctx->pending_step2 = step_no;
@@ -489,7 +505,7 @@ int gxpo_fast_steps(gxpo_ctx *ctx, int which, const void *const *grads, void *st
         // fused schedule: the probe pass only previews the step, the moments are advanced by gxpo_extrapolate
         const int write_moments = fused ? 0 : 1;
         GXPO_HIP(ctx, launch_step(ctx->layout(), ctx->wpb, (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, src, kSrcProbe,
-                                  write_moments, wc, nullptr, GradArg{}, s));
+                                  write_moments, wc, nullptr, GradArg{}, ctx->d_clip, which == 0 ? kClipG0 : kClipG1, s));
         if (fused) {
             ctx->pending_g0.assign(grads, grads + ctx->n);
             ctx->pending_step1 = step_no;
@@ -526,9 +542,9 @@ int gxpo_extrapolate(gxpo_ctx *ctx, const void *const *g0, const void *const *g1
         const StepParams p1 = make_step_params(ctx->cfg, ctx->pending_step1);
         const StepParams p2 = make_step_params(ctx->cfg, ctx->pending_step2);
         GXPO_HIP(ctx, launch_fused_steps_extrapolate(ctx->layout(), ctx->wpb, (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g0, d_g1,
-                                                     p1, p2, e, wc, diag, s));
+                                                     p1, p2, e, wc, diag, ctx->d_clip, s));
     } else {
-        GXPO_HIP(ctx, launch_extrapolate(ctx->layout(), ctx->wpb, (int)ctx->cfg.grad_dtype, d_g0, d_g1, e, wc, diag, s));
+        GXPO_HIP(ctx, launch_extrapolate(ctx->layout(), ctx->wpb, (int)ctx->cfg.grad_dtype, d_g0, d_g1, e, wc, diag, ctx->d_clip, s));
     }
     if (diag)
         GXPO_HIP(ctx, launch_finalize(ctx->d_partial, ctx->n_blocks, ctx->d_seg, ctx->n_segs, ctx->d_tensor_seg_start, ctx->n,
@@ -558,10 +574,15 @@ int gxpo_slow_step(gxpo_ctx *ctx, const void *const *g_slow, void *stream) {
             if (g_slow[t] == ctx->shadow[kRoleG0][t]) cos_valid = false;      // g0 has been overwritten by g_slow
         if (cos_valid) dot = GradArg{ctx->d_grads + (size_t)kRoleG0 * ctx->n, ctx->shadow[kRoleG0][0]};
     }
+    // with clipping the norm has to exist before the pass; otherwise it is accumulated inside it
+    rc = clip_prepass(ctx, d_g, kAccSlowSq, kClipSlow, s);
+    if (rc != GXPO_OK) return rc;
+    double *partial = (ctx->d_clip && !cos_valid) ? nullptr : ctx->d_partial;
     GXPO_HIP(ctx, launch_step(ctx->layout(), ctx->wpb, (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, kSrcTheta, kSrcTheta, 1, wc,
-                              ctx->d_partial, dot, s));
-    GXPO_HIP(ctx, launch_finalize(ctx->d_partial, ctx->n_blocks, ctx->d_seg, ctx->n_segs, ctx->d_tensor_seg_start, ctx->n,
-                                  ctx->d_seg_sum, ctx->d_result, kAccSlowSq, cos_valid ? 2 : 1, s));
+                              partial, dot, ctx->d_clip, kClipSlow, s));
+    if (partial)
+        GXPO_HIP(ctx, launch_finalize(ctx->d_partial, ctx->n_blocks, ctx->d_seg, ctx->n_segs, ctx->d_tensor_seg_start, ctx->n,
+                                      ctx->d_seg_sum, ctx->d_result, kAccSlowSq, cos_valid ? 2 : 1, s));
     ctx->have_norms = true;
     ctx->have_diag = ctx->cfg.diagnostics != 0;
     ctx->cos_valid = cos_valid;
@@ -604,8 +625,10 @@ int gxpo_fallback_step(gxpo_ctx *ctx, const void *const *g0, void *stream) {
     const int64_t step_no = st.optim_steps + 1;
     const StepParams p = make_step_params(ctx->cfg, step_no);
     const int wc = (ctx->cfg.copy_mask & GXPO_COPY_AT_FINAL) ? 1 : 0;
+    rc = clip_prepass(ctx, d_g, kAccClipG0, kClipG0, s);
+    if (rc != GXPO_OK) return rc;
     GXPO_HIP(ctx, launch_step(ctx->layout(), ctx->wpb, (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, kSrcTheta, kSrcTheta, 1, wc,
-                              nullptr, GradArg{}, s));
+                              nullptr, GradArg{}, ctx->d_clip, kClipG0, s));
     st.optim_steps = step_no;
     st.backward_passes += 1;
     st.t += 1;

@@ -90,9 +90,15 @@ enum {
     kAccScale = 7,     // sum over the active set of scale
     kAccD2 = 8,        // sum (theta^{t,2} - theta^t)^2
     kAccDK = 9,        // sum (theta^{t,K} - theta^t)^2
-    kNumAcc = 10
+    kAccClipG0 = 10,   // sum g0^2, pre-pass for gradient clipping (also the fallback step's gradient)
+    kAccClipG1 = 11,   // sum g1^2, pre-pass for gradient clipping
+    kNumAcc = 12
 };
-constexpr int kNumExtrapAcc = kNumAcc - kAccG0Sq;
+constexpr int kNumExtrapAcc = kAccDK - kAccG0Sq + 1;
+
+// Gradient clipping: coef points to three device floats (for g0, g1, g_slow), each
+// min(1, max_norm / (||g|| + 1e-6)), written by the norm pre-pass; nullptr = no clipping.
+enum { kClipG0 = 0, kClipG1 = 1, kClipSlow = 2 };
 __host__ __device__ inline size_t partial_pitch(uint32_t n_blocks) { return (size_t)8 * ((n_blocks + 7u) >> 3); }
 
 // All launchers enqueue on `stream` and return the launch status.
@@ -101,19 +107,28 @@ __host__ __device__ inline size_t partial_pitch(uint32_t n_blocks) { return (siz
 hipError_t launch_step(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype,
                        const GradArg &d_grads, const StepParams &p,
                        int src, int dst, int write_moments, int write_copy, double *d_partial,
-                       const GradArg &d_g0_for_dot, hipStream_t stream);
+                       const GradArg &d_g0_for_dot, const float *d_clip, int clip_index, hipStream_t stream);
+
+// sum of squares of one gradient list into accumulator `acc` (read-only pass, 4 or 2 B/param)
+hipError_t launch_sumsq(const Layout &L, uint32_t wpb, int grad_dtype, const GradArg &d_grads, double *d_partial, int acc,
+                        hipStream_t stream);
+
+// d_clip[clip_index] = min(1, max_norm / (sqrt(result of accumulator acc) + 1e-6))
+hipError_t launch_clip_coefficient(const double *d_result, uint32_t n_tensors, int acc, double max_norm, float *d_clip,
+                                   int clip_index, hipStream_t stream);
 
 // d_diag_partial (both extrapolation launchers): nullptr, or the partial arrays; then the pass
 // also fills accumulators kAccG0Sq .. kAccDK.
 hipError_t launch_extrapolate(const Layout &L, uint32_t wpb, int grad_dtype,
                               const GradArg &d_g0, const GradArg &d_g1,
-                              const ExtrapParams &e, int write_copy, double *d_diag_partial, hipStream_t stream);
+                              const ExtrapParams &e, int write_copy, double *d_diag_partial, const float *d_clip,
+                              hipStream_t stream);
 
 // p1 / p2: constants of the first / second fast step (both are applied here).
 hipError_t launch_fused_steps_extrapolate(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype,
                                           const GradArg &d_g0, const GradArg &d_g1,
                                           const StepParams &p1, const StepParams &p2, const ExtrapParams &e,
-                                          int write_copy, double *d_diag_partial, hipStream_t stream);
+                                          int write_copy, double *d_diag_partial, const float *d_clip, hipStream_t stream);
 
 // Reduces accumulators [first_acc, first_acc + n_acc).  For accumulator a:
 // result[a * (1 + n_tensors)] = sum over all tensors, result[a * (1 + n_tensors) + 1 + t] = tensor t.

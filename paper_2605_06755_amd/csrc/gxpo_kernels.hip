@@ -177,8 +177,11 @@ struct ScaleInfo {
     bool active;     // |g0| > delta
 };
 
-__device__ __forceinline__ ScaleInfo extrap_scale_info(float g0, float g1, const ExtrapParams &e) {
-    const float r = g1 / g0;
+// g0, g1 are the gradients as loaded, c0, c1 their clipping factors (1 when clipping is off
+// or inactive).  The fast steps consumed g0*c0 and g1*c1; the ratio is formed from those.
+__device__ __forceinline__ ScaleInfo extrap_scale_info(float g0, float c0, float g1, float c1, const ExtrapParams &e) {
+    const float g0c = g0 * c0, g1c = g1 * c1;
+    const float r = g1c / g0c;
     const float rc = fminf(fmaxf(r, -e.r_max), e.r_max);
     const float x = rc * rc;
     float series = 1.0f, power = 1.0f;
@@ -190,15 +193,17 @@ __device__ __forceinline__ ScaleInfo extrap_scale_info(float g0, float g1, const
     if (e.odd) {
         power *= x;                                   // r^(K-1)
         const bool clamped = rc != r;
-        const float num = clamped ? 1.0f : g0;
-        const float den = clamped ? 1.0f + rc : g0 + g1;
+        // g0*c0 + g1*c1 with one rounding: exact product inside the fma plus the exact
+        // rounding error of the other product (both vanish when the factors are 1)
+        const float sum = fmaf(g0, c0, g1c) + fmaf(g1, c1, -g1c);
+        const float num = clamped ? 1.0f : g0c;
+        const float den = clamped ? 1.0f + rc : sum;
         scale = fmaf(power, num / den, series);
     }
-    const bool active = fabsf(g0) > e.delta;
+    const bool active = fabsf(g0c) > e.delta;
     const bool use = active && (rc != -1.0f);
     return ScaleInfo{use ? scale : 1.0f, rc, active};
 }
-
 
 __device__ __forceinline__ double wave_sum(double x) {
 #pragma unroll
@@ -268,7 +273,7 @@ __device__ __forceinline__ void add_extrap_diag(double (&acc)[kNumExtrapAcc], fl
 template <int WPB, int OPT, int GDT>
 __global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, GradArg grads, StepParams p, int src, int dst,
                                                        int write_moments, int write_copy, double *__restrict__ partial,
-                                                       GradArg dot_with) {
+                                                       GradArg dot_with, const float *__restrict__ clip, int clip_index) {
     const Span s = locate<WPB>(L);
     const uint32_t elem = threadIdx.x * kLaneElems;
     const uint32_t bytes = s.cnt * 4u;
@@ -287,10 +292,11 @@ __global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, GradArg grads
         m = load_f32(r_m, elem, s.full);
         v = load_f32(r_v, elem, s.full);
     }
+    const float coef = clip ? clip[clip_index] : 1.0f;          // global-norm clipping factor of this gradient
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         float mk = m[k], vk = v[k];
-        th[k] = th[k] - optim_update<OPT>(th[k], mk, vk, g[k], p);
+        th[k] = th[k] - optim_update<OPT>(th[k], mk, vk, g[k] * coef, p);
         m[k] = mk;
         v[k] = vk;
     }
@@ -329,7 +335,8 @@ __global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, GradArg grads
 // ============================================================================
 template <int WPB, int GDT, bool DIAG>
 __global__ __launch_bounds__(64 * WPB) void k_extrapolate(Layout L, GradArg g0s, GradArg g1s, ExtrapParams e,
-                                                        int write_copy, double *__restrict__ diag_partial) {
+                                                        int write_copy, double *__restrict__ diag_partial,
+                                                        const float *__restrict__ clip) {
     const Span s = locate<WPB>(L);
     const uint32_t elem = threadIdx.x * kLaneElems;
     const uint32_t bytes = s.cnt * 4u;
@@ -341,10 +348,11 @@ __global__ __launch_bounds__(64 * WPB) void k_extrapolate(Layout L, GradArg g0s,
     f32x4 th2 = load_f32(r_pr, elem, s.full);
     f32x4 g0 = load_grad<GDT>(r_g0, elem, s.full);
     f32x4 g1 = load_grad<GDT>(r_g1, elem, s.full);
+    const float c0 = clip ? clip[kClipG0] : 1.0f, c1 = clip ? clip[kClipG1] : 1.0f;
     double diag[kNumExtrapAcc] = {};
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        const ScaleInfo si = extrap_scale_info(g0[k], g1[k], e);
+        const ScaleInfo si = extrap_scale_info(g0[k], c0, g1[k], c1, e);
         const float disp2 = th2[k] - th0[k];
         if (DIAG) add_extrap_diag(diag, g0[k], g1[k], si, disp2);
         th0[k] = fmaf(e.alpha * si.scale, disp2, th0[k]);
@@ -375,7 +383,8 @@ __global__ __launch_bounds__(64 * WPB) void k_extrapolate(Layout L, GradArg g0s,
 template <int WPB, int OPT, int GDT, bool DIAG>
 __global__ __launch_bounds__(64 * WPB) void k_fused_steps_extrapolate(Layout L, GradArg g0s, GradArg g1s, StepParams p1,
                                                                     StepParams p2, ExtrapParams e, int write_copy,
-                                                                    double *__restrict__ diag_partial) {
+                                                                    double *__restrict__ diag_partial,
+                                                                    const float *__restrict__ clip) {
     const Span s = locate<WPB>(L);
     const uint32_t elem = threadIdx.x * kLaneElems;
     const uint32_t bytes = s.cnt * 4u;
@@ -393,16 +402,18 @@ __global__ __launch_bounds__(64 * WPB) void k_fused_steps_extrapolate(Layout L, 
         v = load_f32(r_v, elem, s.full);
     }
     f32x4 g1 = load_grad<GDT>(r_g1, elem, s.full);
+    const float c0 = clip ? clip[kClipG0] : 1.0f, c1 = clip ? clip[kClipG1] : 1.0f;
     double diag[kNumExtrapAcc] = {};
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         float mk = m[k], vk = v[k];
-        const float th1 = th0[k] - optim_update<OPT>(th0[k], mk, vk, g0[k], p1);    // theta^{t,1}, as the probe pass stored it
-        const float upd2 = optim_update<OPT>(th1, mk, vk, g1[k], p2);
+        const float g0c = g0[k] * c0, g1c = g1[k] * c1;           // what the fast steps consume (clipped)
+        const float th1 = th0[k] - optim_update<OPT>(th0[k], mk, vk, g0c, p1);    // theta^{t,1}, as the probe pass stored it
+        const float upd2 = optim_update<OPT>(th1, mk, vk, g1c, p2);
         m[k] = mk;
         v[k] = vk;
         const float disp2 = (th1 - th0[k]) - upd2;                // theta^{t,2} - theta^t
-        const ScaleInfo si = extrap_scale_info(g0[k], g1[k], e);
+        const ScaleInfo si = extrap_scale_info(g0[k], c0, g1[k], c1, e);
         if (DIAG) add_extrap_diag(diag, g0[k], g1[k], si, disp2);
         th0[k] = fmaf(e.alpha * si.scale, disp2, th0[k]);
     }
@@ -416,6 +427,28 @@ __global__ __launch_bounds__(64 * WPB) void k_fused_steps_extrapolate(Layout L, 
         store_bf16(r_c, elem, s.full, th0);
     }
     if (DIAG) store_block_sums<WPB, kNumExtrapAcc>(diag, diag_partial, kAccG0Sq, L.n_blocks);
+}
+
+// ============================================================================
+// Norm pre-pass for gradient clipping: sum of squares of one gradient list
+// (read-only, 4 or 2 B/param), same block plan and reduction as the slow step.
+// ============================================================================
+template <int WPB, int GDT>
+__global__ __launch_bounds__(64 * WPB) void k_sumsq(Layout L, GradArg grads, double *__restrict__ partial, int acc_index) {
+    const Span s = locate<WPB>(L);
+    const uint32_t elem = threadIdx.x * kLaneElems;
+    const f32x4 g = load_grad<GDT>(grad_rsrc<GDT>(grad_ptr(grads, L, s.tensor), s.e0, s.cnt), elem, s.full);
+    double acc[1] = {0.0};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) acc[0] = fma((double)g[k], (double)g[k], acc[0]);
+    store_block_sums<WPB, 1>(acc, partial, acc_index, L.n_blocks);
+}
+
+__global__ void k_clip_coefficient(const double *__restrict__ result_all, uint32_t n_tensors, int acc, double max_norm,
+                                   float *__restrict__ clip, int clip_index) {
+    const double norm = sqrt(result_all[(size_t)acc * (1 + n_tensors)]);
+    const double c = max_norm / (norm + 1e-6);
+    clip[clip_index] = (float)(c < 1.0 ? c : 1.0);          // a NaN norm gives c = NaN -> 1: the step then propagates the NaN
 }
 
 // ============================================================================
@@ -487,33 +520,34 @@ __global__ __launch_bounds__(64) void k_stream_copy(const float *__restrict__ sr
 
 template <int WPB>
 hipError_t step_wpb(const Layout &L, int optimizer, int grad_dtype, const GradArg &g, const StepParams &p, int src, int dst,
-                    int write_moments, int write_copy, double *partial, const GradArg &dot, hipStream_t st) {
+                    int write_moments, int write_copy, double *partial, const GradArg &dot, const float *clip, int clip_index,
+                    hipStream_t st) {
     const dim3 grid(L.n_blocks), block(64 * WPB);
-    if (optimizer == 0 && grad_dtype == 0) k_optim_step<WPB, 0, 0><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial, dot);
-    else if (optimizer == 0) k_optim_step<WPB, 0, 1><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial, dot);
-    else if (grad_dtype == 0) k_optim_step<WPB, 1, 0><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial, dot);
-    else k_optim_step<WPB, 1, 1><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial, dot);
+    if (optimizer == 0 && grad_dtype == 0) k_optim_step<WPB, 0, 0><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial, dot, clip, clip_index);
+    else if (optimizer == 0) k_optim_step<WPB, 0, 1><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial, dot, clip, clip_index);
+    else if (grad_dtype == 0) k_optim_step<WPB, 1, 0><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial, dot, clip, clip_index);
+    else k_optim_step<WPB, 1, 1><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial, dot, clip, clip_index);
     return hipGetLastError();
 }
 
 template <int WPB, bool DIAG>
 hipError_t extrap_wpb(const Layout &L, int grad_dtype, const GradArg &g0, const GradArg &g1, const ExtrapParams &e,
-                      int write_copy, double *diag, hipStream_t st) {
+                      int write_copy, double *diag, const float *clip, hipStream_t st) {
     const dim3 grid(L.n_blocks), block(64 * WPB);
-    if (grad_dtype == 0) k_extrapolate<WPB, 0, DIAG><<<grid, block, 0, st>>>(L, g0, g1, e, write_copy, diag);
-    else k_extrapolate<WPB, 1, DIAG><<<grid, block, 0, st>>>(L, g0, g1, e, write_copy, diag);
+    if (grad_dtype == 0) k_extrapolate<WPB, 0, DIAG><<<grid, block, 0, st>>>(L, g0, g1, e, write_copy, diag, clip);
+    else k_extrapolate<WPB, 1, DIAG><<<grid, block, 0, st>>>(L, g0, g1, e, write_copy, diag, clip);
     return hipGetLastError();
 }
 
 template <int WPB, bool DIAG>
 hipError_t fused_wpb(const Layout &L, int optimizer, int grad_dtype, const GradArg &g0, const GradArg &g1,
                      const StepParams &p1, const StepParams &p2, const ExtrapParams &e, int write_copy, double *diag,
-                     hipStream_t st) {
+                     const float *clip, hipStream_t st) {
     const dim3 grid(L.n_blocks), block(64 * WPB);
-    if (optimizer == 0 && grad_dtype == 0) k_fused_steps_extrapolate<WPB, 0, 0, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag);
-    else if (optimizer == 0) k_fused_steps_extrapolate<WPB, 0, 1, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag);
-    else if (grad_dtype == 0) k_fused_steps_extrapolate<WPB, 1, 0, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag);
-    else k_fused_steps_extrapolate<WPB, 1, 1, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag);
+    if (optimizer == 0 && grad_dtype == 0) k_fused_steps_extrapolate<WPB, 0, 0, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag, clip);
+    else if (optimizer == 0) k_fused_steps_extrapolate<WPB, 0, 1, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag, clip);
+    else if (grad_dtype == 0) k_fused_steps_extrapolate<WPB, 1, 0, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag, clip);
+    else k_fused_steps_extrapolate<WPB, 1, 1, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag, clip);
     return hipGetLastError();
 }
 
@@ -521,42 +555,68 @@ hipError_t fused_wpb(const Layout &L, int optimizer, int grad_dtype, const GradA
 
 hipError_t launch_step(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype, const GradArg &d_grads,
                        const StepParams &p, int src, int dst, int write_moments, int write_copy, double *d_partial,
-                       const GradArg &d_g0_for_dot, hipStream_t stream) {
+                       const GradArg &d_g0_for_dot, const float *d_clip, int clip_index, hipStream_t stream) {
     switch (wpb) {
-        case 1: return step_wpb<1>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_moments, write_copy, d_partial, d_g0_for_dot, stream);
-        case 2: return step_wpb<2>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_moments, write_copy, d_partial, d_g0_for_dot, stream);
-        case 4: return step_wpb<4>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_moments, write_copy, d_partial, d_g0_for_dot, stream);
+        case 1: return step_wpb<1>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_moments, write_copy, d_partial, d_g0_for_dot, d_clip, clip_index, stream);
+        case 2: return step_wpb<2>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_moments, write_copy, d_partial, d_g0_for_dot, d_clip, clip_index, stream);
+        case 4: return step_wpb<4>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_moments, write_copy, d_partial, d_g0_for_dot, d_clip, clip_index, stream);
     }
     return hipErrorInvalidValue;
 }
 
 hipError_t launch_extrapolate(const Layout &L, uint32_t wpb, int grad_dtype, const GradArg &d_g0, const GradArg &d_g1,
-                              const ExtrapParams &e, int write_copy, double *d_diag_partial, hipStream_t stream) {
+                              const ExtrapParams &e, int write_copy, double *d_diag_partial, const float *d_clip,
+                              hipStream_t stream) {
     const bool diag = d_diag_partial != nullptr;
     switch (wpb) {
-        case 1: return diag ? extrap_wpb<1, true>(L, grad_dtype, d_g0, d_g1, e, write_copy, d_diag_partial, stream)
-                            : extrap_wpb<1, false>(L, grad_dtype, d_g0, d_g1, e, write_copy, nullptr, stream);
-        case 2: return diag ? extrap_wpb<2, true>(L, grad_dtype, d_g0, d_g1, e, write_copy, d_diag_partial, stream)
-                            : extrap_wpb<2, false>(L, grad_dtype, d_g0, d_g1, e, write_copy, nullptr, stream);
-        case 4: return diag ? extrap_wpb<4, true>(L, grad_dtype, d_g0, d_g1, e, write_copy, d_diag_partial, stream)
-                            : extrap_wpb<4, false>(L, grad_dtype, d_g0, d_g1, e, write_copy, nullptr, stream);
+        case 1: return diag ? extrap_wpb<1, true>(L, grad_dtype, d_g0, d_g1, e, write_copy, d_diag_partial, d_clip, stream)
+                            : extrap_wpb<1, false>(L, grad_dtype, d_g0, d_g1, e, write_copy, nullptr, d_clip, stream);
+        case 2: return diag ? extrap_wpb<2, true>(L, grad_dtype, d_g0, d_g1, e, write_copy, d_diag_partial, d_clip, stream)
+                            : extrap_wpb<2, false>(L, grad_dtype, d_g0, d_g1, e, write_copy, nullptr, d_clip, stream);
+        case 4: return diag ? extrap_wpb<4, true>(L, grad_dtype, d_g0, d_g1, e, write_copy, d_diag_partial, d_clip, stream)
+                            : extrap_wpb<4, false>(L, grad_dtype, d_g0, d_g1, e, write_copy, nullptr, d_clip, stream);
     }
     return hipErrorInvalidValue;
 }
 
 hipError_t launch_fused_steps_extrapolate(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype, const GradArg &d_g0,
                                           const GradArg &d_g1, const StepParams &p1, const StepParams &p2,
-                                          const ExtrapParams &e, int write_copy, double *d_diag_partial, hipStream_t stream) {
+                                          const ExtrapParams &e, int write_copy, double *d_diag_partial, const float *d_clip,
+                                          hipStream_t stream) {
     const bool diag = d_diag_partial != nullptr;
     switch (wpb) {
-        case 1: return diag ? fused_wpb<1, true>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, d_diag_partial, stream)
-                            : fused_wpb<1, false>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, nullptr, stream);
-        case 2: return diag ? fused_wpb<2, true>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, d_diag_partial, stream)
-                            : fused_wpb<2, false>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, nullptr, stream);
-        case 4: return diag ? fused_wpb<4, true>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, d_diag_partial, stream)
-                            : fused_wpb<4, false>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, nullptr, stream);
+        case 1: return diag ? fused_wpb<1, true>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, d_diag_partial, d_clip, stream)
+                            : fused_wpb<1, false>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, nullptr, d_clip, stream);
+        case 2: return diag ? fused_wpb<2, true>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, d_diag_partial, d_clip, stream)
+                            : fused_wpb<2, false>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, nullptr, d_clip, stream);
+        case 4: return diag ? fused_wpb<4, true>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, d_diag_partial, d_clip, stream)
+                            : fused_wpb<4, false>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, nullptr, d_clip, stream);
     }
     return hipErrorInvalidValue;
+}
+
+template <int WPB>
+hipError_t sumsq_wpb(const Layout &L, int grad_dtype, const GradArg &g, double *partial, int acc, hipStream_t st) {
+    const dim3 grid(L.n_blocks), block(64 * WPB);
+    if (grad_dtype == 0) k_sumsq<WPB, 0><<<grid, block, 0, st>>>(L, g, partial, acc);
+    else k_sumsq<WPB, 1><<<grid, block, 0, st>>>(L, g, partial, acc);
+    return hipGetLastError();
+}
+
+hipError_t launch_sumsq(const Layout &L, uint32_t wpb, int grad_dtype, const GradArg &d_grads, double *d_partial, int acc,
+                        hipStream_t stream) {
+    switch (wpb) {
+        case 1: return sumsq_wpb<1>(L, grad_dtype, d_grads, d_partial, acc, stream);
+        case 2: return sumsq_wpb<2>(L, grad_dtype, d_grads, d_partial, acc, stream);
+        case 4: return sumsq_wpb<4>(L, grad_dtype, d_grads, d_partial, acc, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_clip_coefficient(const double *d_result, uint32_t n_tensors, int acc, double max_norm, float *d_clip,
+                                   int clip_index, hipStream_t stream) {
+    k_clip_coefficient<<<dim3(1), dim3(1), 0, stream>>>(d_result, n_tensors, acc, max_norm, d_clip, clip_index);
+    return hipGetLastError();
 }
 
 hipError_t launch_finalize(const double *d_partial, uint32_t n_blocks, const SegRec *d_seg, uint32_t n_segs,

@@ -17,6 +17,10 @@ Comparison rules (fp32 state against the fp64 oracle):
     fp32 number, the oracle's is not, and the extrapolation multiplies that
     storage rounding by alpha * scale_i, which is unbounded next to the pole of
     S_K/S_2 at r = -1 (odd K).
+  * with gradient clipping the gradients entering the ratio are rounded products
+    g * c (c itself an fp32 number), so r carries ~2^-23 relative error and the
+    allowance grows by alpha * |theta^{t,2} - theta^t| * scale_i^2 * 2^-22
+    (d scale / d r ~ scale^2 next to the pole).
   * bf16 model copy: bit-identical to round-to-nearest-even of the GPU's own
     fp32 result, and within 2e-2 relative of the oracle.
 """
@@ -121,7 +125,7 @@ def oracle_config(cfg: B.gxpo_config) -> O.GXPOConfig:
     return O.GXPOConfig(
         optim=O.OptimConfig("adamw" if cfg.optimizer == B.GXPO_OPT_ADAMW else "gd", lr=cfg.lr, beta1=cfg.beta1,
                             beta2=cfg.beta2, eps=cfg.adam_eps, weight_decay=cfg.weight_decay),
-        K=cfg.K, alpha=cfg.alpha, delta=cfg.delta, r_max=cfg.r_max,
+        K=cfg.K, alpha=cfg.alpha, delta=cfg.delta, r_max=cfg.r_max, clip_norm=cfg.clip_norm,
         gate=O.GateConfig(tau=cfg.tau, window=cfg.window, eps=cfg.gate_eps, ddof=cfg.gate_ddof,
                           min_count=(cfg.gate_min_count or None)))
 
@@ -166,6 +170,10 @@ def lockstep_active_step(ctx: B.Context, dev: DeviceState, orc: O.GXPOOracle, gr
             extra = None
             if amplified:
                 extra = 4.0 * 2.0 ** -24 * np.abs(r) * ctx.cfg.alpha * np.abs(orc.scale[i])
+                if ctx.cfg.clip_norm > 0:
+                    # clipped gradients are rounded products and the factor itself is an fp32 number:
+                    # the ratio carries ~2^-23 relative error, and d scale / d r ~ scale^2 next to the pole
+                    extra = extra + ctx.cfg.alpha * np.abs(orc._theta_2[i] - orc._theta_0[i]) * orc.scale[i] ** 2 * 2.0 ** -22
             assert_close(g, r, f"{what} {label} tensor {i}", extra_abs=extra)
         if disp_from is not None:
             num = math.sqrt(sum(float(np.sum(((g - s) - (r - s)) ** 2)) for g, r, s in zip(got, ref_list, disp_from)))

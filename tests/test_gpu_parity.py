@@ -274,6 +274,57 @@ def test_diagnostics_are_refused_without_the_flag():
 
 
 # ---------------------------------------------------------------------------------------------
+# global-norm gradient clipping (the paper trains with clipping at 1.0)
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("fused", [True, False])
+@pytest.mark.parametrize("grad_dtype", ["f32", "bf16"])
+def test_gradient_clipping_lockstep(fused, grad_dtype):
+    numels = RAGGED
+    problem = synth.policy_problem(sum(numels), seed=31, sigma=0.05, device="cuda")
+    # ||g|| is about 0.05 * sqrt(P) = 26 here: clip_norm = 20 clips the sigma = 0.05 gradients, not the sigma = 0.03 ones
+    cfg = B.make_config(grad_dtype=grad_dtype, K=5, alpha=0.5, delta=1.75e-3, lr=1e-4, fuse_step2=fused, gate_min_count=2,
+                        clip_norm=20.0, diagnostics=True)
+    dev, ctx, orc, grads = build(numels, cfg, problem)
+    step_id, call = [0], [0]
+    sigmas = [0.05, 0.03, 0.05,   0.03, 0.05, 0.03,   0.05, 0.05, 0.05]
+
+    def grad_fn(thetas, outs):
+        inner = quad_trainer(problem, numels, sigma=sigmas[call[0]], step_noise=lambda: synth.step_noise(problem, step_id[0]))
+        call[0] += 1
+        inner(thetas, outs)
+    for step in range(3):
+        step_id[0] = step
+        info, _ = H.lockstep_active_step(ctx, dev, orc, grad_fn, grads, dtol=1e-4, fused=fused, what=f"clip step {step}")
+    assert info.norm > 20.0                                # the gate sees the norm before clipping
+    # and the fallback step clips too
+    st = B.gxpo_get_state(ctx); st.s_star = st.t; B.gxpo_set_state(ctx, st)
+    H.sync_oracle_to_device(orc, dev, st.optim_steps)
+    orc.gate.s_star = orc.t = int(st.t)
+    call[0] = 0
+    grad_fn(dev.views["theta"], grads[0])
+    B.gxpo_fallback_step(ctx, grads[0])
+    ref = orc.fallback_step([H.f64(g) for g in grads[0]])
+    for i in range(len(numels)):
+        H.assert_close(dev.host("theta")[i], ref[i], f"clipped fallback theta tensor {i}")
+        H.assert_close(dev.host("v")[i], orc.v[i], f"clipped fallback v tensor {i}")
+
+
+def test_inactive_clipping_changes_nothing():
+    numels = [50000, 77]
+    problem = synth.policy_problem(sum(numels), seed=32, sigma=0.05, device="cuda")
+    outs = []
+    for clip in (0.0, 1e9):
+        cfg = B.make_config(K=8, lr=1e-4, delta=1.75e-3, clip_norm=clip, gate_min_count=2)
+        dev, ctx, orc, grads = build(numels, cfg, problem)
+        grad_fn = quad_trainer(problem, numels, step_noise=lambda: synth.step_noise(problem, 0))
+        info, _ = H.lockstep_active_step(ctx, dev, orc, grad_fn, grads, dtol=1e-4, fused=True, what=f"clip={clip}")
+        outs.append((info.norm, [x.clone() for x in dev.views["theta"]], [x.clone() for x in dev.views["v"]]))
+    assert outs[0][0] == outs[1][0]
+    for a, b in zip(outs[0][1] + outs[0][2], outs[1][1] + outs[1][2]):
+        assert torch.equal(a, b)
+
+
+# ---------------------------------------------------------------------------------------------
 # gate transition and fallback (config 5 at reduced size)
 # ---------------------------------------------------------------------------------------------
 def test_gate_transition_free_running_and_fallback():

@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_sizes_match_the_header_layout():
     # natural C layout of the header's structs on x86-64
     assert ctypes.sizeof(B.gxpo_tensor) == 8 + 5 * 8
-    assert ctypes.sizeof(B.gxpo_config) == 12 * 4 + 10 * 8
+    assert ctypes.sizeof(B.gxpo_config) == 12 * 4 + 11 * 8
     assert ctypes.sizeof(B.gxpo_diagnostics) == 9 * 8 + 8
     assert ctypes.sizeof(B.gxpo_gate_info) == 4 * 8 + 2 * 4 + 2 * 8
     assert ctypes.sizeof(B.gxpo_state) == 2 * 4 + 4 * 8 + 2 * 4 + 8 * B.GXPO_MAX_WINDOW
@@ -60,6 +60,8 @@ def test_default_config_is_valid():
     (dict(waves_per_block=3), B.GXPO_ERR_INVALID_ARG),
     (dict(copy_mask=8), B.GXPO_ERR_INVALID_ARG),
     (dict(diagnostics=2), B.GXPO_ERR_INVALID_ARG),
+    (dict(clip_norm=-1.0), B.GXPO_ERR_INVALID_ARG),
+    (dict(clip_norm=float("inf")), B.GXPO_ERR_INVALID_ARG),
     (dict(optimizer=7), B.GXPO_ERR_UNSUPPORTED),
     (dict(grad_dtype=2), B.GXPO_ERR_UNSUPPORTED),
 ])
