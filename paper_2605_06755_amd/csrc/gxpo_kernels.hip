@@ -125,9 +125,8 @@ struct Span {
     bool full;
 };
 
-template <int WPB> __device__ __forceinline__ Span locate(const Layout &L) {
+template <int WPB> __device__ __forceinline__ Span locate(const Layout &L, uint32_t b) {
     constexpr uint32_t kBlockElems = WPB * kWaveElems;
-    const uint32_t b = blockIdx.x;
     uint32_t t = 0;
     if (L.n_tensors > 1) {
         t = L.coarse[b >> kCoarseShift];
@@ -205,19 +204,38 @@ __device__ __forceinline__ ScaleInfo extrap_scale_info(float g0, float c0, float
     return ScaleInfo{use ? scale : 1.0f, rc, active};
 }
 
+// Sum over the 64 lanes of a wavefront with DPP moves (no LDS traffic, no bpermute): inside
+// each row of 16 lanes two quad permutes and two row rotations leave the row total in every
+// lane; row_bcast:15 then adds row k-1's total into rows 1 and 3, row_bcast:31 adds lane 31's
+// value into rows 2 and 3, so lane 63 holds the total, which is broadcast.  The order of the
+// additions is fixed by the lane numbers.  All 64 lanes must be active.
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ double dpp_fetch(double x) {
+    int lo = __double2loint(x), hi = __double2hiint(x);
+    lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, ROW_MASK, 0xf, false);     // lanes outside ROW_MASK receive 0
+    hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, ROW_MASK, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+
 __device__ __forceinline__ double wave_sum(double x) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
-    return x;
+    x += dpp_fetch<0xb1, 0xf>(x);      // quad_perm:[1,0,3,2]
+    x += dpp_fetch<0x4e, 0xf>(x);      // quad_perm:[2,3,0,1]
+    x += dpp_fetch<0x124, 0xf>(x);     // row_ror:4
+    x += dpp_fetch<0x128, 0xf>(x);     // row_ror:8
+    x += dpp_fetch<0x142, 0xa>(x);     // row_bcast:15 into rows 1 and 3
+    x += dpp_fetch<0x143, 0xc>(x);     // row_bcast:31 into rows 2 and 3
+    const int lo = __builtin_amdgcn_readlane(__double2loint(x), 63);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(x), 63);
+    return __hiloint2double(hi, lo);
 }
 
 // Adds the N per-lane values over the block and stores them as this block's
 // partials of accumulators first_acc .. first_acc + N - 1 (fixed order: lane
 // butterfly, then wavefronts in index order).
 template <int WPB, int N>
-__device__ __forceinline__ void store_block_sums(double (&acc)[N], double *__restrict__ partial, int first_acc, uint32_t n_blocks) {
+__device__ __forceinline__ void store_block_sums(double (&acc)[N], double *__restrict__ partial, int first_acc, uint32_t n_blocks,
+                                                 uint32_t block) {
     const size_t pitch = partial_pitch(n_blocks);
-    const uint32_t slot = partial_slot(blockIdx.x, partial_stride(n_blocks));
+    const uint32_t slot = partial_slot(block, partial_stride(n_blocks));
 #pragma unroll
     for (int a = 0; a < N; ++a) acc[a] = wave_sum(acc[a]);
     if (WPB == 1) {
@@ -241,6 +259,7 @@ __device__ __forceinline__ void store_block_sums(double (&acc)[N], double *__res
                 partial[(size_t)(first_acc + a) * pitch + slot] = total;
             }
         }
+        __syncthreads();        // the staging array may be reused by a following call
     }
 }
 
@@ -274,7 +293,7 @@ template <int WPB, int OPT, int GDT>
 __global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, GradArg grads, StepParams p, int src, int dst,
                                                        int write_moments, int write_copy, double *__restrict__ partial,
                                                        GradArg dot_with, const float *__restrict__ clip, int clip_index) {
-    const Span s = locate<WPB>(L);
+    const Span s = locate<WPB>(L, blockIdx.x);
     const uint32_t elem = threadIdx.x * kLaneElems;
     const uint32_t bytes = s.cnt * 4u;
     const float *src_ptr = (src == kSrcProbe ? s.rec.probe : s.rec.theta) + s.e0;
@@ -320,10 +339,10 @@ __global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, GradArg grads
             const f32x4 o = load_grad<GDT>(grad_rsrc<GDT>(other, s.e0, s.cnt), elem, s.full);
 #pragma unroll
             for (int k = 0; k < 4; ++k) acc[1] = fma((double)o[k], (double)g[k], acc[1]);
-            store_block_sums<WPB, 2>(acc, partial, kAccSlowSq, L.n_blocks);
+            store_block_sums<WPB, 2>(acc, partial, kAccSlowSq, L.n_blocks, blockIdx.x);
         } else {
             double only[1] = {acc[0]};
-            store_block_sums<WPB, 1>(only, partial, kAccSlowSq, L.n_blocks);
+            store_block_sums<WPB, 1>(only, partial, kAccSlowSq, L.n_blocks, blockIdx.x);
         }
     }
 }
@@ -337,7 +356,7 @@ template <int WPB, int GDT, bool DIAG>
 __global__ __launch_bounds__(64 * WPB) void k_extrapolate(Layout L, GradArg g0s, GradArg g1s, ExtrapParams e,
                                                         int write_copy, double *__restrict__ diag_partial,
                                                         const float *__restrict__ clip) {
-    const Span s = locate<WPB>(L);
+    const Span s = locate<WPB>(L, blockIdx.x);
     const uint32_t elem = threadIdx.x * kLaneElems;
     const uint32_t bytes = s.cnt * 4u;
     const auto r_th = span_rsrc(s.rec.theta + s.e0, bytes);
@@ -362,7 +381,7 @@ __global__ __launch_bounds__(64 * WPB) void k_extrapolate(Layout L, GradArg g0s,
         const auto r_c = span_rsrc((unsigned short *)s.rec.copy + s.e0, s.cnt * 2u);
         store_bf16(r_c, elem, s.full, th0);
     }
-    if (DIAG) store_block_sums<WPB, kNumExtrapAcc>(diag, diag_partial, kAccG0Sq, L.n_blocks);
+    if (DIAG) store_block_sums<WPB, kNumExtrapAcc>(diag, diag_partial, kAccG0Sq, L.n_blocks, blockIdx.x);
 }
 
 // ============================================================================
@@ -385,7 +404,7 @@ __global__ __launch_bounds__(64 * WPB) void k_fused_steps_extrapolate(Layout L, 
                                                                     StepParams p2, ExtrapParams e, int write_copy,
                                                                     double *__restrict__ diag_partial,
                                                                     const float *__restrict__ clip) {
-    const Span s = locate<WPB>(L);
+    const Span s = locate<WPB>(L, blockIdx.x);
     const uint32_t elem = threadIdx.x * kLaneElems;
     const uint32_t bytes = s.cnt * 4u;
     const auto r_th = span_rsrc(s.rec.theta + s.e0, bytes);
@@ -426,22 +445,40 @@ __global__ __launch_bounds__(64 * WPB) void k_fused_steps_extrapolate(Layout L, 
         const auto r_c = span_rsrc((unsigned short *)s.rec.copy + s.e0, s.cnt * 2u);
         store_bf16(r_c, elem, s.full, th0);
     }
-    if (DIAG) store_block_sums<WPB, kNumExtrapAcc>(diag, diag_partial, kAccG0Sq, L.n_blocks);
+    if (DIAG) store_block_sums<WPB, kNumExtrapAcc>(diag, diag_partial, kAccG0Sq, L.n_blocks, blockIdx.x);
 }
 
 // ============================================================================
 // Norm pre-pass for gradient clipping: sum of squares of one gradient list
 // (read-only, 4 or 2 B/param), same block plan and reduction as the slow step.
 // ============================================================================
+// A launched block covers kSumsqGroup consecutive blocks of the plan (a single 1 KiB read per
+// launched block would be bound by the block dispatch rate, not by HBM); it still writes one
+// partial per plan block, so the reduction that follows is the same.
+constexpr uint32_t kSumsqGroup = 4;
+
 template <int WPB, int GDT>
 __global__ __launch_bounds__(64 * WPB) void k_sumsq(Layout L, GradArg grads, double *__restrict__ partial, int acc_index) {
-    const Span s = locate<WPB>(L);
     const uint32_t elem = threadIdx.x * kLaneElems;
-    const f32x4 g = load_grad<GDT>(grad_rsrc<GDT>(grad_ptr(grads, L, s.tensor), s.e0, s.cnt), elem, s.full);
-    double acc[1] = {0.0};
+    const uint32_t first = blockIdx.x * kSumsqGroup;
+    f32x4 g[kSumsqGroup];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) acc[0] = fma((double)g[k], (double)g[k], acc[0]);
-    store_block_sums<WPB, 1>(acc, partial, acc_index, L.n_blocks);
+    for (uint32_t i = 0; i < kSumsqGroup; ++i) {
+        g[i] = f32x4{0, 0, 0, 0};
+        if (first + i < L.n_blocks) {
+            const Span s = locate<WPB>(L, first + i);
+            g[i] = load_grad<GDT>(grad_rsrc<GDT>(grad_ptr(grads, L, s.tensor), s.e0, s.cnt), elem, s.full);
+        }
+    }
+#pragma unroll
+    for (uint32_t i = 0; i < kSumsqGroup; ++i) {
+        if (first + i < L.n_blocks) {
+            double acc[1] = {0.0};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) acc[0] = fma((double)g[i][k], (double)g[i][k], acc[0]);
+            store_block_sums<WPB, 1>(acc, partial, acc_index, L.n_blocks, first + i);
+        }
+    }
 }
 
 __global__ void k_clip_coefficient(const double *__restrict__ result_all, uint32_t n_tensors, int acc, double max_norm,
@@ -597,7 +634,7 @@ hipError_t launch_fused_steps_extrapolate(const Layout &L, uint32_t wpb, int opt
 
 template <int WPB>
 hipError_t sumsq_wpb(const Layout &L, int grad_dtype, const GradArg &g, double *partial, int acc, hipStream_t st) {
-    const dim3 grid(L.n_blocks), block(64 * WPB);
+    const dim3 grid((L.n_blocks + kSumsqGroup - 1) / kSumsqGroup), block(64 * WPB);
     if (grad_dtype == 0) k_sumsq<WPB, 0><<<grid, block, 0, st>>>(L, g, partial, acc);
     else k_sumsq<WPB, 1><<<grid, block, 0, st>>>(L, g, partial, acc);
     return hipGetLastError();
