@@ -311,6 +311,7 @@ class GXPOConfig:
     delta: float = 1e-8
     r_max: float = math.inf
     clip_norm: float = 0.0          # 0 = no clipping
+    explicit_steps: int = 0         # n >= 2: take n real fast steps instead of extrapolating (see explicit_*)
     gate: GateConfig = field(default_factory=GateConfig)
 
 
@@ -392,6 +393,28 @@ class GXPOOracle:
             self.scale.append(s)
             self.theta_K.append(tk)
             self.theta_tilde.append(tt)
+        return self.theta_tilde
+
+    # -- explicit lookahead: the slow-fast scheme GXPO is compared with ---------------------
+    # Section 1 describes it as K fast inner steps followed by a slow correction, K + 1
+    # backward passes per update.  Here: n real OptimSteps from theta^t, the same partial
+    # reposition theta~ = theta^t + alpha (theta^{t,n} - theta^t) with no extrapolation
+    # factor, then the usual slow step and gate.
+    def explicit_fast_step(self, j: int, g):
+        """theta^{t,j+1} = OptimStep(theta^{t,j}, g), j = 0 .. n-1 (theta^{t,0} = theta^t)."""
+        assert self.is_active() and 0 <= j < self.cfg.explicit_steps
+        self.backward_passes += 1
+        used, _, _ = clip_gradients(g, self.cfg.clip_norm)
+        if j == 0:
+            self._theta_0 = [t.copy() for t in self.theta]
+            self._theta_j = self._theta_0
+        self._theta_j = self._optim_all(self._theta_j, used)
+        return self._theta_j
+
+    def explicit_reposition(self):
+        """theta~ = theta^t + alpha (theta^{t,n} - theta^t)."""
+        a = self.cfg.alpha
+        self.theta_tilde = [t0 + a * (tn - t0) for t0, tn in zip(self._theta_0, self._theta_j)]
         return self.theta_tilde
 
     def slow_step(self, g_slow):

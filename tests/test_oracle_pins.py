@@ -586,3 +586,34 @@ def test_clipped_gxpo_step_is_the_unclipped_step_on_clipped_gradients():
     np.testing.assert_array_equal(a.theta[0], b.theta[0])
     np.testing.assert_array_equal(a.m[0], b.m[0])
     assert ia.norm == pytest.approx(np.linalg.norm(gs), rel=1e-14) and ia.norm > clip
+
+
+# ---------------------------------------------------------------------------
+# 9. Explicit lookahead (n real fast steps, reposition, slow correction): on the
+#    diagonal quadratic with plain GD it must land where the extrapolation lands
+#    (the paper's corollary read the other way round), and where brute-force GD lands.
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("K", [2, 3, 5, 10])
+@pytest.mark.parametrize("alpha", [1.0, 0.5])
+def test_explicit_lookahead_equals_extrapolation_on_the_surrogate(K, alpha):
+    h, ts, th0 = surrogate_numpy()
+    eta = 0.1
+    grad = lambda th: h * (th - ts)
+    cfg_x = gd_config(K, alpha, eta)
+    cfg_e = O.GXPOConfig(optim=O.OptimConfig("gd", lr=eta), K=K, alpha=alpha, delta=0.0, explicit_steps=K,
+                         gate=O.GateConfig(tau=3.0, window=10))
+    ox, oe = O.GXPOOracle(cfg_x, [th0]), O.GXPOOracle(cfg_e, [th0])
+    for _ in range(3):
+        start = oe.theta[0].copy()
+        ox.train_step(lambda ths: [grad(ths[0])])
+        th = oe.theta
+        for j in range(K):
+            th = oe.explicit_fast_step(j, [grad(th[0])])
+        np.testing.assert_allclose(th[0], gd_unroll(start, grad, eta, K), rtol=1e-12, atol=1e-14)   # K real GD steps
+        tt = oe.explicit_reposition()
+        oe.slow_step([grad(tt[0])])
+        oe.gate_step()
+        np.testing.assert_allclose(oe.theta_tilde[0], ox.theta_tilde[0], rtol=1e-10, atol=1e-12)
+        np.testing.assert_allclose(oe.theta[0], ox.theta[0], rtol=1e-10, atol=1e-12)
+    assert oe.backward_passes == 3 * (K + 1) and ox.backward_passes == 9     # K + 1 against 3 per step
+    assert oe.optim_steps == 3 * (K + 1)
