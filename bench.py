@@ -40,6 +40,7 @@ def parse_args():
     ap.add_argument("--phases", default="", help="experiment: KiB phases (mod 64) of theta,theta_probe,m,v,g0,g1,g2[,model_copy]")
     ap.add_argument("--no-probe", action="store_true",
                     help="workloads with a bf16 model copy: deliver theta^{t,1} through the copy only (no fp32 theta_probe)")
+    ap.add_argument("--explicit-steps", type=int, default=0, help="explicit lookahead with this many real fast steps instead of GXPO")
     ap.add_argument("--clip-norm", type=float, default=0.0, help="global-norm gradient clipping threshold (0 = off)")
     ap.add_argument("--diagnostics", action="store_true", help="also accumulate the mechanism diagnostics in the passes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -114,7 +115,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     spec = workload_spec(args.workload)
-    fused = not args.unfused
+    fused = not args.unfused and not args.explicit_steps
     if args.no_probe:
         if not (spec["copy"] and fused):
             print("bench.py: --no-probe needs a workload with a bf16 model copy and the fused schedule", file=sys.stderr)
@@ -158,7 +159,8 @@ def main():
 
     cfg = B.make_config(optimizer=spec["optimizer"], grad_dtype=spec["grad_dtype"], fuse_step2=fused, copy_mask=7,
                         window=10, tau=3.0, waves_per_block=args.waves_per_block, weight_decay=0.01,
-                        diagnostics=args.diagnostics, clip_norm=args.clip_norm, **spec["cfg"])
+                        diagnostics=args.diagnostics, clip_norm=args.clip_norm, explicit_steps=args.explicit_steps,
+                        **spec["cfg"])
     ctx = B.gxpo_init(cfg, tensors)
 
     # ---- one live step: gradients evaluated where Algorithm 1 asks for them ----------------------------
@@ -167,7 +169,12 @@ def main():
     B.gxpo_fast_steps(ctx, 0, g0)
     quad.grad(flat["model_copy"].float() if spec.get("no_probe") else flat["theta_probe"], 0, gflat[1])
     B.gxpo_fast_steps(ctx, 1, g1)
-    B.gxpo_extrapolate(ctx, g0, g1)
+    for j in range(2, args.explicit_steps):
+        B.gxpo_fast_steps(ctx, j, g1)
+    if args.explicit_steps:
+        B.gxpo_extrapolate(ctx)
+    else:
+        B.gxpo_extrapolate(ctx, g0, g1)
     quad.grad(flat["theta"], 0, gflat[2])
     B.gxpo_slow_step(ctx, gs)
     live_info = B.gxpo_gate(ctx)
@@ -176,10 +183,15 @@ def main():
     g0, g1, gs = B.GradList(ctx, g0), B.GradList(ctx, g1), B.GradList(ctx, gs)
 
     def active_step(events=None):
-        calls = (("fast_step_1", lambda: B.gxpo_fast_steps(ctx, 0, g0)),
-                 ("fast_step_2", lambda: B.gxpo_fast_steps(ctx, 1, g1)),
-                 ("fused_steps_extrapolate" if fused else "extrapolate", lambda: B.gxpo_extrapolate(ctx, g0, g1)),
-                 ("slow_step", lambda: B.gxpo_slow_step(ctx, gs)))
+        if args.explicit_steps:
+            calls = tuple((f"fast_step_{j + 1}", (lambda j=j: B.gxpo_fast_steps(ctx, j, g0 if j == 0 else g1)))
+                          for j in range(args.explicit_steps))
+            calls += (("reposition", lambda: B.gxpo_extrapolate(ctx)), ("slow_step", lambda: B.gxpo_slow_step(ctx, gs)))
+        else:
+            calls = (("fast_step_1", lambda: B.gxpo_fast_steps(ctx, 0, g0)),
+                     ("fast_step_2", lambda: B.gxpo_fast_steps(ctx, 1, g1)),
+                     ("fused_steps_extrapolate" if fused else "extrapolate", lambda: B.gxpo_extrapolate(ctx, g0, g1)),
+                     ("slow_step", lambda: B.gxpo_slow_step(ctx, gs)))
         for name, fn in calls:
             if events is None or (fused and name == "fast_step_2" and not args.clip_norm > 0):
                 fn()
@@ -203,6 +215,10 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     kernel_ms = {k: sum(a.elapsed_time(b) for a, b in v) / len(v) for k, v in events.items()}
     bpp = bytes_per_param(spec, fused)
+    if args.explicit_steps:
+        full = bpp["slow_step"]
+        bpp = {f"fast_step_{j + 1}": full - (0 if spec["copy"] else 0) for j in range(args.explicit_steps)}
+        bpp.update(reposition=12 + (2 if spec["copy"] else 0), slow_step=full, fallback_step=full)
     gbytes = 4 if spec["grad_dtype"] == "f32" else 2
     if args.diagnostics:
         bpp["slow_step"] += gbytes                                            # g0 read again for <g0, g_slow>

@@ -125,7 +125,12 @@ typedef struct gxpo_config {
     uint32_t diagnostics;     /* 1: also accumulate the mechanism diagnostics (gxpo_get_diagnostics) inside
                                  the extrapolation pass and the slow step; g0 is then re-read by the slow
                                  step (+4 or +2 bytes per parameter) and must stay intact until it has run */
-    uint32_t reserved;        /* 0 */
+    uint32_t explicit_steps;  /* 0: GXPO (two probes + extrapolation).  n >= 2: explicit lookahead, the
+                                 slow-fast scheme the paper compares with (Section 1): gxpo_fast_steps is
+                                 called with which = 0 .. n-1, each a real OptimStep on the probe
+                                 trajectory; gxpo_extrapolate (gradient lists may be NULL) then only
+                                 repositions, theta <- theta + alpha (theta^{t,n} - theta); slow step and
+                                 gate as usual.  n + 1 backward passes per step.  Needs diagnostics == 0. */
     double lr, beta1, beta2, adam_eps, weight_decay;   /* OptimStep (AdamW: decoupled weight decay) */
     double alpha;             /* reposition strength in [0, 1]                  (Eq. (9))            */
     double delta;             /* active set is |g0_i| > delta, compared in fp32 (Section 2.2)        */
@@ -192,6 +197,7 @@ void gxpo_destroy(gxpo_ctx *ctx);
 
 /* which == 0: theta_probe <- OptimStep(theta, grads)           ("First fast optimizer step")
  * which == 1: theta_probe <- OptimStep(theta_probe, grads)     ("Second fast optimizer step")
+ * (which = 2 .. explicit_steps - 1 likewise, in order, when explicit_steps is set)
  * The optimizer state (m, v, step counter) advances on both and is not rolled
  * back later (Section 2.3, paragraph after Eq. (9)).  theta is left untouched.
  * The gradients of which == 0 must stay unmodified until gxpo_extrapolate has

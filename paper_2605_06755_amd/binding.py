@@ -57,7 +57,7 @@ class gxpo_config(ctypes.Structure):
     _fields_ = [("struct_size", ctypes.c_uint32), ("optimizer", ctypes.c_uint32), ("grad_dtype", ctypes.c_uint32),
                 ("K", ctypes.c_uint32), ("fuse_step2", ctypes.c_uint32), ("copy_mask", ctypes.c_uint32),
                 ("window", ctypes.c_uint32), ("gate_min_count", ctypes.c_uint32), ("gate_ddof", ctypes.c_uint32),
-                ("waves_per_block", ctypes.c_uint32), ("diagnostics", ctypes.c_uint32), ("reserved", ctypes.c_uint32),
+                ("waves_per_block", ctypes.c_uint32), ("diagnostics", ctypes.c_uint32), ("explicit_steps", ctypes.c_uint32),
                 ("lr", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
                 ("adam_eps", ctypes.c_double), ("weight_decay", ctypes.c_double),
                 ("alpha", ctypes.c_double), ("delta", ctypes.c_double), ("r_max", ctypes.c_double),
@@ -131,7 +131,7 @@ class GxpoError(RuntimeError):
 
 
 def make_config(*, optimizer="adamw", grad_dtype="f32", K=8, fuse_step2=True, copy_mask=7, window=10,
-                gate_min_count=0, gate_ddof=0, waves_per_block=0, diagnostics=False, lr=1e-6, beta1=0.9, beta2=0.999,
+                gate_min_count=0, gate_ddof=0, waves_per_block=0, diagnostics=False, explicit_steps=0, lr=1e-6, beta1=0.9, beta2=0.999,
                 adam_eps=1e-8, weight_decay=0.01, alpha=0.5, delta=1e-8, r_max=math.inf, clip_norm=0.0, tau=3.0,
                 gate_eps=1e-8) -> gxpo_config:
     c = gxpo_config()
@@ -140,7 +140,7 @@ def make_config(*, optimizer="adamw", grad_dtype="f32", K=8, fuse_step2=True, co
     c.grad_dtype = {"f32": GXPO_GRAD_F32, "bf16": GXPO_GRAD_BF16}.get(grad_dtype, grad_dtype)
     c.K, c.fuse_step2, c.copy_mask = int(K), int(bool(fuse_step2)), int(copy_mask)
     c.window, c.gate_min_count, c.gate_ddof, c.waves_per_block = int(window), int(gate_min_count), int(gate_ddof), int(waves_per_block)
-    c.diagnostics, c.reserved = int(diagnostics), 0
+    c.diagnostics, c.explicit_steps = int(diagnostics), int(explicit_steps)
     c.lr, c.beta1, c.beta2, c.adam_eps, c.weight_decay = lr, beta1, beta2, adam_eps, weight_decay
     c.alpha, c.delta, c.r_max, c.clip_norm, c.tau, c.gate_eps = alpha, delta, r_max, clip_norm, tau, gate_eps
     return c
@@ -242,8 +242,11 @@ def gxpo_fast_steps(ctx: Context, which: int, grads: Sequence[torch.Tensor], str
     ctx._check(_lib.gxpo_fast_steps(ctx.handle, which, ctx._grad_list(grads, f"fast{which}"), _stream_ptr(stream)))
 
 
-def gxpo_extrapolate(ctx: Context, g0: Sequence[torch.Tensor], g1: Sequence[torch.Tensor], stream=None) -> None:
-    ctx._check(_lib.gxpo_extrapolate(ctx.handle, ctx._grad_list(g0, "ex0"), ctx._grad_list(g1, "ex1"), _stream_ptr(stream)))
+def gxpo_extrapolate(ctx: Context, g0=None, g1=None, stream=None) -> None:
+    """g0, g1 may be None only for a context with explicit_steps (reposition without extrapolation)."""
+    a0 = ctx._grad_list(g0, "ex0") if g0 is not None else None
+    a1 = ctx._grad_list(g1, "ex1") if g1 is not None else None
+    ctx._check(_lib.gxpo_extrapolate(ctx.handle, a0, a1, _stream_ptr(stream)))
 
 
 def gxpo_slow_step(ctx: Context, g_slow: Sequence[torch.Tensor], stream=None) -> None:

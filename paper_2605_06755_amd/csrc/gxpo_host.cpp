@@ -68,6 +68,7 @@ struct gxpo_ctx {
     std::vector<const void *> shadow[kGradRoles];
     std::vector<const void *> pending_g0;    // fuse_step2: the gradients the probe pass used
     std::vector<const void *> pending_g1;    // fuse_step2: recorded by gxpo_fast_steps(1)
+    uint32_t fast_done = 0;                  // fast steps taken in the current training step
     int64_t pending_step1 = 0;               // optimizer step numbers of the two fast steps the
     int64_t pending_step2 = 0;               //   fused pass applies
 
@@ -118,7 +119,8 @@ int check_config(const gxpo_config *c, std::string &msg) {
     if (c->waves_per_block != 0 && c->waves_per_block != 1 && c->waves_per_block != 2 && c->waves_per_block != 4)
         return bad("waves_per_block must be 0, 1, 2 or 4");
     if (c->diagnostics > 1) return bad("diagnostics must be 0 or 1");
-    if (c->reserved != 0) return bad("reserved must be 0");
+    if (c->explicit_steps == 1 || c->explicit_steps > 4096) return bad("explicit_steps must be 0 or in [2, 4096]");
+    if (c->explicit_steps && c->diagnostics) return bad("diagnostics need the extrapolation (explicit_steps == 0)");
     if (!(c->lr > 0.0) || !std::isfinite(c->lr)) return bad("lr must be finite and > 0");
     if (c->optimizer == GXPO_OPT_ADAMW) {
         if (!(c->beta1 >= 0.0 && c->beta1 < 1.0)) return bad("beta1 must be in [0, 1)");
@@ -475,12 +477,14 @@ void gxpo_destroy(gxpo_ctx *ctx) { release(ctx); }
 int gxpo_fast_steps(gxpo_ctx *ctx, int which, const void *const *grads, void *stream) {
     int rc = check_call(ctx, grads, "gxpo_fast_steps");
     if (rc != GXPO_OK) return rc;
-    if (which != 0 && which != 1) return fail(ctx, GXPO_ERR_INVALID_ARG, "gxpo_fast_steps: which must be 0 or 1");
+    const uint32_t n_fast = ctx->cfg.explicit_steps ? ctx->cfg.explicit_steps : 2u;
+    if (which < 0 || (uint32_t)which >= n_fast)
+        return fail(ctx, GXPO_ERR_INVALID_ARG, "gxpo_fast_steps: which must be in [0, %u)", n_fast);
     gxpo_state &st = ctx->st;
     if (is_fallback_phase(st)) return fail(ctx, GXPO_ERR_BAD_STATE, "gxpo_fast_steps: the gate has tripped (s* = %lld), use gxpo_fallback_step", (long long)st.s_star);
-    const uint32_t want = which == 0 ? GXPO_PHASE_IDLE : GXPO_PHASE_FAST1;
-    if (st.phase != want) return fail(ctx, GXPO_ERR_BAD_STATE, "gxpo_fast_steps(%d) called in phase %u", which, st.phase);
-    const bool fused = ctx->cfg.fuse_step2 != 0;
+    const bool in_order = which == 0 ? st.phase == GXPO_PHASE_IDLE : (st.phase == GXPO_PHASE_FAST1 && ctx->fast_done == (uint32_t)which);
+    if (!in_order) return fail(ctx, GXPO_ERR_BAD_STATE, "gxpo_fast_steps(%d) called in phase %u after %u fast steps", which, st.phase, ctx->fast_done);
+    const bool fused = ctx->cfg.fuse_step2 != 0 && !ctx->cfg.explicit_steps;
     const bool copy_at_probe = (ctx->cfg.copy_mask & GXPO_COPY_AT_PROBE) != 0;
     for (uint32_t t = 0; t < ctx->n; ++t) {
         const gxpo_tensor &x = ctx->tensors[t];
@@ -501,7 +505,8 @@ int gxpo_fast_steps(gxpo_ctx *ctx, int which, const void *const *grads, void *st
     } else {
         const StepParams p = make_step_params(ctx->cfg, step_no);
         const int src = which == 0 ? kSrcTheta : kSrcProbe;
-        const int wc = (which == 0 && copy_at_probe) ? 1 : 0;
+        // the trainer differentiates at theta^{t,1}; with explicit lookahead at every probe iterate
+        const int wc = ((which == 0 || ctx->cfg.explicit_steps) && copy_at_probe) ? 1 : 0;
         // fused schedule: the probe pass only previews the step, the moments are advanced by gxpo_extrapolate
         const int write_moments = fused ? 0 : 1;
         GXPO_HIP(ctx, launch_step(ctx->layout(), ctx->wpb, (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, src, kSrcProbe,
@@ -513,11 +518,24 @@ int gxpo_fast_steps(gxpo_ctx *ctx, int which, const void *const *grads, void *st
     }
     st.optim_steps = step_no;
     st.backward_passes += 1;
-    st.phase = which == 0 ? GXPO_PHASE_FAST1 : GXPO_PHASE_FAST2;
+    ctx->fast_done = (uint32_t)which + 1;
+    st.phase = ctx->fast_done == n_fast ? GXPO_PHASE_FAST2 : GXPO_PHASE_FAST1;
     return GXPO_OK;
 }
 
 int gxpo_extrapolate(gxpo_ctx *ctx, const void *const *g0, const void *const *g1, void *stream) {
+    if (!ctx) return GXPO_ERR_INVALID_ARG;
+    if (ctx->cfg.explicit_steps) {
+        // explicit lookahead: the probe trajectory was walked for real, only the reposition is left
+        static const void *const no_grads[1] = {nullptr};
+        int rc0 = check_call(ctx, no_grads, "gxpo_extrapolate");
+        if (rc0 != GXPO_OK) return rc0;
+        if (ctx->st.phase != GXPO_PHASE_FAST2) return fail(ctx, GXPO_ERR_BAD_STATE, "gxpo_extrapolate called in phase %u", ctx->st.phase);
+        const int wc0 = (ctx->cfg.copy_mask & GXPO_COPY_AT_TILDE) ? 1 : 0;
+        GXPO_HIP(ctx, launch_reposition(ctx->layout(), ctx->wpb, (float)ctx->cfg.alpha, wc0, (hipStream_t)stream));
+        ctx->st.phase = GXPO_PHASE_REPOSITIONED;
+        return GXPO_OK;
+    }
     int rc = check_call(ctx, g0, "gxpo_extrapolate");
     if (rc != GXPO_OK) return rc;
     if (!g1) return fail(ctx, GXPO_ERR_INVALID_ARG, "gxpo_extrapolate: g1 list is NULL");

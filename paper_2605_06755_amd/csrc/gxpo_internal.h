@@ -124,6 +124,9 @@ hipError_t launch_extrapolate(const Layout &L, uint32_t wpb, int grad_dtype,
                               const ExtrapParams &e, int write_copy, double *d_diag_partial, const float *d_clip,
                               hipStream_t stream);
 
+// theta <- theta + alpha (theta_probe - theta), nothing else (explicit lookahead).
+hipError_t launch_reposition(const Layout &L, uint32_t wpb, float alpha, int write_copy, hipStream_t stream);
+
 // p1 / p2: constants of the first / second fast step (both are applied here).
 hipError_t launch_fused_steps_extrapolate(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype,
                                           const GradArg &d_g0, const GradArg &d_g1,

@@ -385,6 +385,28 @@ __global__ __launch_bounds__(64 * WPB) void k_extrapolate(Layout L, GradArg g0s,
 }
 
 // ============================================================================
+// Reposition alone (explicit lookahead): theta <- theta + alpha (theta_probe - theta).
+// 12 B/param (8 read, 4 written).
+// ============================================================================
+template <int WPB>
+__global__ __launch_bounds__(64 * WPB) void k_reposition(Layout L, float alpha, int write_copy) {
+    const Span s = locate<WPB>(L, blockIdx.x);
+    const uint32_t elem = threadIdx.x * kLaneElems;
+    const uint32_t bytes = s.cnt * 4u;
+    const auto r_th = span_rsrc(s.rec.theta + s.e0, bytes);
+    const auto r_pr = span_rsrc(s.rec.probe + s.e0, bytes);
+    f32x4 th0 = load_f32(r_th, elem, s.full);
+    const f32x4 thn = load_f32(r_pr, elem, s.full);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) th0[k] = fmaf(alpha, thn[k] - th0[k], th0[k]);
+    store_f32(r_th, elem, s.full, th0);
+    if (write_copy && s.rec.copy) {
+        const auto r_c = span_rsrc((unsigned short *)s.rec.copy + s.e0, s.cnt * 2u);
+        store_bf16(r_c, elem, s.full, th0);
+    }
+}
+
+// ============================================================================
 // Fused: both fast steps' state update + extrapolate + reposition.
 //
 // The first fast step was only previewed by the probe pass (theta^{t,1} went
@@ -653,6 +675,17 @@ hipError_t launch_sumsq(const Layout &L, uint32_t wpb, int grad_dtype, const Gra
 hipError_t launch_clip_coefficient(const double *d_result, uint32_t n_tensors, int acc, double max_norm, float *d_clip,
                                    int clip_index, hipStream_t stream) {
     k_clip_coefficient<<<dim3(1), dim3(1), 0, stream>>>(d_result, n_tensors, acc, max_norm, d_clip, clip_index);
+    return hipGetLastError();
+}
+
+hipError_t launch_reposition(const Layout &L, uint32_t wpb, float alpha, int write_copy, hipStream_t stream) {
+    const dim3 grid(L.n_blocks);
+    switch (wpb) {
+        case 1: k_reposition<1><<<grid, dim3(64), 0, stream>>>(L, alpha, write_copy); break;
+        case 2: k_reposition<2><<<grid, dim3(128), 0, stream>>>(L, alpha, write_copy); break;
+        case 4: k_reposition<4><<<grid, dim3(256), 0, stream>>>(L, alpha, write_copy); break;
+        default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 

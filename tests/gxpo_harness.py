@@ -126,6 +126,7 @@ def oracle_config(cfg: B.gxpo_config) -> O.GXPOConfig:
         optim=O.OptimConfig("adamw" if cfg.optimizer == B.GXPO_OPT_ADAMW else "gd", lr=cfg.lr, beta1=cfg.beta1,
                             beta2=cfg.beta2, eps=cfg.adam_eps, weight_decay=cfg.weight_decay),
         K=cfg.K, alpha=cfg.alpha, delta=cfg.delta, r_max=cfg.r_max, clip_norm=cfg.clip_norm,
+        explicit_steps=cfg.explicit_steps,
         gate=O.GateConfig(tau=cfg.tau, window=cfg.window, eps=cfg.gate_eps, ddof=cfg.gate_ddof,
                           min_count=(cfg.gate_min_count or None)))
 
@@ -144,6 +145,15 @@ def check_bf16_copy(dev: DeviceState, ref_thetas: Sequence[np.ndarray], what: st
         got_bits = c.detach().cpu().view(torch.int16).numpy().view(np.uint16)
         want_bits = O.bf16_round_bits(th.detach().cpu().numpy())
         np.testing.assert_array_equal(got_bits, want_bits, err_msg=f"{what}: tensor {i} copy is not RNE(theta)")
+        assert_close(O.bf16_bits_to_f64(got_bits), ref_thetas[i], f"{what}: tensor {i} bf16 copy", rtol=RTOL_BF16)
+
+
+def check_bf16_copy_of(dev: DeviceState, key: str, ref_thetas: Sequence[np.ndarray], what: str):
+    """model_copy must be round-to-nearest-even of the fp32 buffer `key`, and near the oracle."""
+    for i, (c, th) in enumerate(zip(dev.views["model_copy"], dev.views[key])):
+        got_bits = c.detach().cpu().view(torch.int16).numpy().view(np.uint16)
+        np.testing.assert_array_equal(got_bits, O.bf16_round_bits(th.detach().cpu().numpy()),
+                                      err_msg=f"{what}: tensor {i} copy is not RNE({key})")
         assert_close(O.bf16_bits_to_f64(got_bits), ref_thetas[i], f"{what}: tensor {i} bf16 copy", rtol=RTOL_BF16)
 
 

@@ -325,6 +325,79 @@ def test_inactive_clipping_changes_nothing():
 
 
 # ---------------------------------------------------------------------------------------------
+# explicit lookahead: n real fast steps, reposition, slow correction (the scheme the paper compares with)
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n_steps,grad_dtype,clip", [(3, "f32", 0.0), (5, "bf16", 0.0), (2, "f32", 20.0)])
+def test_explicit_lookahead_lockstep(n_steps, grad_dtype, clip):
+    numels = RAGGED
+    problem = synth.policy_problem(sum(numels), seed=41, sigma=0.05, device="cuda")
+    cfg = B.make_config(grad_dtype=grad_dtype, alpha=0.5, lr=1e-4, explicit_steps=n_steps, clip_norm=clip, gate_min_count=2,
+                        copy_mask=7)
+    dev, ctx, orc, grads = build(numels, cfg, problem, with_copy=True)
+    g_fast, _, g_slow = grads
+    for step in range(3):
+        noise = synth.step_noise(problem, step)
+        grad_fn = quad_trainer(problem, numels, step_noise=lambda: noise)
+        st = B.gxpo_get_state(ctx)
+        H.sync_oracle_to_device(orc, dev, st.optim_steps)
+        start = dev.host("theta")
+        src = dev.views["theta"]
+        for j in range(n_steps):
+            grad_fn(src, g_fast)
+            with pytest.raises(B.GxpoError):
+                B.gxpo_fast_steps(ctx, j + 1 if j + 1 < n_steps else 0, g_fast)        # out of order
+            B.gxpo_fast_steps(ctx, j, g_fast)
+            ref = orc.explicit_fast_step(j, [H.f64(g) for g in g_fast])
+            src = dev.views["theta_probe"]
+            for i in range(len(numels)):
+                H.assert_close(dev.host("theta_probe")[i], ref[i], f"explicit step {j} tensor {i}")
+                H.assert_close(dev.host("v")[i], orc.v[i], f"explicit step {j} v tensor {i}")
+            H.check_bf16_copy_of(dev, "theta_probe", ref, f"explicit step {j}")
+        B.gxpo_extrapolate(ctx)
+        ref_t = orc.explicit_reposition()
+        num = den = 0.0
+        for i in range(len(numels)):
+            got = dev.host("theta")[i]
+            H.assert_close(got, ref_t[i], f"explicit theta~ tensor {i}")
+            num += float(np.sum(((got - start[i]) - (ref_t[i] - start[i])) ** 2)); den += float(np.sum((ref_t[i] - start[i]) ** 2))
+        assert math.sqrt(num) <= 1e-4 * math.sqrt(den) + (2 + n_steps) * 2.0 ** -24 * math.sqrt(sum(float(np.sum(r * r)) for r in ref_t))
+        grad_fn(dev.views["theta"], g_slow)
+        B.gxpo_slow_step(ctx, g_slow)
+        ref_n = orc.slow_step([H.f64(g) for g in g_slow])
+        info, ref_info = B.gxpo_gate(ctx), orc.gate_step()
+        for i in range(len(numels)):
+            H.assert_close(dev.host("theta")[i], ref_n[i], f"explicit theta^(t+1) tensor {i}")
+        assert info.norm == pytest.approx(ref_info.norm, rel=1e-12) and bool(info.tripped) == ref_info.tripped
+        dev.check_canaries()
+    st = B.gxpo_get_state(ctx)
+    assert st.backward_passes == orc.backward_passes == 3 * (n_steps + 1) and st.optim_steps == 3 * (n_steps + 1)
+
+
+def test_explicit_lookahead_matches_extrapolation_on_the_surrogate():
+    """Plain GD on the diagonal quadratic: K real fast steps and the 3-pass extrapolation reach the same theta~."""
+    P, eta, K = 1 << 18, 0.1, 5
+    problem = synth.surrogate_problem(P, 0, device="cuda")
+    outs = []
+    for explicit in (0, K):
+        cfg = B.make_config(optimizer="gd", K=K, alpha=1.0, delta=0.0, lr=eta, explicit_steps=explicit)
+        dev, ctx, orc, grads = build([P], cfg, problem)
+        grad_fn = quad_trainer(problem, [P])
+        g = grads[0]
+        if explicit:
+            src = dev.views["theta"]
+            for j in range(K):
+                grad_fn(src, g); B.gxpo_fast_steps(ctx, j, g); src = dev.views["theta_probe"]
+            B.gxpo_extrapolate(ctx)
+        else:
+            grad_fn(dev.views["theta"], grads[0]); B.gxpo_fast_steps(ctx, 0, grads[0])
+            grad_fn(dev.views["theta_probe"], grads[1]); B.gxpo_fast_steps(ctx, 1, grads[1])
+            B.gxpo_extrapolate(ctx, grads[0], grads[1])
+        outs.append(dev.host("theta")[0])
+    start = H.f64(problem.theta_0)
+    assert np.linalg.norm(outs[0] - outs[1]) <= 2e-6 * np.linalg.norm(outs[1] - start)
+
+
+# ---------------------------------------------------------------------------------------------
 # gate transition and fallback (config 5 at reduced size)
 # ---------------------------------------------------------------------------------------------
 def test_gate_transition_free_running_and_fallback():

@@ -60,6 +60,8 @@ def test_default_config_is_valid():
     (dict(waves_per_block=3), B.GXPO_ERR_INVALID_ARG),
     (dict(copy_mask=8), B.GXPO_ERR_INVALID_ARG),
     (dict(diagnostics=2), B.GXPO_ERR_INVALID_ARG),
+    (dict(explicit_steps=1), B.GXPO_ERR_INVALID_ARG),
+    (dict(explicit_steps=3, diagnostics=1), B.GXPO_ERR_INVALID_ARG),
     (dict(clip_norm=-1.0), B.GXPO_ERR_INVALID_ARG),
     (dict(clip_norm=float("inf")), B.GXPO_ERR_INVALID_ARG),
     (dict(optimizer=7), B.GXPO_ERR_UNSUPPORTED),
@@ -73,7 +75,8 @@ def test_bad_configs_are_rejected_with_a_message(kwargs, code):
 
 @pytest.mark.parametrize("kwargs", [dict(K=2), dict(alpha=0.0), dict(alpha=1.0), dict(delta=math.inf),
                                     dict(delta=0.0), dict(r_max=1.0), dict(optimizer="gd"), dict(grad_dtype="bf16"),
-                                    dict(gate_min_count=2), dict(window=B.GXPO_MAX_WINDOW), dict(tau=-1.0)])
+                                    dict(gate_min_count=2), dict(window=B.GXPO_MAX_WINDOW), dict(tau=-1.0), dict(explicit_steps=5),
+                                    dict(clip_norm=1.0)])
 def test_edge_configs_are_accepted(kwargs):
     rc, msg = B.gxpo_validate_config(B.make_config(**kwargs))
     assert rc == B.GXPO_OK, msg
