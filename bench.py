@@ -8,7 +8,7 @@ are produced once, before the timed region, by the synthetic trainer at the
 points the algorithm asks for them (theta, theta^{t,1}, theta~) and are then
 reused: computing gradients is the trainer's work, not the engine's.
 
-Prints ONE JSON line (see the design doc for the fields).  `--workload` selects a
+Prints ONE JSON line (throughput, per-kernel roofline, CPU baseline).  `--workload` selects a
 parity-test configuration instead of the default one for ad-hoc measurements.
 """
 from __future__ import annotations
@@ -101,7 +101,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU only (asked for --gpus {args.gpus}); "
-              "sharding is described in DESIGN.md, not implemented", file=sys.stderr)
+              "sharding over data-parallel ranks is not implemented", file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -6,7 +6,7 @@ gradient buffers).  On MI355X the achieved bandwidth of such a pass depends on
 how the base addresses of those arrays relate modulo 64 KiB: when all of them
 share one phase the memory system serves them ~7 % slower than when about half
 of the traffic sits 32 KiB out of phase with the other half (measured: 77 %
-against 83.6 % of the 8 TB/s peak for the AdamW passes; the design doc has the table).
+against 83.6 % of the 8 TB/s peak for the AdamW passes).
 
 The rule used here: parameters, the probe buffer and gradients keep phase 0,
 the AdamW moments m and v are placed 32 KiB (mod 64 KiB) away from them.  The

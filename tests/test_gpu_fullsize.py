@@ -1,4 +1,4 @@
-"""GPU parity at BASELINE.json's full sizes, in the launch configuration bench.py times
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times
 (fused second step, one wave per block, phased HBM layout).
 
 The oracle cannot run 1.5e9 - 8e9 coordinates in seconds, but every step of the path is

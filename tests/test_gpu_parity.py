@@ -97,6 +97,29 @@ def test_adamw_ragged_lockstep(fused, grad_dtype, wpb):
     assert (st.t, st.optim_steps, st.backward_passes) == (4, 12, 12)
 
 
+@pytest.mark.parametrize("fused", [True, False])
+def test_lockstep_on_a_side_stream(fused):
+    """Every call takes the caller's stream: run a whole active step, with clipping and
+    diagnostics so that every kernel and both host read-backs are involved, on a
+    non-default stream (default priority) while the default stream stays idle."""
+    numels = [4099, 257, 70001]
+    problem = synth.policy_problem(sum(numels), seed=9, sigma=0.05, device="cuda")
+    cfg = B.make_config(K=8, alpha=0.5, delta=1.75e-3, lr=1e-4, weight_decay=0.01, fuse_step2=fused, gate_min_count=2,
+                        diagnostics=1, clip_norm=5.0)
+    dev, ctx, orc, grads = build(numels, cfg, problem)
+    step_id = [0]
+    grad_fn = quad_trainer(problem, numels, step_noise=lambda: synth.step_noise(problem, step_id[0]))
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        assert torch.cuda.current_stream().cuda_stream == side.cuda_stream != 0
+        for step in range(3):
+            step_id[0] = step
+            H.lockstep_active_step(ctx, dev, orc, grad_fn, grads, dtol=1e-4, fused=fused, what=f"side stream step {step}")
+        side.synchronize()
+    assert B.gxpo_get_state(ctx).t == 3
+
+
 @pytest.mark.parametrize("K", [2, 3, 5, 10])
 @pytest.mark.parametrize("alpha", [0.0, 0.1, 0.5, 1.0])
 def test_paper_K_alpha_grid(K, alpha):
