@@ -49,6 +49,9 @@
  *  - Gradient lists are host arrays of n_tensors device pointers, one per
  *    parameter tensor, in gxpo_init() order; element i of a gradient buffer
  *    belongs to element i of that tensor.  Gradient buffers are never written.
+ *    A gradient buffer that overlaps one of the context's buffers, and a g1
+ *    that overlaps g0 while the extrapolation still needs both, are refused
+ *    with GXPO_ERR_INVALID_ARG (g_slow may reuse g0's buffers).
  *  - fp32 buffers must be 16-byte aligned, bf16 buffers 8-byte aligned
  *    (GXPO_ERR_ALIGNMENT otherwise).  Any numel >= 1 is accepted.
  */

@@ -31,6 +31,8 @@ constexpr int kGradRoles = 3;        // g0, g1, g_slow
 constexpr int kStageSlots = 8;       // pinned staging slots for pointer-table uploads
 enum { kRoleG0 = 0, kRoleG1 = 1, kRoleSlow = 2 };
 
+struct Interval { uintptr_t lo, hi; uint32_t t; const char *what; };
+
 }  // namespace
 
 struct gxpo_ctx {
@@ -40,6 +42,7 @@ struct gxpo_ctx {
     int device = -1;
     std::vector<gxpo_tensor> tensors;
     std::vector<uint32_t> blk_start;
+    std::vector<Interval> owned;             // every engine buffer, sorted by address, pairwise disjoint
 
     // device tables
     TensorRec *d_tab = nullptr;
@@ -168,8 +171,6 @@ int check_device_range(const gxpo_ctx *ctx, const void *p, uint64_t bytes, const
     return GXPO_OK;
 }
 
-struct Interval { uintptr_t lo, hi; uint32_t t; const char *what; };
-
 template <typename T> int dev_alloc(gxpo_ctx *ctx, T **p, size_t count) {
     hipError_t e = hipMalloc((void **)p, std::max<size_t>(count, 1) * sizeof(T));
     if (e != hipSuccess) { *p = nullptr; return fail(nullptr, GXPO_ERR_NOMEM, "hipMalloc of %zu bytes failed: %s", count * sizeof(T), hipGetErrorString(e)); }
@@ -215,6 +216,14 @@ int check_call(gxpo_ctx *ctx, const void *const *grads, const char *name) {
     return GXPO_OK;
 }
 
+// The engine buffer that [p, p + bytes) touches, or nullptr.
+const Interval *overlapping_buffer(const gxpo_ctx *ctx, const void *p, uint64_t bytes) {
+    const uintptr_t lo = (uintptr_t)p, hi = lo + bytes;
+    // first owned interval that ends after lo; the intervals are disjoint, so their ends are sorted too
+    auto it = std::upper_bound(ctx->owned.begin(), ctx->owned.end(), lo, [](uintptr_t x, const Interval &iv) { return x < iv.hi; });
+    return (it != ctx->owned.end() && it->lo < hi) ? &*it : nullptr;
+}
+
 // Make the device pointer table of `role` hold `grads`; returns the device table.
 int stage_grads(gxpo_ctx *ctx, int role, const void *const *grads, hipStream_t stream, GradArg *d_out) {
     const uint32_t n = ctx->n;
@@ -229,6 +238,8 @@ int stage_grads(gxpo_ctx *ctx, int role, const void *const *grads, hipStream_t s
         if ((uintptr_t)g % align) return fail(ctx, GXPO_ERR_ALIGNMENT, "gradient pointer of tensor %u is not %u-byte aligned", t, (unsigned)align);
         int rc = check_device_range(ctx, g, ctx->tensors[t].numel * gbytes, "gradient", t);
         if (rc != GXPO_OK) return rc;
+        if (const Interval *hit = overlapping_buffer(ctx, g, ctx->tensors[t].numel * gbytes))
+            return fail(ctx, GXPO_ERR_INVALID_ARG, "gradient of tensor %u overlaps %s of tensor %u", t, hit->what, hit->t);
         changed = true;
     }
     const void **d_tab = ctx->d_grads + (size_t)role * n;
@@ -413,6 +424,7 @@ int gxpo_init(gxpo_ctx **out, const gxpo_config *cfg, const gxpo_tensor *tensors
     ctx->device = device;
     ctx->tensors.assign(tensors, tensors + n_tensors);
     ctx->blk_start = blk_start;
+    ctx->owned = iv;
     ctx->n_blocks = blk_start[n_tensors];
     for (auto &s : ctx->shadow) s.assign(n_tensors, nullptr);
     ctx->st.struct_size = sizeof(gxpo_state);
@@ -491,6 +503,16 @@ int gxpo_fast_steps(gxpo_ctx *ctx, int which, const void *const *grads, void *st
         if (!x.theta_probe && !(fused && copy_at_probe && x.model_copy))
             return fail(ctx, GXPO_ERR_INVALID_ARG,
                         "tensor %u has no theta_probe: the active phase needs it unless fuse_step2 is set and theta^{t,1} goes to model_copy", t);
+    }
+    if (which == 1 && !ctx->cfg.explicit_steps) {
+        // the extrapolation reads g0 and g1 side by side: g1 must not have been written over g0
+        const uint64_t gbytes = ctx->cfg.grad_dtype == GXPO_GRAD_F32 ? 4u : 2u;
+        for (uint32_t t = 0; t < ctx->n; ++t) {
+            const uintptr_t a = (uintptr_t)ctx->shadow[kRoleG0][t], b = (uintptr_t)grads[t];
+            const uint64_t bytes = ctx->tensors[t].numel * gbytes;
+            if (b && a < b + bytes && b < a + bytes)
+                return fail(ctx, GXPO_ERR_INVALID_ARG, "gxpo_fast_steps(1): g1 of tensor %u overlaps g0, which gxpo_extrapolate still needs", t);
+        }
     }
     hipStream_t s = (hipStream_t)stream;
     GradArg d_g{};

@@ -503,7 +503,10 @@ def test_fallback_step_parity_and_bitwise_equal_to_first_fast_step(grad_dtype, f
     # warm both contexts up with one identical active step so the moments are non-trivial
     for ctx, dev in ((ctx_a, dev_a), (ctx_b, dev_b)):
         grad_fn(dev.views["theta"], g0b)
-        B.gxpo_fast_steps(ctx, 0, g0b); B.gxpo_fast_steps(ctx, 1, g0b); B.gxpo_extrapolate(ctx, g0b, g0b)
+        g1b = grads[1]
+        for a, b in zip(g1b, g0b):
+            a.copy_(b)
+        B.gxpo_fast_steps(ctx, 0, g0b); B.gxpo_fast_steps(ctx, 1, g1b); B.gxpo_extrapolate(ctx, g0b, g1b)
         B.gxpo_slow_step(ctx, g0b); B.gxpo_gate(ctx)
     for k in ("theta", "m", "v"):
         for a, b in zip(dev_a.views[k], dev_b.views[k]):
@@ -569,10 +572,13 @@ def test_call_order_state_machine_and_errors():
     B.gxpo_fast_steps(ctx, 0, g)
     refused(lambda: B.gxpo_fast_steps(ctx, 0, g))
     refused(lambda: B.gxpo_set_state(ctx, B.gxpo_get_state(ctx)))
-    B.gxpo_fast_steps(ctx, 1, g)
+    refused(lambda: B.gxpo_fast_steps(ctx, 1, g), B.GXPO_ERR_INVALID_ARG)          # g1 written over g0
+    refused(lambda: B.gxpo_fast_steps(ctx, 1, dev.views["theta"]), B.GXPO_ERR_INVALID_ARG)   # a gradient inside an engine buffer
+    g1 = [torch.randn(n, device="cuda")]
+    B.gxpo_fast_steps(ctx, 1, g1)
     refused(lambda: B.gxpo_extrapolate(ctx, g, g_other), B.GXPO_ERR_INVALID_ARG)   # not the g1 that was recorded
-    refused(lambda: B.gxpo_extrapolate(ctx, g_other, g), B.GXPO_ERR_INVALID_ARG)   # not the g0 the probe pass used
-    B.gxpo_extrapolate(ctx, g, g)
+    refused(lambda: B.gxpo_extrapolate(ctx, g_other, g1), B.GXPO_ERR_INVALID_ARG)  # not the g0 the probe pass used
+    B.gxpo_extrapolate(ctx, g, g1)
     refused(lambda: B.gxpo_fast_steps(ctx, 0, g))
     B.gxpo_slow_step(ctx, g)
     refused(lambda: B.gxpo_slow_step(ctx, g))
@@ -592,6 +598,25 @@ def test_call_order_state_machine_and_errors():
     assert (st2.t, st2.optim_steps, st2.s_star) == (7, 21, 9)
     B.gxpo_fast_steps(ctx, 0, g)                       # still active: t = 7 < s* = 9
     B.gxpo_destroy(ctx)
+
+
+def test_non_finite_slow_gradient_trips_the_gate():
+    """A NaN or infinite ||g_slow|| can never satisfy Z >= tau by comparison; the engine trips on it."""
+    n = 5000
+    for poison in (float("nan"), float("inf")):
+        problem = synth.policy_problem(n, seed=4, device="cuda")
+        dev, ctx, orc, grads = build([n], B.make_config(gate_min_count=2, lr=1e-4), problem)
+        g0, g1, gs = grads
+        for buf in (g0[0], g1[0], gs[0]):
+            buf.copy_(torch.randn(n, device="cuda"))
+        B.gxpo_fast_steps(ctx, 0, g0); B.gxpo_fast_steps(ctx, 1, g1); B.gxpo_extrapolate(ctx, g0, g1)
+        gs[0][n // 2] = poison
+        B.gxpo_slow_step(ctx, gs)
+        info = B.gxpo_gate(ctx)
+        ref = O.RollingGate(H.oracle_config(ctx.cfg).gate).step(0, float(info.norm))
+        assert not math.isfinite(info.norm) and info.tripped and not info.evaluated and info.s_star == 1 == ref.s_star
+        with pytest.raises(B.GxpoError):
+            B.gxpo_fast_steps(ctx, 0, g0)                  # fallback phase from t = 1 on
 
 
 def test_init_rejects_host_memory_and_short_allocations():
@@ -628,7 +653,8 @@ def test_norm_reduction_is_bit_reproducible_and_matches_oracle():
         for x in dev.views["theta"]:
             x.zero_()
         ctx = B.gxpo_init(cfg, dev.tensor_dicts())
-        B.gxpo_fast_steps(ctx, 0, g); B.gxpo_fast_steps(ctx, 1, g); B.gxpo_extrapolate(ctx, g, g); B.gxpo_slow_step(ctx, g)
+        g1 = [x.clone() for x in g]
+        B.gxpo_fast_steps(ctx, 0, g); B.gxpo_fast_steps(ctx, 1, g1); B.gxpo_extrapolate(ctx, g, g1); B.gxpo_slow_step(ctx, g)
         info = B.gxpo_gate(ctx)
         results.append((info.norm, tuple(B.gxpo_tensor_norms(ctx))))
         B.gxpo_destroy(ctx)
