@@ -170,6 +170,18 @@ def crafted_gradient_pairs(delta32: float):
 @pytest.mark.parametrize("r_max", [math.inf, 4.0, 1.0])
 @pytest.mark.parametrize("fused", [True, False])
 def test_scale_factor_crafted(K, r_max, fused):
+    check_scale_factor(K, r_max, fused)
+
+
+@pytest.mark.parametrize("K", [64, 65, 129])
+@pytest.mark.parametrize("fused", [True, False])
+def test_scale_factor_long_horizons(K, fused):
+    """Horizons far beyond the paper's K <= 10, with |r| clamped to 1 so that neither side overflows:
+    the series loop runs K/2 times; its rounding error grows like K 2^-24, still inside 1e-5 here."""
+    check_scale_factor(K, 1.0, fused)
+
+
+def check_scale_factor(K, r_max, fused):
     delta = 1e-3
     g0_np, g1_np = crafted_gradient_pairs(float(np.float32(delta)))
     n = g0_np.size

@@ -170,6 +170,22 @@ def test_host_gate_matches_oracle_gate(window, min_count, ddof, tau):
             assert list(st.window[:st.window_len]) == orc.buffer
 
 
+def test_host_gate_at_the_largest_window():
+    w = B.GXPO_MAX_WINDOW
+    cfg = B.make_config(window=w, tau=5.0, gate_eps=1e-8)
+    st = B.new_state()
+    orc = O.RollingGate(O.GateConfig(tau=5.0, window=w, eps=1e-8))
+    rng = np.random.default_rng(3)
+    for t in range(2 * w + 50):
+        x = float(10.0 + 0.1 * rng.normal() + (5.0 if t == 2 * w + 20 else 0.0))
+        info = B.gxpo_host_gate_step(cfg, st, x)
+        ref = orc.step(t, x)
+        assert bool(info.evaluated) == ref.evaluated == (t >= w)
+        assert (info.s_star if info.s_star >= 0 else None) == ref.s_star
+        assert st.window_len == min(t + 1, w) and list(st.window[:st.window_len]) == orc.buffer
+    assert st.s_star == 2 * w + 21
+
+
 def test_host_gate_hand_case_and_nan():
     cfg = B.make_config(window=4, gate_min_count=2, tau=2.0, gate_eps=0.5)
     st = B.new_state()
