@@ -168,6 +168,73 @@ def test_config4_llama_8b_ragged_bf16_grads_full_size():
     run_sampled_active_step(layout, seed=3, grad_dtype="bf16", with_copy=False, n_random=300)
 
 
+@pytest.mark.parametrize("clip_norm", [0.0, 1000.0])
+def test_config2_full_size_periodic_data_every_accumulator(clip_norm):
+    """Every buffer of the 1.54e9-parameter workload is a 4e6-element pattern repeated 385 times.  All of
+    the path is per-coordinate apart from sums, so the engine's full-size result must be the oracle's
+    result on ONE period, repeated (bit-identical from period to period), every mean, fraction and ratio
+    of the diagnostics must equal the one-period value and every norm sqrt(385) times it.  That checks all
+    ten reduction accumulators, the clipping pre-passes and the block plan at the benchmark's size."""
+    need_memory(70)
+    dev = torch.device("cuda:0")
+    P, period = synth.QWEN25_1P5B_PARAMS, 4_000_000
+    reps = P // period
+    assert reps * period == P and reps == 385
+    problem = synth.policy_problem(period, seed=12, sigma=0.05, device=dev)
+    flat, gflat = layout_mod.alloc_engine_state(P, dev, adam=True, grad_dtype=torch.float32)
+    tiled = lambda t: t.view(reps, period)
+    tiled(flat["theta"]).copy_(problem.theta_0)
+    cfg = B.make_config(K=5, alpha=0.5, delta=1.75e-3, lr=1e-4, weight_decay=0.01, tau=3.0, window=10, gate_min_count=2,
+                        fuse_step2=True, diagnostics=1, clip_norm=clip_norm)
+    ctx = B.gxpo_init(cfg, [dict(flat)])
+    oc = H.oracle_config(cfg)
+    oc.clip_norm = clip_norm / math.sqrt(reps)           # one period carries 1/385 of the squared norm
+    orc = O.GXPOOracle(oc, [H.f64(problem.theta_0)])
+    g0, g1, gs = ([g] for g in gflat)
+
+    def fill(gbuf, theta_period, step):
+        g = synth.quadratic_grad(problem, theta_period, synth.step_noise(problem, step))
+        tiled(gbuf).copy_(g)
+        return [H.f64(g)]
+
+    def check_state(label, theta_extra):
+        for k, ref in (("theta", orc.theta), ("m", orc.m), ("v", orc.v)):
+            rows = tiled(flat[k])
+            for r in (1, reps // 2, reps - 1):
+                assert torch.equal(rows[r], rows[0]), f"{label}: {k} differs between periods 0 and {r}"
+            H.assert_close(H.f64(rows[0]), ref[0], f"{label} {k}", extra_abs=theta_extra if k == "theta" else None)
+
+    for step in range(2):
+        a0 = fill(gflat[0], flat["theta"][:period], step)
+        B.gxpo_fast_steps(ctx, 0, g0)
+        th1 = orc.fast_step_1(a0)
+        H.assert_close(H.f64(flat["theta_probe"][:period]), th1[0], f"step {step} theta^(t,1)")
+        a1 = fill(gflat[1], flat["theta_probe"][:period], step)
+        B.gxpo_fast_steps(ctx, 1, g1)
+        orc.fast_step_2(a1)
+        B.gxpo_extrapolate(ctx, g0, g1)
+        ref_t = orc.extrapolate(a0, a1)
+        extra = 4.0 * 2.0 ** -24 * np.abs(ref_t[0]) * cfg.alpha * np.abs(orc.scale[0])
+        if clip_norm:
+            extra = extra + cfg.alpha * np.abs(orc._theta_2[0] - orc._theta_0[0]) * orc.scale[0] ** 2 * 2.0 ** -22
+        H.assert_close(H.f64(flat["theta"][:period]), ref_t[0], f"step {step} theta~", extra_abs=extra)
+        a_s = fill(gflat[2], flat["theta"][:period], step)
+        B.gxpo_slow_step(ctx, gs)
+        orc.slow_step(a_s)
+        info, ref_info = B.gxpo_gate(ctx), orc.gate_step()
+        check_state(f"step {step} after the slow step", extra)
+        assert info.norm == pytest.approx(math.sqrt(reps) * ref_info.norm, rel=1e-12)
+        got, ref = B.gxpo_get_diagnostics(ctx), orc.diagnostics()
+        for k in ("norm_g0", "norm_g1", "norm_g_slow"):
+            ref[k] *= math.sqrt(reps)
+        H.check_diagnostics(got, ref, aliased=False, what=f"full-size periodic step {step} clip={clip_norm}")
+        if clip_norm:
+            assert ref["norm_g0"] > 1.5 * clip_norm          # the threshold bites
+        # the next step starts from the engine's own state
+        orc.theta, orc.m, orc.v = [H.f64(flat["theta"][:period])], [H.f64(flat["m"][:period])], [H.f64(flat["v"][:period])]
+    B.gxpo_destroy(ctx)
+
+
 @pytest.mark.parametrize("K,alpha", [(3, 0.1), (5, 1.0), (10, 0.5)])
 def test_lora_shaped_many_small_tensors_paper_grid(K, alpha):
     """224 rank-128 adapter tensors (the paper's Qwen2.5-7B runs train LoRA adapters on q, k, v, o),
