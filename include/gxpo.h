@@ -245,6 +245,18 @@ int gxpo_get_diagnostics(gxpo_ctx *ctx, gxpo_diagnostics *out_host, void *stream
 int gxpo_get_state(const gxpo_ctx *ctx, gxpo_state *out);
 int gxpo_set_state(gxpo_ctx *ctx, const gxpo_state *in);
 
+/* Replaces the scalar inputs of Algorithm 1 (its "Require" line: K, alpha,
+ * delta, tau, the learning rate) and the other numeric settings (betas,
+ * adam_eps, weight_decay, r_max, the clip_norm value, gate_eps, gate_ddof,
+ * gate_min_count, window, copy_mask) between two training steps, e.g. for a
+ * learning-rate or alpha schedule.  Takes effect from the next call on.  What
+ * shapes the context's tables and workspace must equal what gxpo_init was
+ * given (optimizer, grad_dtype, fuse_step2, waves_per_block, diagnostics,
+ * explicit_steps, and whether clip_norm is zero): GXPO_ERR_INVALID_ARG
+ * otherwise.  Phase must be IDLE (GXPO_ERR_BAD_STATE).  A smaller window keeps
+ * the most recent norms.  Launches nothing. */
+int gxpo_update_config(gxpo_ctx *ctx, const gxpo_config *cfg);
+
 /* Message of the last failure on `ctx`, or of the last failed gxpo_init on
  * this thread when ctx is NULL.  Never NULL; valid until the next call. */
 const char *gxpo_last_error(const gxpo_ctx *ctx);

@@ -43,7 +43,7 @@ GXPO_MAX_WINDOW = 256
 EXPORTED_SYMBOLS = [
     "gxpo_init", "gxpo_destroy", "gxpo_fast_steps", "gxpo_extrapolate", "gxpo_slow_step", "gxpo_gate",
     "gxpo_fallback_step", "gxpo_tensor_norms", "gxpo_get_diagnostics", "gxpo_get_state", "gxpo_set_state", "gxpo_last_error",
-    "gxpo_validate_config", "gxpo_host_gate_step", "gxpo_plan_blocks", "gxpo_stream_copy",
+    "gxpo_validate_config", "gxpo_host_gate_step", "gxpo_plan_blocks", "gxpo_stream_copy", "gxpo_update_config",
 ]
 
 
@@ -109,6 +109,8 @@ _lib.gxpo_get_state.restype = ctypes.c_int
 _lib.gxpo_get_state.argtypes = [_ctx_p, ctypes.POINTER(gxpo_state)]
 _lib.gxpo_set_state.restype = ctypes.c_int
 _lib.gxpo_set_state.argtypes = [_ctx_p, ctypes.POINTER(gxpo_state)]
+_lib.gxpo_update_config.restype = ctypes.c_int
+_lib.gxpo_update_config.argtypes = [_ctx_p, ctypes.POINTER(gxpo_config)]
 _lib.gxpo_last_error.restype = ctypes.c_char_p
 _lib.gxpo_last_error.argtypes = [_ctx_p]
 _lib.gxpo_validate_config.restype = ctypes.c_int
@@ -283,6 +285,11 @@ def gxpo_get_state(ctx: Context) -> gxpo_state:
 
 def gxpo_set_state(ctx: Context, st: gxpo_state) -> None:
     ctx._check(_lib.gxpo_set_state(ctx.handle, ctypes.byref(st)))
+
+
+def gxpo_update_config(ctx: Context, cfg: gxpo_config) -> None:
+    ctx._check(_lib.gxpo_update_config(ctx.handle, ctypes.byref(cfg)))
+    ctx.cfg = cfg
 
 
 def gxpo_last_error(ctx: Optional[Context] = None) -> str:

@@ -739,6 +739,30 @@ int gxpo_set_state(gxpo_ctx *ctx, const gxpo_state *in) {
     return GXPO_OK;
 }
 
+int gxpo_update_config(gxpo_ctx *ctx, const gxpo_config *cfg) {
+    if (!ctx) return GXPO_ERR_INVALID_ARG;
+    std::string msg;
+    int rc = check_config(cfg, msg);
+    if (rc != GXPO_OK) return fail(ctx, rc, "gxpo_update_config: %s", msg.c_str());
+    if (ctx->st.phase != GXPO_PHASE_IDLE) return fail(ctx, GXPO_ERR_BAD_STATE, "gxpo_update_config: a training step is in progress");
+    const gxpo_config &o = ctx->cfg;
+    const bool same_shape = cfg->optimizer == o.optimizer && cfg->grad_dtype == o.grad_dtype && cfg->fuse_step2 == o.fuse_step2 &&
+                            resolve_wpb(cfg->waves_per_block) == ctx->wpb && cfg->diagnostics == o.diagnostics &&
+                            cfg->explicit_steps == o.explicit_steps && (cfg->clip_norm > 0.0) == (o.clip_norm > 0.0);
+    if (!same_shape)
+        return fail(ctx, GXPO_ERR_INVALID_ARG,
+                    "gxpo_update_config: optimizer, grad_dtype, fuse_step2, waves_per_block, diagnostics, explicit_steps and "
+                    "clipping on/off are fixed at gxpo_init");
+    gxpo_state &st = ctx->st;
+    if (st.window_len > cfg->window) {       // keep the most recent norms
+        const uint32_t drop = st.window_len - cfg->window;
+        std::memmove(&st.window[0], &st.window[drop], sizeof(double) * cfg->window);
+        st.window_len = cfg->window;
+    }
+    ctx->cfg = *cfg;
+    return GXPO_OK;
+}
+
 int gxpo_stream_copy(void *dst_device, const void *src_device, uint64_t bytes, void *stream) {
     if (!dst_device || !src_device) return fail(nullptr, GXPO_ERR_INVALID_ARG, "gxpo_stream_copy: NULL pointer");
     if (bytes % 16 || (uintptr_t)dst_device % 16 || (uintptr_t)src_device % 16)

@@ -612,6 +612,46 @@ def test_call_order_state_machine_and_errors():
     B.gxpo_destroy(ctx)
 
 
+def test_hyper_parameter_schedule_through_update_config():
+    """A learning-rate / alpha / K / delta schedule between steps: the engine with gxpo_update_config
+    against the oracle whose configuration is changed the same way."""
+    numels = [4099, 70001]
+    problem = synth.policy_problem(sum(numels), seed=14, sigma=0.05, device="cuda")
+    base = dict(delta=1.75e-3, weight_decay=0.01, gate_min_count=2, window=4, fuse_step2=True, tau=1e6)    # never trips
+    schedule = [dict(lr=1e-4, alpha=0.5, K=5), dict(lr=5e-5, alpha=0.25, K=8), dict(lr=2e-5, alpha=1.0, K=3, delta=1e-2, gate_eps=1e-3),
+                dict(lr=2e-5, alpha=0.5, K=4, r_max=2.0, window=2)]
+    cfg = B.make_config(**base, **schedule[0])
+    dev, ctx, orc, grads = build(numels, cfg, problem)
+    step_id = [0]
+    grad_fn = quad_trainer(problem, numels, step_noise=lambda: synth.step_noise(problem, step_id[0]))
+    for step, hp in enumerate(schedule):
+        step_id[0] = step
+        if step:
+            cfg = B.make_config(**{**base, **hp})
+            B.gxpo_update_config(ctx, cfg)
+            oc = H.oracle_config(cfg)
+            orc.cfg, orc.gate.cfg = oc, oc.gate
+            if len(orc.gate.buffer) > oc.gate.window:
+                del orc.gate.buffer[:len(orc.gate.buffer) - oc.gate.window]
+        H.lockstep_active_step(ctx, dev, orc, grad_fn, grads, dtol=1e-4, fused=True, what=f"schedule step {step}")
+    st = B.gxpo_get_state(ctx)
+    assert st.window_len == 2 and list(st.window[:2]) == orc.gate.buffer
+    # what shapes the workspace cannot change; nothing changes in the middle of a step
+    for bad in (dict(optimizer="gd"), dict(grad_dtype="bf16"), dict(fuse_step2=False), dict(waves_per_block=4),
+                dict(diagnostics=1), dict(explicit_steps=3), dict(clip_norm=1.0)):
+        with pytest.raises(B.GxpoError) as e:
+            B.gxpo_update_config(ctx, B.make_config(**{**base, **schedule[0], **bad}))
+        assert e.value.code == B.GXPO_ERR_INVALID_ARG, bad
+    with pytest.raises(B.GxpoError) as e:
+        B.gxpo_update_config(ctx, B.make_config(**{**base, **schedule[0], "K": 1}))
+    assert e.value.code == B.GXPO_ERR_INVALID_ARG
+    grad_fn(dev.views["theta"], grads[0])
+    B.gxpo_fast_steps(ctx, 0, grads[0])
+    with pytest.raises(B.GxpoError) as e:
+        B.gxpo_update_config(ctx, cfg)
+    assert e.value.code == B.GXPO_ERR_BAD_STATE
+
+
 def test_non_finite_slow_gradient_trips_the_gate():
     """A NaN or infinite ||g_slow|| can never satisfy Z >= tau by comparison; the engine trips on it."""
     n = 5000
