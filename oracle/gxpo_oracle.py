@@ -34,7 +34,7 @@ import ctypes
 import math
 import os
 import subprocess
-from dataclasses import dataclass, field
+from dataclasses import dataclass, field, replace
 from typing import List, Optional, Sequence
 
 import numpy as np
@@ -343,6 +343,9 @@ class GXPOOracle:
         self.scale = None
         self._sumsq = None
         self._g0 = self._g1 = self._g_slow = None
+        # parameter groups: per-tensor multipliers of lr and weight_decay (all 1 = the paper's uniform setting)
+        self.lr_scale = [1.0] * len(self.theta)
+        self.weight_decay_scale = [1.0] * len(self.theta)
 
     # -- phase ----------------------------------------------------------------
     @property
@@ -356,8 +359,13 @@ class GXPOOracle:
         """OptimStep on every tensor with one shared step counter."""
         outs = []
         new_count = self.optim_steps
-        for th, g, m, v in zip(thetas_in, grads, self.m, self.v):
-            out, new_count = optim_step(self.cfg.optim, self.optim_steps, th, _f64(g).ravel(), m, v)
+        for i, (th, g, m, v) in enumerate(zip(thetas_in, grads, self.m, self.v)):
+            oc = self.cfg.optim
+            if self.lr_scale[i] != 1.0 or self.weight_decay_scale[i] != 1.0:
+                # READING (the paper trains with one uniform setting): a parameter group is the same
+                # OptimStep with its own learning rate and weight decay, as optimizer libraries define it
+                oc = replace(oc, lr=oc.lr * self.lr_scale[i], weight_decay=oc.weight_decay * self.weight_decay_scale[i])
+            out, new_count = optim_step(oc, self.optim_steps, th, _f64(g).ravel(), m, v)
             outs.append(out)
         self.optim_steps = new_count
         return outs

@@ -356,6 +356,39 @@ def test_gxpo_K2_alpha1_is_three_library_adamw_steps():
     assert orc.optim_steps == 9          # the step counter runs through all three steps
 
 
+def test_parameter_groups_match_library_param_groups():
+    """Per-tensor lr / weight-decay multipliers against a library AdamW with three parameter groups
+    (decay, no decay, lower learning rate), K = 2 and alpha = 1 so that GXPO is three plain steps."""
+    rng = np.random.default_rng(8)
+    sizes = [300, 17, 120]
+    lr, wd, eps = 1e-3, 0.1, 1e-8
+    lr_scale, wd_scale = [1.0, 1.0, 0.25], [1.0, 0.0, 2.0]
+    th0 = [rng.normal(scale=0.5, size=n) for n in sizes]
+    cfg = O.GXPOConfig(optim=O.OptimConfig("adamw", lr=lr, eps=eps, weight_decay=wd), K=2, alpha=1.0, delta=1e-8)
+    orc = O.GXPOOracle(cfg, th0)
+    orc.lr_scale, orc.weight_decay_scale = lr_scale, wd_scale
+    params = [torch.nn.Parameter(torch.tensor(t, dtype=torch.float64)) for t in th0]
+    opt = torch.optim.AdamW([dict(params=[p], lr=lr * a, weight_decay=wd * b) for p, a, b in zip(params, lr_scale, wd_scale)],
+                            betas=(0.9, 0.999), eps=eps, foreach=False)
+
+    def lib_step(gs):
+        for p, g in zip(params, gs):
+            p.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+    for step in range(2):
+        g0, g1, gs = ([rng.normal(scale=0.05, size=n) for n in sizes] for _ in range(3))
+        orc.fast_step_1(g0); lib_step(g0)
+        orc.fast_step_2(g1); lib_step(g1)
+        orc.extrapolate(g0, g1)
+        orc.slow_step(gs); lib_step(gs)
+        orc.gate_step()
+    for i, p in enumerate(params):
+        np.testing.assert_allclose(orc.theta[i], p.detach().numpy(), rtol=1e-11, atol=1e-15)
+        np.testing.assert_allclose(orc.m[i], opt.state[p]["exp_avg"].numpy(), rtol=1e-12)
+    # the groups really differ: tensor 1 saw no decay, tensor 2 a quarter of the step
+    assert orc.optim_steps == 6
+
+
 def test_optimizer_state_is_not_rolled_back_on_reposition():
     """With alpha = 0 the parameters return to theta^t before the slow step but
     the moments and the step counter keep what the two probes did."""
