@@ -203,6 +203,11 @@ def main():
             events.setdefault(name, []).append((a, b))
         return B.gxpo_gate(ctx)
 
+    # the interpreter's cyclic collector is not part of the path: a full collection (tens of ms with torch
+    # loaded) landing inside the timed region would leave the GPU idle behind the gate's synchronisation
+    import gc
+    gc.collect()
+    gc.disable()
     for _ in range(args.warmup):
         active_step()
     torch.cuda.synchronize()
@@ -212,6 +217,7 @@ def main():
         info = active_step(events)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    gc.enable()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     kernel_ms = {k: sum(a.elapsed_time(b) for a, b in v) / len(v) for k, v in events.items()}
     bpp = bytes_per_param(spec, fused)

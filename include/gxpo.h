@@ -257,6 +257,22 @@ int gxpo_set_state(gxpo_ctx *ctx, const gxpo_state *in);
  * the most recent norms.  Launches nothing. */
 int gxpo_update_config(gxpo_ctx *ctx, const gxpo_config *cfg);
 
+/* Parameter groups: per-tensor multipliers of config.lr and config.weight_decay
+ * (optimizer libraries' "param groups": e.g. no weight decay on norm weights and
+ * biases, a lower learning rate for embeddings).  Tensor i then takes every
+ * OptimStep of Algorithm 1 with lr * lr_scale[i] and, for AdamW, weight decay
+ * weight_decay * weight_decay_scale[i]; everything else (extrapolation, gate,
+ * clipping, diagnostics) is unchanged.  All multipliers are 1 after gxpo_init.
+ * `opts` is a host array of n_tensors entries; values must be finite and >= 0
+ * (lr_scale 0 freezes a tensor's parameters while its moments keep advancing).
+ * Phase must be IDLE.  Waits for the device (the table the kernels read is
+ * replaced), so call it at set-up, not per step. */
+typedef struct gxpo_tensor_options {
+    double lr_scale;
+    double weight_decay_scale;
+} gxpo_tensor_options;
+int gxpo_set_tensor_options(gxpo_ctx *ctx, const gxpo_tensor_options *opts);
+
 /* Message of the last failure on `ctx`, or of the last failed gxpo_init on
  * this thread when ctx is NULL.  Never NULL; valid until the next call. */
 const char *gxpo_last_error(const gxpo_ctx *ctx);

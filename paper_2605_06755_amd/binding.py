@@ -44,6 +44,7 @@ EXPORTED_SYMBOLS = [
     "gxpo_init", "gxpo_destroy", "gxpo_fast_steps", "gxpo_extrapolate", "gxpo_slow_step", "gxpo_gate",
     "gxpo_fallback_step", "gxpo_tensor_norms", "gxpo_get_diagnostics", "gxpo_get_state", "gxpo_set_state", "gxpo_last_error",
     "gxpo_validate_config", "gxpo_host_gate_step", "gxpo_plan_blocks", "gxpo_stream_copy", "gxpo_update_config",
+    "gxpo_set_tensor_options",
 ]
 
 
@@ -62,6 +63,10 @@ class gxpo_config(ctypes.Structure):
                 ("adam_eps", ctypes.c_double), ("weight_decay", ctypes.c_double),
                 ("alpha", ctypes.c_double), ("delta", ctypes.c_double), ("r_max", ctypes.c_double),
                 ("clip_norm", ctypes.c_double), ("tau", ctypes.c_double), ("gate_eps", ctypes.c_double)]
+
+
+class gxpo_tensor_options(ctypes.Structure):
+    _fields_ = [("lr_scale", ctypes.c_double), ("weight_decay_scale", ctypes.c_double)]
 
 
 class gxpo_gate_info(ctypes.Structure):
@@ -111,6 +116,8 @@ _lib.gxpo_set_state.restype = ctypes.c_int
 _lib.gxpo_set_state.argtypes = [_ctx_p, ctypes.POINTER(gxpo_state)]
 _lib.gxpo_update_config.restype = ctypes.c_int
 _lib.gxpo_update_config.argtypes = [_ctx_p, ctypes.POINTER(gxpo_config)]
+_lib.gxpo_set_tensor_options.restype = ctypes.c_int
+_lib.gxpo_set_tensor_options.argtypes = [_ctx_p, ctypes.POINTER(gxpo_tensor_options)]
 _lib.gxpo_last_error.restype = ctypes.c_char_p
 _lib.gxpo_last_error.argtypes = [_ctx_p]
 _lib.gxpo_validate_config.restype = ctypes.c_int
@@ -290,6 +297,15 @@ def gxpo_set_state(ctx: Context, st: gxpo_state) -> None:
 def gxpo_update_config(ctx: Context, cfg: gxpo_config) -> None:
     ctx._check(_lib.gxpo_update_config(ctx.handle, ctypes.byref(cfg)))
     ctx.cfg = cfg
+
+
+def gxpo_set_tensor_options(ctx: Context, lr_scale: Sequence[float], weight_decay_scale: Sequence[float]) -> None:
+    if len(lr_scale) != ctx.n_tensors or len(weight_decay_scale) != ctx.n_tensors:
+        raise ValueError(f"expected {ctx.n_tensors} multipliers of each kind")
+    arr = (gxpo_tensor_options * ctx.n_tensors)()
+    for i, (a, b) in enumerate(zip(lr_scale, weight_decay_scale)):
+        arr[i].lr_scale, arr[i].weight_decay_scale = float(a), float(b)
+    ctx._check(_lib.gxpo_set_tensor_options(ctx.handle, arr))
 
 
 def gxpo_last_error(ctx: Optional[Context] = None) -> str:

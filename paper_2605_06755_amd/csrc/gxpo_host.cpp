@@ -41,6 +41,7 @@ struct gxpo_ctx {
     uint32_t wpb = kDefaultWavesPerBlock;
     int device = -1;
     std::vector<gxpo_tensor> tensors;
+    std::vector<gxpo_tensor_options> options;   // parameter groups, all {1, 1} unless set
     std::vector<uint32_t> blk_start;
     std::vector<Interval> owned;             // every engine buffer, sorted by address, pairwise disjoint
 
@@ -78,10 +79,13 @@ struct gxpo_ctx {
     gxpo_state st{};
     mutable std::string err;
 
-    Layout layout() const {
-        const gxpo_tensor &x = tensors[0];
-        return Layout{d_tab, d_blk_start, d_coarse, n, n_blocks, TensorRec{x.theta, x.theta_probe, x.m, x.v, x.model_copy, x.numel}};
+    TensorRec record(uint32_t t) const {
+        const gxpo_tensor &x = tensors[t];
+        const gxpo_tensor_options &o = options[t];
+        return TensorRec{x.theta, x.theta_probe, x.m, x.v, x.model_copy, x.numel, (float)o.lr_scale,
+                         (float)(o.lr_scale * o.weight_decay_scale)};
     }
+    Layout layout() const { return Layout{d_tab, d_blk_start, d_coarse, n, n_blocks, record(0)}; }
 };
 
 namespace {
@@ -423,6 +427,7 @@ int gxpo_init(gxpo_ctx **out, const gxpo_config *cfg, const gxpo_tensor *tensors
     ctx->n_acc = (cfg->diagnostics || cfg->clip_norm > 0.0) ? (uint32_t)kNumAcc : 1u;
     ctx->device = device;
     ctx->tensors.assign(tensors, tensors + n_tensors);
+    ctx->options.assign(n_tensors, gxpo_tensor_options{1.0, 1.0});
     ctx->blk_start = blk_start;
     ctx->owned = iv;
     ctx->n_blocks = blk_start[n_tensors];
@@ -443,8 +448,7 @@ int gxpo_init(gxpo_ctx **out, const gxpo_config *cfg, const gxpo_tensor *tensors
     ctx->n_segs = (uint32_t)segs.size();
 
     std::vector<TensorRec> tab(n_tensors);
-    for (uint32_t t = 0; t < n_tensors; ++t)
-        tab[t] = TensorRec{tensors[t].theta, tensors[t].theta_probe, tensors[t].m, tensors[t].v, tensors[t].model_copy, tensors[t].numel};
+    for (uint32_t t = 0; t < n_tensors; ++t) tab[t] = ctx->record(t);
     std::vector<uint32_t> coarse;
     if (n_tensors > 1) {
         coarse.resize(((size_t)ctx->n_blocks >> kCoarseShift) + 1);
@@ -760,6 +764,33 @@ int gxpo_update_config(gxpo_ctx *ctx, const gxpo_config *cfg) {
         st.window_len = cfg->window;
     }
     ctx->cfg = *cfg;
+    return GXPO_OK;
+}
+
+int gxpo_set_tensor_options(gxpo_ctx *ctx, const gxpo_tensor_options *opts) {
+    if (!ctx) return GXPO_ERR_INVALID_ARG;
+    if (!opts) return fail(ctx, GXPO_ERR_INVALID_ARG, "gxpo_set_tensor_options: options are NULL");
+    if (ctx->st.phase != GXPO_PHASE_IDLE) return fail(ctx, GXPO_ERR_BAD_STATE, "gxpo_set_tensor_options: a training step is in progress");
+    for (uint32_t t = 0; t < ctx->n; ++t) {
+        const double a = opts[t].lr_scale, b = opts[t].weight_decay_scale;
+        if (!(a >= 0.0) || !std::isfinite(a) || !(b >= 0.0) || !std::isfinite(b))
+            return fail(ctx, GXPO_ERR_INVALID_ARG, "gxpo_set_tensor_options: tensor %u: multipliers must be finite and >= 0", t);
+    }
+    int dev = -1;
+    GXPO_HIP(ctx, hipGetDevice(&dev));
+    if (dev != ctx->device)
+        return fail(ctx, GXPO_ERR_INVALID_ARG, "gxpo_set_tensor_options: current device %d is not the context's device %d", dev, ctx->device);
+    const std::vector<gxpo_tensor_options> before = ctx->options;
+    ctx->options.assign(opts, opts + ctx->n);
+    std::vector<TensorRec> tab(ctx->n);
+    for (uint32_t t = 0; t < ctx->n; ++t) tab[t] = ctx->record(t);
+    // kernels of earlier calls may still be reading the table
+    hipError_t e = hipDeviceSynchronize();
+    if (e == hipSuccess) e = hipMemcpy(ctx->d_tab, tab.data(), sizeof(TensorRec) * ctx->n, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        ctx->options = before;
+        return fail_hip(ctx, e, "gxpo_set_tensor_options: table upload");
+    }
     return GXPO_OK;
 }
 

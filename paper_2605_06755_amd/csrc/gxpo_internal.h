@@ -22,6 +22,8 @@ struct TensorRec {          // device copy of one gxpo_tensor
     float *v;
     void *copy;             // bf16 model copy or nullptr
     uint64_t numel;
+    float lr_scale;         // parameter group: multiplies the step size (1 = the context's lr)
+    float lr_wd_scale;      // lr_scale * weight_decay_scale: multiplies lr * weight_decay
 };
 
 // How the 1-D grid covers the ragged tensor list: tensor t owns blocks

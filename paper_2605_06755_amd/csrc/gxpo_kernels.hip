@@ -163,6 +163,15 @@ __device__ __forceinline__ float optim_update(float theta, float &m, float &v, f
     return fmaf(p.lr_wd, theta, p.step_size * (m / denom));
 }
 
+// The step constants of one tensor: its parameter group scales the learning rate and the
+// decoupled decay.  Multipliers of exactly 1 leave every constant bit-identical.
+__device__ __forceinline__ StepParams for_tensor(StepParams p, const TensorRec &rec) {
+    p.lr *= rec.lr_scale;
+    p.step_size *= rec.lr_scale;
+    p.lr_wd *= rec.lr_wd_scale;
+    return p;
+}
+
 // ---- extrapolation factor (Eqs. (4), (7); Algorithm 1 "Extrapolation factor") -------------
 // scale = S_K(r)/S_2(r) with r = g1/g0, written so that nothing cancels:
 //   K even: S_K/S_2 = sum_{j<K/2} r^{2j}
@@ -290,10 +299,11 @@ __device__ __forceinline__ void add_extrap_diag(double (&acc)[kNumExtrapAcc], fl
 // (20 B/param: 16 read, 4 written; 18 when only the bf16 copy is written).
 // ============================================================================
 template <int WPB, int OPT, int GDT>
-__global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, GradArg grads, StepParams p, int src, int dst,
+__global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, GradArg grads, StepParams p_all, int src, int dst,
                                                        int write_moments, int write_copy, double *__restrict__ partial,
                                                        GradArg dot_with, const float *__restrict__ clip, int clip_index) {
     const Span s = locate<WPB>(L, blockIdx.x);
+    const StepParams p = for_tensor(p_all, s.rec);
     const uint32_t elem = threadIdx.x * kLaneElems;
     const uint32_t bytes = s.cnt * 4u;
     const float *src_ptr = (src == kSrcProbe ? s.rec.probe : s.rec.theta) + s.e0;
@@ -422,11 +432,12 @@ __global__ __launch_bounds__(64 * WPB) void k_reposition(Layout L, float alpha, 
 // 32 B/param with fp32 gradients (20 read, 12 written).
 // ============================================================================
 template <int WPB, int OPT, int GDT, bool DIAG>
-__global__ __launch_bounds__(64 * WPB) void k_fused_steps_extrapolate(Layout L, GradArg g0s, GradArg g1s, StepParams p1,
-                                                                    StepParams p2, ExtrapParams e, int write_copy,
+__global__ __launch_bounds__(64 * WPB) void k_fused_steps_extrapolate(Layout L, GradArg g0s, GradArg g1s, StepParams p1_all,
+                                                                    StepParams p2_all, ExtrapParams e, int write_copy,
                                                                     double *__restrict__ diag_partial,
                                                                     const float *__restrict__ clip) {
     const Span s = locate<WPB>(L, blockIdx.x);
+    const StepParams p1 = for_tensor(p1_all, s.rec), p2 = for_tensor(p2_all, s.rec);
     const uint32_t elem = threadIdx.x * kLaneElems;
     const uint32_t bytes = s.cnt * 4u;
     const auto r_th = span_rsrc(s.rec.theta + s.e0, bytes);

@@ -612,6 +612,62 @@ def test_call_order_state_machine_and_errors():
     B.gxpo_destroy(ctx)
 
 
+@pytest.mark.parametrize("fused", [True, False])
+@pytest.mark.parametrize("optimizer,numels", [("adamw", RAGGED), ("adamw", [70001]), ("gd", [257, 4099, 5])])
+def test_parameter_groups_lockstep(fused, optimizer, numels):
+    """Per-tensor lr / weight-decay multipliers (no decay on some tensors, a lower or zero learning rate on
+    others), on the ragged list, on a single flat tensor (pointers and multipliers from the kernel
+    arguments) and with plain GD."""
+    problem = synth.policy_problem(sum(numels), seed=15, sigma=0.05, device="cuda")
+    cfg = B.make_config(optimizer=optimizer, K=5, alpha=0.5, delta=1.75e-3, lr=1e-4, weight_decay=0.1, fuse_step2=fused,
+                        gate_min_count=2, tau=1e6)
+    dev, ctx, orc, grads = build(numels, cfg, problem)
+    pattern_lr, pattern_wd = [1.0, 0.25, 1.0, 0.0, 3.0], [1.0, 0.0, 2.0, 1.0, 0.5]
+    lr_scale = [pattern_lr[i % 5] for i in range(len(numels))] if len(numels) > 1 else [0.5]
+    wd_scale = [pattern_wd[i % 5] for i in range(len(numels))] if len(numels) > 1 else [0.0]
+    B.gxpo_set_tensor_options(ctx, lr_scale, wd_scale)
+    orc.lr_scale, orc.weight_decay_scale = list(lr_scale), list(wd_scale)
+    step_id = [0]
+    grad_fn = quad_trainer(problem, numels, step_noise=lambda: synth.step_noise(problem, step_id[0]))
+    before = dev.host("theta")
+    for step in range(3):
+        step_id[0] = step
+        H.lockstep_active_step(ctx, dev, orc, grad_fn, grads, dtol=1e-4, fused=fused, what=f"groups step {step}")
+    after = dev.host("theta")
+    for i, a in enumerate(lr_scale):
+        if a == 0.0:
+            np.testing.assert_array_equal(after[i], before[i])          # a frozen tensor does not move at all
+    # refused: wrong values, mid-step
+    with pytest.raises(B.GxpoError) as e:
+        B.gxpo_set_tensor_options(ctx, [-1.0] * len(numels), wd_scale)
+    assert e.value.code == B.GXPO_ERR_INVALID_ARG
+    with pytest.raises(B.GxpoError) as e:
+        B.gxpo_set_tensor_options(ctx, lr_scale, [float("nan")] * len(numels))
+    assert e.value.code == B.GXPO_ERR_INVALID_ARG
+    grad_fn(dev.views["theta"], grads[0])
+    B.gxpo_fast_steps(ctx, 0, grads[0])
+    with pytest.raises(B.GxpoError) as e:
+        B.gxpo_set_tensor_options(ctx, lr_scale, wd_scale)
+    assert e.value.code == B.GXPO_ERR_BAD_STATE
+
+
+def test_unit_parameter_groups_change_nothing():
+    """Multipliers of exactly 1 must leave every result bit-identical to a context that never set them."""
+    numels = [4099, 257]
+    problem = synth.policy_problem(sum(numels), seed=16, sigma=0.05, device="cuda")
+    cfg = B.make_config(K=8, alpha=0.5, delta=1.75e-3, lr=1e-4, weight_decay=0.01, gate_min_count=2)
+    runs = []
+    for set_them in (False, True):
+        dev, ctx, orc, grads = build(numels, cfg, problem)
+        if set_them:
+            B.gxpo_set_tensor_options(ctx, [1.0, 1.0], [1.0, 1.0])
+        grad_fn = quad_trainer(problem, numels, step_noise=lambda: synth.step_noise(problem, 0))
+        H.lockstep_active_step(ctx, dev, orc, grad_fn, grads, dtol=1e-4, fused=True, what="unit groups")
+        runs.append([x.clone() for k in ("theta", "m", "v") for x in dev.views[k]])
+    for a, b in zip(*runs):
+        assert torch.equal(a, b)
+
+
 def test_hyper_parameter_schedule_through_update_config():
     """A learning-rate / alpha / K / delta schedule between steps: the engine with gxpo_update_config
     against the oracle whose configuration is changed the same way."""

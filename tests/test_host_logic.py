@@ -29,6 +29,7 @@ def test_struct_sizes_match_the_header_layout():
     # natural C layout of the header's structs on x86-64
     assert ctypes.sizeof(B.gxpo_tensor) == 8 + 5 * 8
     assert ctypes.sizeof(B.gxpo_config) == 12 * 4 + 11 * 8
+    assert ctypes.sizeof(B.gxpo_tensor_options) == 2 * 8
     assert ctypes.sizeof(B.gxpo_diagnostics) == 9 * 8 + 8
     assert ctypes.sizeof(B.gxpo_gate_info) == 4 * 8 + 2 * 4 + 2 * 8
     assert ctypes.sizeof(B.gxpo_state) == 2 * 4 + 4 * 8 + 2 * 4 + 8 * B.GXPO_MAX_WINDOW
