@@ -172,6 +172,81 @@ def test_planted_mistake_in_the_gate_is_caught(variant, golden_dir, monkeypatch)
     assert gate_battery_fails(golden_dir), f"no pin noticed the gate mutation: {variant}"
 
 
+def driver_battery_fails(golden_dir) -> bool:
+    checks = [lambda: pins.test_extrapolated_point_equals_K_gd_steps(4), lambda: pins.test_partial_reposition_closed_form(0.5),
+              pins.test_gxpo_K2_alpha1_is_three_library_adamw_steps, pins.test_parameter_groups_match_library_param_groups,
+              lambda: pins.test_backward_pass_budget_matches_printed_table(golden_dir),
+              pins.test_clipped_gxpo_step_is_the_unclipped_step_on_clipped_gradients,
+              lambda: pins.test_explicit_lookahead_equals_extrapolation_on_the_surrogate(3, 0.5)]
+    for check in checks:
+        try:
+            check()
+        except Exception:
+            return True
+    return False
+
+
+def _second_step_from_theta_0(self, g1):
+    self.backward_passes += 1
+    self._g1_used, self.norm_g1_raw, _ = O.clip_gradients(g1, self.cfg.clip_norm)
+    self._theta_2 = self._optim_all(self._theta_0, self._g1_used)          # should start from theta^{t,1}
+    return self._theta_2
+
+
+def _slow_step_from_theta_K(self, g_slow):
+    self.backward_passes += 1
+    self._sumsq = [O.sum_squares(g) for g in g_slow]
+    self._g_slow = [np.asarray(g, dtype=np.float64).ravel() for g in g_slow]
+    used, _, _ = O.clip_gradients(g_slow, self.cfg.clip_norm)
+    self.theta = self._optim_all(self.theta_K, used)                       # should start from theta~
+    return self.theta
+
+
+def _slow_step_not_counted(self, g_slow):
+    out = _REAL["slow_step"](self, g_slow)
+    self.backward_passes -= 1
+    return out
+
+
+def _fallback_takes_three_passes(self, g0):
+    out = _REAL["fallback_step"](self, g0)
+    self.backward_passes += 2
+    return out
+
+
+def _groups_scale_only_lr(self, thetas_in, grads):
+    saved = self.weight_decay_scale
+    self.weight_decay_scale = [1.0] * len(saved)
+    try:
+        return _REAL["_optim_all"](self, thetas_in, grads)
+    finally:
+        self.weight_decay_scale = saved
+
+
+def _explicit_reposition_full(self):
+    self.theta_tilde = [tn.copy() for tn in self._theta_j]                 # ignores alpha
+    return self.theta_tilde
+
+
+_REAL = {k: getattr(O.GXPOOracle, k) for k in ("slow_step", "fallback_step", "_optim_all")}
+DRIVER_MUTATIONS = {
+    "second fast step starts from theta^t": ("fast_step_2", _second_step_from_theta_0),
+    "slow step starts from theta^{t,K}": ("slow_step", _slow_step_from_theta_K),
+    "slow step's backward pass not counted": ("slow_step", _slow_step_not_counted),
+    "fallback step charged three passes": ("fallback_step", _fallback_takes_three_passes),
+    "parameter groups ignore the decay multiplier": ("_optim_all", _groups_scale_only_lr),
+    "explicit reposition ignores alpha": ("explicit_reposition", _explicit_reposition_full),
+}
+
+
+@pytest.mark.parametrize("name", list(DRIVER_MUTATIONS))
+def test_planted_mistake_in_the_step_driver_is_caught(name, golden_dir, monkeypatch):
+    assert not driver_battery_fails(golden_dir)
+    attr, mutant = DRIVER_MUTATIONS[name]
+    monkeypatch.setattr(O.GXPOOracle, attr, mutant)
+    assert driver_battery_fails(golden_dir), f"no pin noticed: {name}"
+
+
 def test_planted_mistake_in_the_driver_is_caught(golden_dir, monkeypatch):
     # the driver restores the moments when it repositions (the paper says it must not)
     real = O.GXPOOracle.extrapolate
