@@ -43,9 +43,11 @@
  *    workspace.
  *  - All GPU work is enqueued on the caller's stream (`stream` is a
  *    hipStream_t passed as void*; NULL is the default stream) and returns
- *    without waiting.  Only gxpo_gate() and gxpo_tensor_norms() wait for the
- *    stream.  Calls on one context must be issued on one stream, or be ordered
- *    by the caller.
+ *    without waiting.  Only gxpo_gate(), gxpo_tensor_norms() and
+ *    gxpo_get_diagnostics() wait for the stream (gxpo_set_tensor_options() and
+ *    gxpo_destroy() wait for the device).  Calls on one context must be issued
+ *    on one stream, or be ordered by the caller.  A context is not thread-safe:
+ *    one thread at a time per context; different contexts are independent.
  *  - Gradient lists are host arrays of n_tensors device pointers, one per
  *    parameter tensor, in gxpo_init() order; element i of a gradient buffer
  *    belongs to element i of that tensor.  Gradient buffers are never written.
