@@ -61,5 +61,24 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+ABI_DRIVER_SRC = os.path.join(ROOT, "tests", "abi", "abi_driver.c")
+ABI_DRIVER = os.path.join(ROOT, "tests", "abi", "abi_driver")
+
+
+def build_abi_driver(verbose: bool = False) -> str:
+    """The plain-C test program that drives the library through its C ABI: strict C99, gcc, no
+    Python and no torch in the process.  Needs libgxpo.so (link) and the HIP runtime's C API."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-Wextra", "-Werror", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(rocm, "include"),
+           "-I", os.path.join(ROOT, "include"), ABI_DRIVER_SRC, "-o", ABI_DRIVER,
+           "-L", PKG, "-lgxpo", "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-lm",
+           "-Wl,-rpath,$ORIGIN/../../paper_2605_06755_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    if verbose:
+        print(" ".join(cmd), file=sys.stderr)
+    _run(cmd)
+    return ABI_DRIVER
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_abi_driver(verbose=True))

@@ -773,6 +773,18 @@ def test_norm_reduction_is_bit_reproducible_and_matches_oracle():
     assert results[0][0] == pytest.approx(math.sqrt(sum(w * w for w in want)), rel=1e-13)
 
 
+def test_plain_c_program_drives_the_library():
+    """No Python, no torch in the process: a gcc-built C99 program allocates with the HIP runtime's C API,
+    calls the engine through include/gxpo.h and checks the paper's closed form for the diagonal surrogate."""
+    import os
+    import subprocess
+    from paper_2605_06755_amd import build as lib_build
+    if not os.path.exists(lib_build.ABI_DRIVER):
+        pytest.fail(f"{lib_build.ABI_DRIVER} is not built: run __graft_entry__.build() first")
+    res = subprocess.run([lib_build.ABI_DRIVER], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
+    assert res.returncode == 0 and res.stdout.strip().endswith("abi driver ok"), res.stdout
+
+
 def test_stream_copy_reference_kernel():
     for n in (4, 256, 260, 1 << 20, (1 << 20) + 12):
         src = torch.randn(n, device="cuda")

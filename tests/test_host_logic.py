@@ -25,6 +25,34 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, name), name
 
 
+@pytest.mark.parametrize("compiler,flags", [("gcc", ["-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror"]),
+                                            ("g++", ["-std=c++11", "-Wall", "-Wextra", "-Werror"])])
+def test_header_is_plain_c_and_cxx(compiler, flags, tmp_path):
+    """The boundary is a C ABI: the header must compile on its own as strict C99 and as C++,
+    and the struct sizes the binding assumes must be the compiler's."""
+    import subprocess
+    src = tmp_path / ("probe.c" if compiler == "gcc" else "probe.cpp")
+    src.write_text('#include "gxpo.h"\n#include <stdio.h>\n'
+                   'int main(void) { printf("%u %u %u %u %u %u\\n", (unsigned)sizeof(gxpo_tensor), (unsigned)sizeof(gxpo_config),\n'
+                   '  (unsigned)sizeof(gxpo_gate_info), (unsigned)sizeof(gxpo_diagnostics), (unsigned)sizeof(gxpo_state),\n'
+                   '  (unsigned)sizeof(gxpo_tensor_options)); return 0; }\n')
+    exe = tmp_path / "probe"
+    subprocess.check_call([compiler, *flags, "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)])
+    sizes = [int(x) for x in subprocess.check_output([str(exe)]).split()]
+    assert sizes == [ctypes.sizeof(t) for t in (B.gxpo_tensor, B.gxpo_config, B.gxpo_gate_info, B.gxpo_diagnostics,
+                                                B.gxpo_state, B.gxpo_tensor_options)]
+
+
+def test_plain_c_driver_links_against_the_library():
+    """The gcc-built C99 program finds libgxpo.so and the HIP runtime; without a GPU it stops at its
+    device check (exit status 2), with one it runs to the end (exit status 0)."""
+    import subprocess
+    from paper_2605_06755_amd import build as lib_build
+    assert os.path.exists(lib_build.ABI_DRIVER), "run __graft_entry__.build() first"
+    res = subprocess.run([lib_build.ABI_DRIVER], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
+    assert res.returncode in (0, 2), res.stdout
+
+
 def test_struct_sizes_match_the_header_layout():
     # natural C layout of the header's structs on x86-64
     assert ctypes.sizeof(B.gxpo_tensor) == 8 + 5 * 8
