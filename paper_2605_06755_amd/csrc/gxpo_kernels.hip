@@ -272,20 +272,95 @@ __device__ __forceinline__ void store_block_sums(double (&acc)[N], double *__res
     }
 }
 
-// Per-lane contribution of one coordinate to the extrapolation-pass diagnostics.
-__device__ __forceinline__ void add_extrap_diag(double (&acc)[kNumExtrapAcc], float g0, float g1, const ScaleInfo &si, float disp2) {
-    acc[kAccG0Sq - kAccG0Sq] = fma((double)g0, (double)g0, acc[kAccG0Sq - kAccG0Sq]);
-    acc[kAccG1Sq - kAccG0Sq] = fma((double)g1, (double)g1, acc[kAccG1Sq - kAccG0Sq]);
-    if (si.active) {
-        const double rm1 = (double)(si.r - 1.0f);        // centred on the common case r ~ 1: no cancellation in the variance
-        acc[kAccActive - kAccG0Sq] += 1.0;
-        acc[kAccR - kAccG0Sq] += rm1;
-        acc[kAccR2 - kAccG0Sq] = fma(rm1, rm1, acc[kAccR2 - kAccG0Sq]);
-        acc[kAccScale - kAccG0Sq] += (double)si.scale;
+// Per-lane accumulators of the extrapolation-pass diagnostics.  The two gradient norms must
+// match an fp64 reference to ~1e-12 and stay in fp64.  The other statistics are means and
+// ratios of fp32 quantities (r, scale and the displacements are formed in fp32 to begin
+// with): they are summed in fp32 inside a block (256 * WPB terms, pairwise over the lanes)
+// and in fp64 from the block partial on; the active count is an integer.  That keeps the
+// diagnostics from turning the pass ALU-bound (fp64 adds and 64-bit lane exchanges are the
+// expensive part of a block's reduction).
+struct ExtrapDiag {
+    double g0_sq = 0.0, g1_sq = 0.0;
+    float rm1_sum = 0.0f, rm1_sq = 0.0f, scale_sum = 0.0f, d2_sq = 0.0f, dK_sq = 0.0f;
+    uint32_t active = 0;
+};
+
+// `in_range`: the coordinate exists (lanes past the ragged end of a tensor loaded zeros; their
+// gradients add nothing, but a zero-state AdamW step with eps = 0 is 0/0, which must not reach the sums).
+__device__ __forceinline__ void add_extrap_diag(ExtrapDiag &d, float g0, float g1, const ScaleInfo &si, float disp2, bool in_range) {
+    d.g0_sq = fma((double)g0, (double)g0, d.g0_sq);
+    d.g1_sq = fma((double)g1, (double)g1, d.g1_sq);
+    const float rm1 = si.r - 1.0f;          // centred on the common case r ~ 1: no cancellation in the variance
+    d.active += si.active ? 1u : 0u;
+    d.rm1_sum += si.active ? rm1 : 0.0f;
+    d.rm1_sq = si.active ? fmaf(rm1, rm1, d.rm1_sq) : d.rm1_sq;
+    d.scale_sum += si.active ? si.scale : 0.0f;
+    const float d2 = in_range ? disp2 : 0.0f;
+    const float dK = in_range ? si.scale * disp2 : 0.0f;
+    d.d2_sq = fmaf(d2, d2, d.d2_sq);
+    d.dK_sq = fmaf(dK, dK, d.dK_sq);
+}
+
+// 32-bit versions of the wave reduction above (same lane pattern, same fixed order).
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ float dpp_fetch(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, ROW_MASK, 0xf, false));
+}
+__device__ __forceinline__ float wave_sum(float x) {
+    x += dpp_fetch<0xb1, 0xf>(x);
+    x += dpp_fetch<0x4e, 0xf>(x);
+    x += dpp_fetch<0x124, 0xf>(x);
+    x += dpp_fetch<0x128, 0xf>(x);
+    x += dpp_fetch<0x142, 0xa>(x);
+    x += dpp_fetch<0x143, 0xc>(x);
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
+}
+__device__ __forceinline__ uint32_t wave_sum(uint32_t x) {
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xb1, 0xf, 0xf, false);
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4e, 0xf, 0xf, false);
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x124, 0xf, 0xf, false);
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x128, 0xf, 0xf, false);
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xa, 0xf, false);
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xc, 0xf, false);
+    return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
+}
+
+// Block totals of the eight extrapolation-pass accumulators -> this block's partials of
+// accumulators kAccG0Sq .. kAccDK (fixed order: lanes, then wavefronts in index order).
+template <int WPB>
+__device__ __forceinline__ void store_extrap_diag(const ExtrapDiag &d, double *__restrict__ partial, uint32_t n_blocks, uint32_t block) {
+    double acc[kNumExtrapAcc];
+    acc[kAccG0Sq - kAccG0Sq] = wave_sum(d.g0_sq);
+    acc[kAccG1Sq - kAccG0Sq] = wave_sum(d.g1_sq);
+    acc[kAccActive - kAccG0Sq] = (double)wave_sum(d.active);
+    acc[kAccR - kAccG0Sq] = (double)wave_sum(d.rm1_sum);
+    acc[kAccR2 - kAccG0Sq] = (double)wave_sum(d.rm1_sq);
+    acc[kAccScale - kAccG0Sq] = (double)wave_sum(d.scale_sum);
+    acc[kAccD2 - kAccG0Sq] = (double)wave_sum(d.d2_sq);
+    acc[kAccDK - kAccG0Sq] = (double)wave_sum(d.dK_sq);
+    const size_t pitch = partial_pitch(n_blocks);
+    const uint32_t slot = partial_slot(block, partial_stride(n_blocks));
+    if (WPB == 1) {
+        if (threadIdx.x == 0) {
+#pragma unroll
+            for (int a = 0; a < kNumExtrapAcc; ++a) partial[(size_t)(kAccG0Sq + a) * pitch + slot] = acc[a];
+        }
+    } else {
+        __shared__ double wave_part[kNumExtrapAcc][WPB];
+        if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+            for (int a = 0; a < kNumExtrapAcc; ++a) wave_part[a][threadIdx.x >> 6] = acc[a];
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+#pragma unroll
+            for (int a = 0; a < kNumExtrapAcc; ++a) {
+                double total = 0.0;
+#pragma unroll
+                for (int w = 0; w < WPB; ++w) total += wave_part[a][w];
+                partial[(size_t)(kAccG0Sq + a) * pitch + slot] = total;
+            }
+        }
     }
-    const double d2 = (double)disp2, dK = (double)(si.scale * disp2);
-    acc[kAccD2 - kAccG0Sq] = fma(d2, d2, acc[kAccD2 - kAccG0Sq]);
-    acc[kAccDK - kAccG0Sq] = fma(dK, dK, acc[kAccDK - kAccG0Sq]);
 }
 
 // ============================================================================
@@ -378,12 +453,12 @@ __global__ __launch_bounds__(64 * WPB) void k_extrapolate(Layout L, GradArg g0s,
     f32x4 g0 = load_grad<GDT>(r_g0, elem, s.full);
     f32x4 g1 = load_grad<GDT>(r_g1, elem, s.full);
     const float c0 = clip ? clip[kClipG0] : 1.0f, c1 = clip ? clip[kClipG1] : 1.0f;
-    double diag[kNumExtrapAcc] = {};
+    ExtrapDiag diag;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const ScaleInfo si = extrap_scale_info(g0[k], c0, g1[k], c1, e);
         const float disp2 = th2[k] - th0[k];
-        if (DIAG) add_extrap_diag(diag, g0[k], g1[k], si, disp2);
+        if (DIAG) add_extrap_diag(diag, g0[k], g1[k], si, disp2, elem + k < s.cnt);
         th0[k] = fmaf(e.alpha * si.scale, disp2, th0[k]);
     }
     store_f32(r_th, elem, s.full, th0);
@@ -391,7 +466,7 @@ __global__ __launch_bounds__(64 * WPB) void k_extrapolate(Layout L, GradArg g0s,
         const auto r_c = span_rsrc((unsigned short *)s.rec.copy + s.e0, s.cnt * 2u);
         store_bf16(r_c, elem, s.full, th0);
     }
-    if (DIAG) store_block_sums<WPB, kNumExtrapAcc>(diag, diag_partial, kAccG0Sq, L.n_blocks, blockIdx.x);
+    if (DIAG) store_extrap_diag<WPB>(diag, diag_partial, L.n_blocks, blockIdx.x);
 }
 
 // ============================================================================
@@ -455,7 +530,7 @@ __global__ __launch_bounds__(64 * WPB) void k_fused_steps_extrapolate(Layout L, 
     }
     f32x4 g1 = load_grad<GDT>(r_g1, elem, s.full);
     const float c0 = clip ? clip[kClipG0] : 1.0f, c1 = clip ? clip[kClipG1] : 1.0f;
-    double diag[kNumExtrapAcc] = {};
+    ExtrapDiag diag;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         float mk = m[k], vk = v[k];
@@ -466,7 +541,7 @@ __global__ __launch_bounds__(64 * WPB) void k_fused_steps_extrapolate(Layout L, 
         v[k] = vk;
         const float disp2 = (th1 - th0[k]) - upd2;                // theta^{t,2} - theta^t
         const ScaleInfo si = extrap_scale_info(g0[k], c0, g1[k], c1, e);
-        if (DIAG) add_extrap_diag(diag, g0[k], g1[k], si, disp2);
+        if (DIAG) add_extrap_diag(diag, g0[k], g1[k], si, disp2, elem + k < s.cnt);
         th0[k] = fmaf(e.alpha * si.scale, disp2, th0[k]);
     }
     store_f32(r_th, elem, s.full, th0);
@@ -478,7 +553,7 @@ __global__ __launch_bounds__(64 * WPB) void k_fused_steps_extrapolate(Layout L, 
         const auto r_c = span_rsrc((unsigned short *)s.rec.copy + s.e0, s.cnt * 2u);
         store_bf16(r_c, elem, s.full, th0);
     }
-    if (DIAG) store_block_sums<WPB, kNumExtrapAcc>(diag, diag_partial, kAccG0Sq, L.n_blocks, blockIdx.x);
+    if (DIAG) store_extrap_diag<WPB>(diag, diag_partial, L.n_blocks, blockIdx.x);
 }
 
 // ============================================================================

@@ -271,6 +271,20 @@ def test_mechanism_diagnostics_policy_like(fused, grad_dtype, wpb):
     H.lockstep_active_step(ctx, dev, orc, grad_fn, (grads[0], grads[1], grads[0]), dtol=1e-4, fused=fused, what="aliased")
 
 
+@pytest.mark.parametrize("fused", [True, False])
+def test_mechanism_diagnostics_ignore_lanes_past_a_ragged_end(fused):
+    """With adam_eps = 0 a lane past the end of a tensor (all-zero loads) computes 0/0 in its
+    would-be AdamW step; nothing of it may reach the displacement sums."""
+    numels = [1, 3, 255, 257, 1000, 4099]
+    problem = synth.policy_problem(sum(numels), seed=23, sigma=0.05, device="cuda")
+    cfg = B.make_config(K=5, alpha=0.5, delta=1.75e-3, lr=1e-4, adam_eps=0.0, fuse_step2=fused, gate_min_count=2, diagnostics=True)
+    dev, ctx, orc, grads = build(numels, cfg, problem)
+    grad_fn = quad_trainer(problem, numels, step_noise=lambda: synth.step_noise(problem, 0))
+    H.lockstep_active_step(ctx, dev, orc, grad_fn, grads, dtol=1e-4, fused=fused, what="eps = 0 ragged diagnostics")
+    d = B.gxpo_get_diagnostics(ctx)
+    assert math.isfinite(d.displacement_ratio) and d.displacement_ratio > 1.0
+
+
 def test_mechanism_diagnostics_broad_ratios_and_surrogate():
     # broad, clamped ratios
     numels = [60000, 333]
