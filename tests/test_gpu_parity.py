@@ -97,6 +97,27 @@ def test_adamw_ragged_lockstep(fused, grad_dtype, wpb):
     assert (st.t, st.optim_steps, st.backward_passes) == (4, 12, 12)
 
 
+@pytest.mark.parametrize("grad_dtype", ["f32", "bf16"])
+def test_thousands_of_tiny_tensors(grad_dtype):
+    """1500 tensors of 1 .. 700 elements: almost every block is a ragged tail and the block -> tensor
+    search walks up to 64 table entries per block; per-tensor norms are checked one by one."""
+    rng = np.random.default_rng(31)
+    numels = [int(x) for x in rng.integers(1, 700, size=1500)]
+    problem = synth.policy_problem(sum(numels), seed=31, sigma=0.05, device="cuda")
+    cfg = B.make_config(grad_dtype=grad_dtype, K=5, alpha=0.5, delta=1.75e-3, lr=1e-4, weight_decay=0.01, gate_min_count=2,
+                        copy_mask=7, diagnostics=True)
+    dev, ctx, orc, grads = build(numels, cfg, problem, with_copy=True)
+    step_id = [0]
+    grad_fn = quad_trainer(problem, numels, step_noise=lambda: synth.step_noise(problem, step_id[0]))
+    for step in range(2):
+        step_id[0] = step
+        H.lockstep_active_step(ctx, dev, orc, grad_fn, grads, dtol=1e-4, fused=True, check_copy=True, what=f"tiny tensors step {step}")
+    got, want = B.gxpo_tensor_norms(ctx), orc.tensor_norms()
+    assert len(got) == 1500
+    np.testing.assert_allclose(got, want, rtol=1e-12)
+    dev.check_canaries()
+
+
 @pytest.mark.parametrize("fused", [True, False])
 def test_lockstep_on_a_side_stream(fused):
     """Every call takes the caller's stream: run a whole active step, with clipping and
