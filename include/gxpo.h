@@ -115,7 +115,9 @@ typedef struct gxpo_config {
     uint32_t struct_size;     /* = sizeof(gxpo_config) */
     uint32_t optimizer;       /* GXPO_OPT_*   : OptimStep of Algorithm 1 */
     uint32_t grad_dtype;      /* GXPO_GRAD_*  : element type of every gradient buffer */
-    uint32_t K;               /* virtual lookahead depth, >= 2 (K = 2 makes scale == 1) */
+    uint32_t K;               /* virtual lookahead depth, 2 .. 4096 (K = 2 makes scale == 1; the paper uses
+                                 3 .. 10).  The fp32 series for S_K/S_2 rounds like K * 2^-24: within
+                                 1e-5 of the exact factor up to K of a few hundred. */
     uint32_t fuse_step2;      /* 1: gxpo_fast_steps(0) writes theta^{t,1} but leaves m, v alone,
                                  gxpo_fast_steps(1) only records g1, and gxpo_extrapolate replays
                                  the first fast step, takes the second and extrapolates in one pass

@@ -117,7 +117,7 @@ int check_config(const gxpo_config *c, std::string &msg) {
     if (c->optimizer != GXPO_OPT_GD && c->optimizer != GXPO_OPT_ADAMW) { msg = "unknown optimizer"; return GXPO_ERR_UNSUPPORTED; }
     if (c->grad_dtype != GXPO_GRAD_F32 && c->grad_dtype != GXPO_GRAD_BF16) { msg = "unknown grad_dtype"; return GXPO_ERR_UNSUPPORTED; }
     if (c->K < 2) return bad("K must be >= 2");
-    if (c->K > (1u << 20)) return bad("K is unreasonably large");
+    if (c->K > 4096) return bad("K must be <= 4096");
     if (c->fuse_step2 > 1) return bad("fuse_step2 must be 0 or 1");
     if (c->copy_mask & ~7u) return bad("copy_mask has unknown bits");
     if (c->window < 2 || c->window > GXPO_MAX_WINDOW) return bad("window must be in [2, GXPO_MAX_WINDOW]");

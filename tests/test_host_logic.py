@@ -71,6 +71,7 @@ def test_default_config_is_valid():
 @pytest.mark.parametrize("kwargs,code", [
     (dict(K=1), B.GXPO_ERR_INVALID_ARG),
     (dict(K=0), B.GXPO_ERR_INVALID_ARG),
+    (dict(K=4097), B.GXPO_ERR_INVALID_ARG),
     (dict(alpha=-0.1), B.GXPO_ERR_INVALID_ARG),
     (dict(alpha=1.5), B.GXPO_ERR_INVALID_ARG),
     (dict(alpha=float("nan")), B.GXPO_ERR_INVALID_ARG),
@@ -102,7 +103,7 @@ def test_bad_configs_are_rejected_with_a_message(kwargs, code):
     assert msg
 
 
-@pytest.mark.parametrize("kwargs", [dict(K=2), dict(alpha=0.0), dict(alpha=1.0), dict(delta=math.inf),
+@pytest.mark.parametrize("kwargs", [dict(K=2), dict(K=4096), dict(alpha=0.0), dict(alpha=1.0), dict(delta=math.inf),
                                     dict(delta=0.0), dict(r_max=1.0), dict(optimizer="gd"), dict(grad_dtype="bf16"),
                                     dict(gate_min_count=2), dict(window=B.GXPO_MAX_WINDOW), dict(tau=-1.0), dict(explicit_steps=5),
                                     dict(clip_norm=1.0)])
