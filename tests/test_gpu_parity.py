@@ -703,6 +703,26 @@ def test_unit_parameter_groups_change_nothing():
         assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("fused", [True, False])
+def test_all_inactive_equals_lookahead_depth_two(fused):
+    """delta = +inf switches every coordinate off the active set (scale = 1 everywhere); K = 2 makes the
+    geometric factor 1 on the active set.  Both leave theta~ = theta + alpha (theta^{t,2} - theta): the two
+    configurations must agree bit for bit, and with the oracle."""
+    numels = [4099, 257, 70001]
+    problem = synth.policy_problem(sum(numels), seed=17, sigma=0.05, device="cuda")
+    results = []
+    for kwargs in (dict(K=8, delta=math.inf), dict(K=2, delta=0.0), dict(K=9, delta=math.inf)):
+        cfg = B.make_config(alpha=0.5, lr=1e-4, weight_decay=0.01, fuse_step2=fused, gate_min_count=2, **kwargs)
+        dev, ctx, orc, grads = build(numels, cfg, problem)
+        grad_fn = quad_trainer(problem, numels, step_noise=lambda: synth.step_noise(problem, 0))
+        H.lockstep_active_step(ctx, dev, orc, grad_fn, grads, dtol=1e-4, fused=fused, what=f"{kwargs}")
+        assert all(np.all(s == 1.0) for s in orc.scale)
+        results.append([x.clone() for k in ("theta", "m", "v") for x in dev.views[k]])
+    for other in results[1:]:
+        for a, b in zip(results[0], other):
+            assert torch.equal(a, b)
+
+
 def test_hyper_parameter_schedule_through_update_config():
     """A learning-rate / alpha / K / delta schedule between steps: the engine with gxpo_update_config
     against the oracle whose configuration is changed the same way."""
