@@ -226,3 +226,45 @@ def test_host_gate_hand_case_and_nan():
     st = B.new_state()
     info = B.gxpo_host_gate_step(cfg, st, float("inf"))
     assert info.tripped == 1 and info.s_star == 1 and info.evaluated == 0
+
+
+# ---- the product path fails loudly instead of falling back ------------------------------------------
+def test_bench_refuses_more_than_one_gpu_and_a_missing_gpu():
+    import subprocess
+    import sys
+    bench = os.path.join(ROOT, "bench.py")
+    res = subprocess.run([sys.executable, bench, "--gpus", "2"], stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=300)
+    assert res.returncode != 0 and "one GPU" in res.stderr and not res.stdout.strip()
+    import torch
+    if not torch.cuda.is_available():
+        res = subprocess.run([sys.executable, bench, "--steps", "1", "--warmup", "0"], stdout=subprocess.PIPE, stderr=subprocess.PIPE,
+                             text=True, timeout=300)
+        assert res.returncode != 0 and "no CPU path" in res.stderr and not res.stdout.strip()
+
+
+def test_binding_import_fails_loudly_without_the_built_library(tmp_path):
+    """A copy of the package without libgxpo.so must refuse to import its binding: there is no CPU fallback."""
+    import shutil
+    import subprocess
+    import sys
+    pkg = tmp_path / "paper_2605_06755_amd"
+    pkg.mkdir()
+    for name in ("__init__.py", "binding.py"):
+        shutil.copy(os.path.join(ROOT, "paper_2605_06755_amd", name), pkg / name)
+    res = subprocess.run([sys.executable, "-c", "import paper_2605_06755_amd.binding"], cwd=tmp_path, stdout=subprocess.PIPE,
+                         stderr=subprocess.PIPE, text=True, timeout=300, env={**os.environ, "PYTHONPATH": str(tmp_path)})
+    assert res.returncode != 0 and "ImportError" in res.stderr and "no CPU fallback" in res.stderr
+
+
+def test_product_code_never_touches_the_oracle():
+    """Only tests, the smoke check and bench.py's CPU-baseline leg may use oracle/."""
+    for folder in ("paper_2605_06755_amd", "include"):
+        for base, _, files in os.walk(os.path.join(ROOT, folder)):
+            for f in files:
+                if f.endswith((".py", ".h", ".hip", ".cpp", ".c")):
+                    text = open(os.path.join(base, f)).read()
+                    assert not re.search(r"^\s*(from|import)\s+oracle|gxpo_oracle", text, flags=re.M), f"{f} reaches into oracle/"
+    bench = open(os.path.join(ROOT, "bench.py")).read()
+    uses = [i for i, line in enumerate(bench.splitlines()) if "from oracle" in line or "import oracle" in line]
+    start = bench.splitlines().index("def time_oracle(spec, cfg, inputs, S):")
+    assert uses and all(i > start for i in uses), "bench.py may import the oracle only inside its CPU-baseline leg"
