@@ -599,9 +599,10 @@ __global__ void k_clip_coefficient(const double *__restrict__ result_all, uint32
 // ============================================================================
 // Fixed-order reduction of the per-block partial sums.
 // Stage 1: one block per run of <= kSegPartials partials of one tensor.
-// Stage 2: one block; a wavefront adds the run sums of a tensor (lane-strided,
-// then a butterfly), wavefront 0 then adds the tensor sums the same way.  The
-// order of every addition is fixed by the shapes alone.
+// Stage 2: one wavefront per tensor adds that tensor's run sums (lane-strided,
+// then over the lanes).  Stage 3, only for lists of several tensors: one
+// wavefront adds the tensor sums the same way.  The order of every addition is
+// fixed by the shapes alone.
 // ============================================================================
 constexpr int kFinalThreads = 256;
 
@@ -629,24 +630,30 @@ __global__ __launch_bounds__(kFinalThreads) void k_reduce_runs(const double *__r
 __global__ __launch_bounds__(kFinalThreads) void k_reduce_tensors(const double *__restrict__ seg_sum_all, uint32_t n_segs, int first_acc,
                                                                 const uint32_t *__restrict__ tensor_seg_start, uint32_t n_tensors,
                                                                 double *__restrict__ result_all) {
-    // blockIdx.x: accumulator
-    const double *seg_sum = seg_sum_all + (size_t)(first_acc + blockIdx.x) * n_segs;
+    // blockIdx.x: group of kFinalThreads / 64 tensors, blockIdx.y: accumulator.  One wavefront per
+    // tensor: lane l adds runs l, l + 64, ... in order, then the lanes are summed.
+    const double *seg_sum = seg_sum_all + (size_t)(first_acc + blockIdx.y) * n_segs;
+    double *result = result_all + (size_t)(first_acc + blockIdx.y) * (1 + n_tensors);
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t t = blockIdx.x * (kFinalThreads / 64) + (threadIdx.x >> 6);
+    if (t >= n_tensors) return;                          // whole wavefronts leave together
+    double acc = 0.0;
+    for (uint32_t i = tensor_seg_start[t] + lane; i < tensor_seg_start[t + 1]; i += 64) acc += seg_sum[i];
+    acc = wave_sum(acc);
+    if (lane == 0) {
+        result[1 + t] = acc;
+        if (n_tensors == 1) result[0] = acc;             // nothing left to add: the total is this tensor's sum
+    }
+}
+
+// Stage 3 (lists of several tensors): one wavefront per accumulator adds the tensor sums,
+// lane-strided in index order, then over the lanes.
+__global__ __launch_bounds__(64) void k_reduce_total(uint32_t n_tensors, int first_acc, double *__restrict__ result_all) {
     double *result = result_all + (size_t)(first_acc + blockIdx.x) * (1 + n_tensors);
-    // one wavefront per tensor at a time: lane l adds runs l, l + 64, ... in order, then a butterfly
-    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    for (uint32_t t = wave; t < n_tensors; t += kFinalThreads / 64) {
-        double acc = 0.0;
-        for (uint32_t i = tensor_seg_start[t] + lane; i < tensor_seg_start[t + 1]; i += 64) acc += seg_sum[i];
-        acc = wave_sum(acc);
-        if (lane == 0) result[1 + t] = acc;
-    }
-    __syncthreads();
-    if (wave == 0) {
-        double total = 0.0;
-        for (uint32_t t = lane; t < n_tensors; t += 64) total += result[1 + t];
-        total = wave_sum(total);
-        if (lane == 0) result[0] = total;
-    }
+    double total = 0.0;
+    for (uint32_t t = threadIdx.x; t < n_tensors; t += 64) total += result[1 + t];
+    total = wave_sum(total);
+    if (threadIdx.x == 0) result[0] = total;
 }
 
 // ============================================================================
@@ -781,8 +788,12 @@ hipError_t launch_finalize(const double *d_partial, uint32_t n_blocks, const Seg
     k_reduce_runs<<<dim3(n_segs, n_acc), dim3(kFinalThreads), 0, stream>>>(d_partial, n_blocks, first_acc, d_seg, d_seg_sum);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    k_reduce_tensors<<<dim3(n_acc), dim3(kFinalThreads), 0, stream>>>(d_seg_sum, n_segs, first_acc, d_tensor_seg_start, n_tensors,
-                                                                      d_result);
+    const uint32_t tensors_per_block = kFinalThreads / 64;
+    k_reduce_tensors<<<dim3((n_tensors + tensors_per_block - 1) / tensors_per_block, n_acc), dim3(kFinalThreads), 0, stream>>>(
+        d_seg_sum, n_segs, first_acc, d_tensor_seg_start, n_tensors, d_result);
+    e = hipGetLastError();
+    if (e != hipSuccess || n_tensors == 1) return e;
+    k_reduce_total<<<dim3(n_acc), dim3(64), 0, stream>>>(n_tensors, first_acc, d_result);
     return hipGetLastError();
 }
 
