@@ -723,6 +723,56 @@ def test_all_inactive_equals_lookahead_depth_two(fused):
             assert torch.equal(a, b)
 
 
+def test_checkpoint_and_resume_is_bit_identical():
+    """Six steps in one go against three steps, a checkpoint (the caller's buffers plus gxpo_get_state),
+    a brand-new context restored with gxpo_set_state, and three more steps: same bits, same gate records."""
+    numels = [4099, 257, 70001]
+    problem = synth.policy_problem(sum(numels), seed=18, sigma=0.05, device="cuda")
+    cfg = B.make_config(K=8, alpha=0.5, delta=1.75e-3, lr=1e-4, weight_decay=0.01, gate_min_count=2, window=3, tau=1e6)
+    step_id = [0]
+    grad_fn = quad_trainer(problem, numels, step_noise=lambda: synth.step_noise(problem, step_id[0]))
+
+    def run_steps(ctx, dev, grads, steps):
+        infos = []
+        for step in steps:
+            step_id[0] = step
+            g0, g1, gs = grads
+            grad_fn(dev.views["theta"], g0); B.gxpo_fast_steps(ctx, 0, g0)
+            grad_fn(dev.views["theta_probe"], g1); B.gxpo_fast_steps(ctx, 1, g1)
+            B.gxpo_extrapolate(ctx, g0, g1)
+            grad_fn(dev.views["theta"], gs); B.gxpo_slow_step(ctx, gs)
+            i = B.gxpo_gate(ctx)
+            infos.append((i.norm, i.mu, i.sigma, i.z, i.evaluated, i.t))
+        return infos
+
+    dev_a, ctx_a, _, grads_a = build(numels, cfg, problem)
+    infos_a = run_steps(ctx_a, dev_a, grads_a, range(6))
+
+    dev_b, ctx_b, _, grads_b = build(numels, cfg, problem)
+    infos_b = run_steps(ctx_b, dev_b, grads_b, range(3))
+    saved_state = B.gxpo_get_state(ctx_b)
+    saved = {k: [x.clone() for x in dev_b.views[k]] for k in ("theta", "m", "v")}
+    B.gxpo_destroy(ctx_b)
+    del dev_b
+
+    dev_c = H.DeviceState(numels, adam=True, with_copy=False)
+    for k, xs in saved.items():
+        for dst, src in zip(dev_c.views[k], xs):
+            dst.copy_(src)
+    ctx_c = B.gxpo_init(cfg, dev_c.tensor_dicts())
+    B.gxpo_set_state(ctx_c, saved_state)
+    infos_b += run_steps(ctx_c, dev_c, grads_b, range(3, 6))
+
+    same = lambda a, b: all((x == y) or (x != x and y != y) for x, y in zip(a, b))       # NaN == NaN during warm-up
+    assert all(same(a, b) for a, b in zip(infos_a, infos_b)) and len(infos_b) == 6
+    for k in ("theta", "m", "v"):
+        for a, c in zip(dev_a.views[k], dev_c.views[k]):
+            assert torch.equal(a, c), f"{k} differs after resume"
+    sa, sc = B.gxpo_get_state(ctx_a), B.gxpo_get_state(ctx_c)
+    assert (sa.t, sa.optim_steps, sa.backward_passes, sa.window_len, list(sa.window[:3])) == \
+           (sc.t, sc.optim_steps, sc.backward_passes, sc.window_len, list(sc.window[:3])) and sa.t == 6
+
+
 def test_hyper_parameter_schedule_through_update_config():
     """A learning-rate / alpha / K / delta schedule between steps: the engine with gxpo_update_config
     against the oracle whose configuration is changed the same way."""
