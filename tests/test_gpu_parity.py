@@ -773,6 +773,49 @@ def test_checkpoint_and_resume_is_bit_identical():
            (sc.t, sc.optim_steps, sc.backward_passes, sc.window_len, list(sc.window[:3])) and sa.t == 6
 
 
+def test_two_contexts_interleaved_on_two_streams_do_not_interact():
+    """Contexts own their workspace: two of them, driven call by call on two side streams,
+    give exactly what each gives alone."""
+    specs = [([4099, 257], 19, dict(K=8, alpha=0.5, lr=1e-4)), ([70001], 20, dict(K=5, alpha=1.0, lr=3e-5, clip_norm=5.0, diagnostics=1))]
+
+    def make(numels, seed, kw):
+        problem = synth.policy_problem(sum(numels), seed=seed, sigma=0.05, device="cuda")
+        cfg = B.make_config(delta=1.75e-3, weight_decay=0.01, gate_min_count=2, tau=1e6, **kw)
+        dev, ctx, _, grads = build(numels, cfg, problem)
+        return dict(problem=problem, numels=numels, dev=dev, ctx=ctx, grads=grads,
+                    grad_fn=quad_trainer(problem, numels, step_noise=lambda: synth.step_noise(problem, 0)))
+
+    def calls(r):
+        g0, g1, gs = r["grads"]
+        dev, ctx, grad_fn = r["dev"], r["ctx"], r["grad_fn"]
+        yield lambda: (grad_fn(dev.views["theta"], g0), B.gxpo_fast_steps(ctx, 0, g0))
+        yield lambda: (grad_fn(dev.views["theta_probe"], g1), B.gxpo_fast_steps(ctx, 1, g1))
+        yield lambda: B.gxpo_extrapolate(ctx, g0, g1)
+        yield lambda: (grad_fn(dev.views["theta"], gs), B.gxpo_slow_step(ctx, gs))
+        yield lambda: r.__setitem__("norm", B.gxpo_gate(ctx).norm)
+
+    solo = [make(*sp) for sp in specs]
+    for r in solo:
+        for _ in range(2):
+            for c in calls(r):
+                c()
+    pair = [make(*sp) for sp in specs]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for _ in range(2):
+        for ca, cb in zip(calls(pair[0]), calls(pair[1])):
+            with torch.cuda.stream(streams[0]):
+                ca()
+            with torch.cuda.stream(streams[1]):
+                cb()
+    torch.cuda.synchronize()
+    for a, b in zip(solo, pair):
+        assert a["norm"] == b["norm"]
+        for k in ("theta", "m", "v"):
+            for x, y in zip(a["dev"].views[k], b["dev"].views[k]):
+                assert torch.equal(x, y)
+
+
 def test_hyper_parameter_schedule_through_update_config():
     """A learning-rate / alpha / K / delta schedule between steps: the engine with gxpo_update_config
     against the oracle whose configuration is changed the same way."""
