@@ -816,6 +816,32 @@ def test_two_contexts_interleaved_on_two_streams_do_not_interact():
                 assert torch.equal(x, y)
 
 
+def test_fresh_gradient_buffers_on_every_call():
+    """A trainer that hands in newly allocated gradient tensors on every call makes the engine re-validate and
+    re-upload its pointer tables each time (more uploads than it has staging slots): same bits as with fixed buffers."""
+    numels = [4099, 257, 1000]
+    problem = synth.policy_problem(sum(numels), seed=24, sigma=0.05, device="cuda")
+    cfg = B.make_config(K=8, alpha=0.5, delta=1.75e-3, lr=1e-4, weight_decay=0.01, gate_min_count=2, tau=1e6)
+    grad_fn = quad_trainer(problem, numels, step_noise=lambda: synth.step_noise(problem, 0))
+    outs = []
+    for fresh in (False, True):
+        dev, ctx, _, fixed = build(numels, cfg, problem)
+        keep = []                                            # fresh buffers stay alive (and distinct) until the end
+        for step in range(6):
+            bufs = [H.grad_buffers(numels, torch.float32) for _ in range(3)] if fresh else fixed
+            keep.append(bufs)
+            g0, g1, gs = bufs
+            grad_fn(dev.views["theta"], g0); B.gxpo_fast_steps(ctx, 0, g0)
+            grad_fn(dev.views["theta_probe"], g1); B.gxpo_fast_steps(ctx, 1, g1)
+            B.gxpo_extrapolate(ctx, g0, g1)
+            grad_fn(dev.views["theta"], gs); B.gxpo_slow_step(ctx, gs)
+            norm = B.gxpo_gate(ctx).norm
+        outs.append((norm, [x.clone() for k in ("theta", "m", "v") for x in dev.views[k]]))
+    assert outs[0][0] == outs[1][0]
+    for a, b in zip(outs[0][1], outs[1][1]):
+        assert torch.equal(a, b)
+
+
 def test_hyper_parameter_schedule_through_update_config():
     """A learning-rate / alpha / K / delta schedule between steps: the engine with gxpo_update_config
     against the oracle whose configuration is changed the same way."""
