@@ -36,7 +36,10 @@
  *    human-readable description of the last failure.
  *  - "device" pointers are HIP device allocations on the GPU that was current
  *    when gxpo_init() ran; that GPU must be current on every later call.
- *    "host" pointers are ordinary process memory.
+ *    "host" pointers are ordinary process memory.  Every device range is
+ *    checked with hipMemGetAddressRange before a kernel may touch it, so the
+ *    buffers must lie in allocations that call can resolve (hipMalloc and
+ *    allocators built on it).
  *  - The caller owns every parameter-sized buffer (theta, theta_probe, m, v,
  *    model_copy, gradients) and keeps it alive and un-aliased while the
  *    context lives; the context owns only its small tables and the reduction
