@@ -301,6 +301,16 @@ int gxpo_host_gate_step(const gxpo_config *cfg, gxpo_state *state, double norm, 
 int gxpo_plan_blocks(const uint64_t *numel, uint32_t n_tensors, uint32_t waves_per_block,
                      uint32_t *block_start, uint32_t *elems_per_block);
 
+/* Where to put the caller-owned buffers in HBM.  Every pass streams several
+ * parameter-sized arrays at the same element offset; on MI355X the achieved
+ * bandwidth depends on how their base addresses relate modulo *period_bytes
+ * (measured: about 6 % between the worst and the best placement).  For the buffer
+ * kind asked about, *phase_bytes is the recommended base address modulo
+ * *period_bytes.  Only a hint: any pointer with the stated alignment is accepted. */
+enum { GXPO_BUF_THETA = 0, GXPO_BUF_THETA_PROBE = 1, GXPO_BUF_M = 2, GXPO_BUF_V = 3,
+       GXPO_BUF_MODEL_COPY = 4, GXPO_BUF_GRAD = 5 };
+int gxpo_layout_hint(int buffer_kind, uint64_t *phase_bytes, uint64_t *period_bytes);
+
 /* ---- measurement aid ------------------------------------------------------------ */
 
 /* Plain device-to-device streaming copy of `bytes` (multiple of 16, both

@@ -39,12 +39,13 @@ GXPO_GRAD_F32, GXPO_GRAD_BF16 = 0, 1
 GXPO_COPY_AT_PROBE, GXPO_COPY_AT_TILDE, GXPO_COPY_AT_FINAL = 1, 2, 4
 GXPO_PHASE_IDLE, GXPO_PHASE_FAST1, GXPO_PHASE_FAST2, GXPO_PHASE_REPOSITIONED, GXPO_PHASE_SLOW_DONE = range(5)
 GXPO_MAX_WINDOW = 256
+GXPO_BUF_THETA, GXPO_BUF_THETA_PROBE, GXPO_BUF_M, GXPO_BUF_V, GXPO_BUF_MODEL_COPY, GXPO_BUF_GRAD = range(6)
 
 EXPORTED_SYMBOLS = [
     "gxpo_init", "gxpo_destroy", "gxpo_fast_steps", "gxpo_extrapolate", "gxpo_slow_step", "gxpo_gate",
     "gxpo_fallback_step", "gxpo_tensor_norms", "gxpo_get_diagnostics", "gxpo_get_state", "gxpo_set_state", "gxpo_last_error",
     "gxpo_validate_config", "gxpo_host_gate_step", "gxpo_plan_blocks", "gxpo_stream_copy", "gxpo_update_config",
-    "gxpo_set_tensor_options",
+    "gxpo_set_tensor_options", "gxpo_layout_hint",
 ]
 
 
@@ -128,6 +129,8 @@ _lib.gxpo_host_gate_step.argtypes = [ctypes.POINTER(gxpo_config), ctypes.POINTER
 _lib.gxpo_plan_blocks.restype = ctypes.c_int
 _lib.gxpo_plan_blocks.argtypes = [ctypes.POINTER(ctypes.c_uint64), ctypes.c_uint32, ctypes.c_uint32,
                                   ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_uint32)]
+_lib.gxpo_layout_hint.restype = ctypes.c_int
+_lib.gxpo_layout_hint.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64)]
 _lib.gxpo_stream_copy.restype = ctypes.c_int
 _lib.gxpo_stream_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p]
 
@@ -344,6 +347,15 @@ def gxpo_plan_blocks(numels: Sequence[int], waves_per_block: int = 0):
     if rc != GXPO_OK:
         raise GxpoError(rc, "gxpo_plan_blocks rejected its arguments")
     return list(out), epb.value
+
+
+def gxpo_layout_hint(buffer_kind: int):
+    """Returns (phase_bytes, period_bytes) for a GXPO_BUF_* kind."""
+    phase, period = ctypes.c_uint64(0), ctypes.c_uint64(0)
+    rc = _lib.gxpo_layout_hint(int(buffer_kind), ctypes.byref(phase), ctypes.byref(period))
+    if rc != GXPO_OK:
+        raise GxpoError(rc, "gxpo_layout_hint rejected its arguments")
+    return phase.value, period.value
 
 
 def gxpo_stream_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

@@ -320,6 +320,15 @@ int gxpo_plan_blocks(const uint64_t *numel, uint32_t n_tensors, uint32_t waves_p
     return GXPO_OK;
 }
 
+int gxpo_layout_hint(int buffer_kind, uint64_t *phase_bytes, uint64_t *period_bytes) {
+    if (!phase_bytes || !period_bytes || buffer_kind < GXPO_BUF_THETA || buffer_kind > GXPO_BUF_GRAD) return GXPO_ERR_INVALID_ARG;
+    // the moments sit half a period away from everything else, which splits the traffic of every
+    // pass about evenly between the two halves of the period
+    *period_bytes = 64u * 1024u;
+    *phase_bytes = (buffer_kind == GXPO_BUF_M || buffer_kind == GXPO_BUF_V) ? 32u * 1024u : 0u;
+    return GXPO_OK;
+}
+
 int gxpo_host_gate_step(const gxpo_config *cfg, gxpo_state *st, double norm, gxpo_gate_info *out) {
     if (!cfg || !st) return GXPO_ERR_INVALID_ARG;
     if (st->window_len > GXPO_MAX_WINDOW || cfg->window < 2 || cfg->window > GXPO_MAX_WINDOW) return GXPO_ERR_INVALID_ARG;

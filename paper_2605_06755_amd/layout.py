@@ -17,8 +17,11 @@ from __future__ import annotations
 
 import torch
 
-PHASE_PERIOD_BYTES = 64 * 1024
-MOMENT_PHASE_BYTES = 32 * 1024
+from . import binding as _B
+
+# the library is the one place that states the placement
+MOMENT_PHASE_BYTES, PHASE_PERIOD_BYTES = _B.gxpo_layout_hint(_B.GXPO_BUF_M)
+assert _B.gxpo_layout_hint(_B.GXPO_BUF_THETA)[0] == 0 and _B.gxpo_layout_hint(_B.GXPO_BUF_GRAD)[0] == 0
 
 
 def alloc_phased(numel: int, dtype, device, phase_bytes: int = 0, fill=None) -> torch.Tensor:

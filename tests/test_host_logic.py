@@ -144,6 +144,13 @@ def test_init_rejects_bad_arguments_before_touching_the_gpu():
     assert out.value is None
 
 
+def test_layout_hint():
+    assert B.gxpo_layout_hint(B.GXPO_BUF_THETA) == (0, 65536) and B.gxpo_layout_hint(B.GXPO_BUF_GRAD) == (0, 65536)
+    assert B.gxpo_layout_hint(B.GXPO_BUF_M) == B.gxpo_layout_hint(B.GXPO_BUF_V) == (32768, 65536)
+    with pytest.raises(B.GxpoError):
+        B.gxpo_layout_hint(6)
+
+
 # ---- block plan ---------------------------------------------------------------------------------
 @pytest.mark.parametrize("wpb", [0, 1, 2, 4])
 def test_block_plan_covers_every_element_exactly_once(wpb):
