@@ -108,6 +108,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the GXPO engine has no CPU path", file=sys.stderr)
         sys.exit(2)
+    from paper_2605_06755_amd import build as lib_build
+    lib_build.ensure_built()                     # loads what is built; builds only if nothing is there
     from paper_2605_06755_amd import binding as B
     from paper_2605_06755_amd import layout as layout_mod
     from paper_2605_06755_amd import synth

@@ -79,6 +79,15 @@ def build_abi_driver(verbose: bool = False) -> str:
     return ABI_DRIVER
 
 
+def ensure_built() -> None:
+    """For the harness around the library (tests, smoke check, bench): build what is missing, and only that.
+    The binding itself never builds and never falls back: without libgxpo.so it refuses to import."""
+    if not os.path.exists(LIB):
+        build_library()
+    if not os.path.exists(ABI_DRIVER):
+        build_abi_driver()
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
     print(build_abi_driver(verbose=True))

@@ -10,6 +10,9 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run through the GPU box)")
+    # the tests load what is built; they build only if nothing is there
+    from paper_2605_06755_amd import build as lib_build
+    lib_build.ensure_built()
 
 
 @pytest.fixture(scope="session")
