@@ -27,6 +27,15 @@ Parity status of the pieces (see tests/test_oracle_pins.py):
     r_max readings, and the non-finite-norm rule.  They follow the readings
     documented next to each function and are exercised only by hand-computed
     examples.
+  * parity unpinned against the paper, pinned against something else: the
+    mechanism diagnostics (the paper names the quantities, not their formulas;
+    pinned to numpy definitions and closed forms on the diagonal surrogate),
+    global-norm clipping (the paper gives only the threshold; pinned to the
+    library routine), the explicit n-step lookahead (the paper only names the
+    scheme; pinned to brute-force gradient descent and to the extrapolation on
+    the diagonal surrogate) and parameter groups (not in the paper; pinned to a
+    library AdamW with parameter groups).
+How sharp the pins are is tested by planting mistakes (tests/test_oracle_mutations.py).
 """
 from __future__ import annotations
 
