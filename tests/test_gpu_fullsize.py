@@ -73,7 +73,21 @@ def gather(flat, windows):
     return H.f64(flat[idx])
 
 
-def run_sampled_active_step(spec_layout, *, seed, grad_dtype, with_copy, n_random, step_index=0, K=8, alpha=0.5):
+def dot64(a: torch.Tensor, b: torch.Tensor, chunk: int = 1 << 27) -> float:
+    total = 0.0
+    for lo in range(0, a.numel(), chunk):
+        total += float((a[lo:lo + chunk].double() * b[lo:lo + chunk].double()).sum())
+    return total
+
+
+def count_active(g: torch.Tensor, delta32: float, chunk: int = 1 << 28) -> int:
+    n = 0
+    for lo in range(0, g.numel(), chunk):
+        n += int((g[lo:lo + chunk].float().abs() > delta32).sum())
+    return n
+
+
+def run_sampled_active_step(spec_layout, *, seed, grad_dtype, with_copy, n_random, step_index=0, K=8, alpha=0.5, diagnostics=False):
     dev = torch.device("cuda:0")
     numels = [n for _, n in spec_layout]
     padded = synth.padded_numel(spec_layout, 4)
@@ -84,7 +98,7 @@ def run_sampled_active_step(spec_layout, *, seed, grad_dtype, with_copy, n_rando
     quad = synth.ChunkedQuadratic(padded, seed, 0.05, device=dev)
     quad.init_theta(flat["theta"])
     cfg = B.make_config(grad_dtype=grad_dtype, K=K, alpha=alpha, delta=1.75e-3, lr=1e-6, weight_decay=0.01,
-                        tau=3.0, window=10, fuse_step2=True, copy_mask=7)
+                        tau=3.0, window=10, fuse_step2=True, copy_mask=7, diagnostics=diagnostics)
     ctx = B.gxpo_init(cfg, [{k: views[k][i] for k in views} for i in range(len(numels))])
     rng = np.random.default_rng(seed)
     wins = windows_for(spec_layout, rng, n_random)
@@ -146,6 +160,21 @@ def run_sampled_active_step(spec_layout, *, seed, grad_dtype, with_copy, n_rando
         assert tn[i] == pytest.approx(math.sqrt(O.sum_squares(H.f64(gs[i]))), rel=1e-12), f"tensor {i} norm"
     st2 = B.gxpo_get_state(ctx)
     assert (st2.t, st2.optim_steps, st2.backward_passes) == (st.t + 1, st.optim_steps + 3, st.backward_passes + 3)
+    if diagnostics:
+        # the whole-list statistics that have a definition a library reduction can evaluate at this size
+        d = B.gxpo_get_diagnostics(ctx)
+        n0 = math.sqrt(sum(sumsq64(x) for x in g0))
+        n1 = math.sqrt(sum(sumsq64(x) for x in g1))
+        assert d.norm_g0 == pytest.approx(n0, rel=1e-11) and d.norm_g1 == pytest.approx(n1, rel=1e-11)
+        assert d.norm_g_slow == pytest.approx(want, rel=1e-11)
+        cos = sum(dot64(a, b) for a, b in zip(g0, gs)) / (n0 * want)
+        assert d.cos_g0_g_slow == pytest.approx(cos, rel=1e-9)
+        active = sum(count_active(x, float(np.float32(cfg.delta))) for x in g0)
+        assert d.inactive_fraction == pytest.approx(1.0 - active / sum(numels), rel=1e-12, abs=1e-15)
+        # and on the sampled coordinates the oracle's statistics bracket what the engine reports for the whole list
+        ref = orc.diagnostics()
+        assert abs(d.retention_mean - ref["retention_mean"]) < 0.05 and abs(d.scale_mean - ref["scale_mean"]) < 0.2
+        assert d.displacement_ratio == pytest.approx(ref["displacement_ratio"], rel=0.05)
     B.gxpo_destroy(ctx)
     return info
 
@@ -233,6 +262,13 @@ def test_config2_full_size_periodic_data_every_accumulator(clip_norm):
         # the next step starts from the engine's own state
         orc.theta, orc.m, orc.v = [H.f64(flat["theta"][:period])], [H.f64(flat["m"][:period])], [H.f64(flat["v"][:period])]
     B.gxpo_destroy(ctx)
+
+
+def test_config4_llama_8b_with_diagnostics_full_size():
+    """The ragged 290-tensor list at full size with every accumulator on: norms, cosine and the active count
+    against fp64 library reductions over the whole list, the rest against the oracle on the sampled windows."""
+    need_memory(200)
+    run_sampled_active_step(synth.llama31_8b_layout(), seed=6, grad_dtype="bf16", with_copy=False, n_random=300, diagnostics=True)
 
 
 @pytest.mark.parametrize("K,alpha", [(3, 0.1), (5, 1.0), (10, 0.5)])
