@@ -173,6 +173,10 @@ def sum_squares(g) -> float:
     return _load().gxpo_oracle_sum_squares(g.size, _p(g))
 
 
+def clip_coefficient(total_norm: float, max_norm: float) -> float:
+    return _load().gxpo_oracle_clip_coefficient(float(total_norm), float(max_norm))
+
+
 def clip_gradients(grads, max_norm: float):
     """Global-norm clipping of one gradient (a list of tensors): returns
     (clipped list, total norm before clipping, coefficient)."""

@@ -87,7 +87,8 @@ def count_active(g: torch.Tensor, delta32: float, chunk: int = 1 << 28) -> int:
     return n
 
 
-def run_sampled_active_step(spec_layout, *, seed, grad_dtype, with_copy, n_random, step_index=0, K=8, alpha=0.5, diagnostics=False):
+def run_sampled_active_step(spec_layout, *, seed, grad_dtype, with_copy, n_random, step_index=0, K=8, alpha=0.5, diagnostics=False,
+                            clip_norm=0.0):
     dev = torch.device("cuda:0")
     numels = [n for _, n in spec_layout]
     padded = synth.padded_numel(spec_layout, 4)
@@ -98,7 +99,7 @@ def run_sampled_active_step(spec_layout, *, seed, grad_dtype, with_copy, n_rando
     quad = synth.ChunkedQuadratic(padded, seed, 0.05, device=dev)
     quad.init_theta(flat["theta"])
     cfg = B.make_config(grad_dtype=grad_dtype, K=K, alpha=alpha, delta=1.75e-3, lr=1e-6, weight_decay=0.01,
-                        tau=3.0, window=10, fuse_step2=True, copy_mask=7, diagnostics=diagnostics)
+                        tau=3.0, window=10, fuse_step2=True, copy_mask=7, diagnostics=diagnostics, clip_norm=clip_norm)
     ctx = B.gxpo_init(cfg, [{k: views[k][i] for k in views} for i in range(len(numels))])
     rng = np.random.default_rng(seed)
     wins = windows_for(spec_layout, rng, n_random)
@@ -111,13 +112,24 @@ def run_sampled_active_step(spec_layout, *, seed, grad_dtype, with_copy, n_rando
     B.gxpo_gate(ctx)
 
     st = B.gxpo_get_state(ctx)
-    orc = O.GXPOOracle(H.oracle_config(cfg), [gather(flat["theta"], wins)])
+    oc = H.oracle_config(cfg)
+    oc.clip_norm = 0.0          # the oracle sees windows only: it is handed gradients already clipped with the whole list's norm
+    orc = O.GXPOOracle(oc, [gather(flat["theta"], wins)])
     orc.m, orc.v, orc.optim_steps = [gather(flat["m"], wins)], [gather(flat["v"], wins)], st.optim_steps
     start = orc.theta[0].copy()
+
+    def clipped(sample, whole_list):
+        if not clip_norm:
+            return sample
+        c = O.clip_coefficient(math.sqrt(sum(sumsq64(x) for x in whole_list)), clip_norm)
+        assert c < 0.9, "the threshold was meant to bite"
+        return sample * c
 
     def check(key, ref, label, amplified=False):
         got = gather(flat[key], wins)
         extra = 4.0 * 2.0 ** -24 * np.abs(ref) * cfg.alpha * np.abs(orc.scale[0]) if amplified else None
+        if amplified and clip_norm:
+            extra = extra + cfg.alpha * np.abs(orc._theta_2[0] - orc._theta_0[0]) * orc.scale[0] ** 2 * 2.0 ** -22
         H.assert_close(got, ref, label, extra_abs=extra)
         if key in ("theta", "theta_probe"):
             num = np.linalg.norm((got - start) - (ref - start))
@@ -127,11 +139,11 @@ def run_sampled_active_step(spec_layout, *, seed, grad_dtype, with_copy, n_rando
 
     quad.grad(flat["theta"], step_index, gflat[0])
     B.gxpo_fast_steps(ctx, 0, g0)
-    g0s = gather(gflat[0], wins)
+    g0s = clipped(gather(gflat[0], wins), g0)
     check("theta_probe", orc.fast_step_1([g0s])[0], "theta^{t,1}")
     quad.grad(flat["theta_probe"], step_index, gflat[1])
     B.gxpo_fast_steps(ctx, 1, g1)
-    g1s = gather(gflat[1], wins)
+    g1s = clipped(gather(gflat[1], wins), g1)
     orc.fast_step_2([g1s])
     B.gxpo_extrapolate(ctx, g0, g1)
     ref_t = orc.extrapolate([g0s], [g1s])[0]
@@ -145,7 +157,7 @@ def run_sampled_active_step(spec_layout, *, seed, grad_dtype, with_copy, n_rando
         H.assert_close(O.bf16_bits_to_f64(got_bits), ref_t, "bf16 copy at theta~", rtol=H.RTOL_BF16)
     quad.grad(flat["theta"], step_index, gflat[2])
     B.gxpo_slow_step(ctx, gs)
-    gss = gather(gflat[2], wins)
+    gss = clipped(gather(gflat[2], wins), gs)
     ref_n = orc.slow_step([gss])[0]
     check("theta", ref_n, "theta^{t+1}", amplified=True)
     check("m", orc.m[0], "m after slow step"); check("v", orc.v[0], "v after slow step")
@@ -262,6 +274,13 @@ def test_config2_full_size_periodic_data_every_accumulator(clip_norm):
         # the next step starts from the engine's own state
         orc.theta, orc.m, orc.v = [H.f64(flat["theta"][:period])], [H.f64(flat["m"][:period])], [H.f64(flat["v"][:period])]
     B.gxpo_destroy(ctx)
+
+
+def test_config4_llama_8b_with_gradient_clipping_full_size():
+    """Clipping on the ragged list at full size: the norm pre-passes run over 290 tensors of bf16 gradients, the
+    factor never leaves the device; the oracle is handed the sampled gradients clipped with the norm of the whole list."""
+    need_memory(200)
+    run_sampled_active_step(synth.llama31_8b_layout(), seed=7, grad_dtype="bf16", with_copy=False, n_random=300, clip_norm=2000.0)
 
 
 def test_config4_llama_8b_with_diagnostics_full_size():
