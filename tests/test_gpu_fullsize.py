@@ -276,6 +276,14 @@ def test_config2_full_size_periodic_data_every_accumulator(clip_norm):
     B.gxpo_destroy(ctx)
 
 
+def test_tensor_longer_than_2_to_32_elements_inside_a_list():
+    """Element offsets inside a tensor are 64-bit: a 2^32 + 1027 element tensor between two small ones
+    (the table-driven path, unlike the flat 7.6e9 buffer, which takes its pointers from the kernel arguments)."""
+    need_memory(150)
+    layout = [("head", 4099), ("long", (1 << 32) + 1027), ("tail", 257)]
+    run_sampled_active_step(layout, seed=8, grad_dtype="f32", with_copy=False, n_random=300)
+
+
 def test_config4_llama_8b_with_gradient_clipping_full_size():
     """Clipping on the ragged list at full size: the norm pre-passes run over 290 tensors of bf16 gradients, the
     factor never leaves the device; the oracle is handed the sampled gradients clipped with the norm of the whole list."""
