@@ -901,6 +901,80 @@ def test_non_finite_slow_gradient_trips_the_gate():
             B.gxpo_fast_steps(ctx, 0, g0)                  # fallback phase from t = 1 on
 
 
+@pytest.mark.parametrize("mode", ["fused", "unfused", "explicit"])
+def test_random_call_sequences_follow_the_state_machine(mode):
+    """600 randomly chosen calls per mode against a few-line model of Algorithm 1's call order: every call the
+    model allows must succeed, every other one must be refused with BAD_STATE and change nothing."""
+    n = 300
+    n_fast = 3 if mode == "explicit" else 2
+    cfg = B.make_config(fuse_step2=(mode == "fused"), explicit_steps=(3 if mode == "explicit" else 0), lr=1e-4, gate_min_count=2,
+                        window=4, tau=1e6)
+    problem = synth.policy_problem(n, seed=25, device="cuda")
+    dev, ctx, _, _ = build([n], cfg, problem)
+    g = [[torch.randn(n, device="cuda")] for _ in range(4)]
+    rng = np.random.default_rng({"fused": 1, "unfused": 2, "explicit": 3}[mode])
+    phase, fast_done, t, s_star, optim_steps, passes = "idle", 0, 0, None, 0, 0
+    n_ok = 0
+    for _ in range(600):
+        fallback = s_star is not None and t >= s_star
+        op = rng.choice(["fast", "extrapolate", "slow", "gate", "fallback", "trip", "rearm"], p=[0.3, 0.2, 0.2, 0.2, 0.05, 0.025, 0.025])
+        which = int(rng.integers(0, n_fast))
+        if rng.random() < 0.5:                  # half of the time, the call Algorithm 1 would make next
+            op = {"idle": "fallback" if fallback else "fast", "fast": "fast", "fast_done": "extrapolate",
+                  "repositioned": "slow", "slow_done": "gate"}[phase]
+            which = fast_done if phase == "fast" else 0
+        if op == "fast":
+            legal = not fallback and ((which == 0 and phase == "idle") or (which > 0 and phase == "fast" and fast_done == which))
+            call = lambda: B.gxpo_fast_steps(ctx, which, g[min(which, 1)])
+        elif op == "extrapolate":
+            legal = phase == "fast_done"
+            call = (lambda: B.gxpo_extrapolate(ctx)) if mode == "explicit" else (lambda: B.gxpo_extrapolate(ctx, g[0], g[1]))
+        elif op == "slow":
+            legal = phase == "repositioned"
+            call = lambda: B.gxpo_slow_step(ctx, g[2])
+        elif op == "gate":
+            legal = phase == "slow_done"
+            call = lambda: B.gxpo_gate(ctx)
+        elif op == "fallback":
+            legal = fallback and phase == "idle"
+            call = lambda: B.gxpo_fallback_step(ctx, g[3])
+        else:                                   # flip the gate through the state interface (legal between steps only)
+            legal = phase == "idle"
+            new_star = t if op == "trip" else -1
+
+            def call(new_star=new_star):
+                st = B.gxpo_get_state(ctx)
+                st.s_star = new_star
+                B.gxpo_set_state(ctx, st)
+        if legal:
+            call()
+            n_ok += 1
+            if op == "fast":
+                fast_done, optim_steps, passes = which + 1, optim_steps + 1, passes + 1
+                phase = "fast_done" if fast_done == n_fast else "fast"
+            elif op == "extrapolate":
+                phase = "repositioned"
+            elif op == "slow":
+                phase, optim_steps, passes = "slow_done", optim_steps + 1, passes + 1
+            elif op == "gate":
+                phase, t = "idle", t + 1
+            elif op == "fallback":
+                t, optim_steps, passes = t + 1, optim_steps + 1, passes + 1
+            elif op == "trip":
+                s_star = t
+            else:
+                s_star = None
+        else:
+            with pytest.raises(B.GxpoError) as e:
+                call()
+            assert e.value.code == B.GXPO_ERR_BAD_STATE, (op, which, phase, e.value.message)
+        st = B.gxpo_get_state(ctx)
+        assert (st.t, st.optim_steps, st.backward_passes, st.s_star) == (t, optim_steps, passes, -1 if s_star is None else s_star)
+    assert n_ok > 100
+    torch.cuda.synchronize()
+    dev.check_canaries()
+
+
 def test_init_rejects_host_memory_and_short_allocations():
     n = 4096
     cfg = B.make_config(optimizer="gd")
