@@ -33,10 +33,11 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "lora"])
-    ap.add_argument("--waves-per-block", type=int, default=0)
     ap.add_argument("--unfused", action="store_true", help="run the second fast step and the extrapolation as two passes")
     ap.add_argument("--same-phase", action="store_true", help="plain torch allocations instead of the phased HBM layout")
     ap.add_argument("--arena", action="store_true", help="carve all buffers from one allocation")
+    ap.add_argument("--placement", default="auto", choices=["auto", "ranked", "phased"],
+                    help="ranked: rank-aware placement through HIP's virtual-memory API; phased: one plain allocation per buffer")
     ap.add_argument("--phases", default="", help="experiment: KiB phases (mod 64) of theta,theta_probe,m,v,g0,g1,g2[,model_copy]")
     ap.add_argument("--no-probe", action="store_true",
                     help="workloads with a bf16 model copy: deliver theta^{t,1} through the copy only (no fp32 theta_probe)")
@@ -146,7 +147,7 @@ def main():
         gflat = [torch.empty(padded, dtype=gdt, device=dev) for _ in range(3)]
     else:
         flat, gflat = layout_mod.alloc_engine_state(padded, dev, adam=adam, model_copy=spec["copy"], grad_dtype=gdt,
-                                                    arena=args.arena, phases_kib=phases)
+                                                    arena=args.arena, phases_kib=phases, placement=args.placement, verbose=True)
     print("base addresses:", {k: hex(v.data_ptr()) for k, v in flat.items()}, [hex(g.data_ptr()) for g in gflat], file=sys.stderr)
     views = {k: synth.split_like(v, layout, 4) for k, v in flat.items()}
     g0, g1, gs = (synth.split_like(g, layout, 4) for g in gflat)
@@ -160,7 +161,7 @@ def main():
     quad.init_theta(flat["theta"])
 
     cfg = B.make_config(optimizer=spec["optimizer"], grad_dtype=spec["grad_dtype"], fuse_step2=fused, copy_mask=7,
-                        window=10, tau=3.0, waves_per_block=args.waves_per_block, weight_decay=0.01,
+                        window=10, tau=3.0, weight_decay=0.01,
                         diagnostics=args.diagnostics, clip_norm=args.clip_norm, explicit_steps=args.explicit_steps,
                         **spec["cfg"])
     ctx = B.gxpo_init(cfg, tensors)
@@ -305,7 +306,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": (f"configs[{int(args.workload[1]) - 1}]: " if args.workload[0] == "c" else "") + spec["label"], "params": P,
                    "tensors": len(numels), "grad_dtype": spec["grad_dtype"], "fused_step2": fused,
-                   "waves_per_block": args.waves_per_block or 1, "hbm_layout": "same-phase" if args.same_phase else "moments +32KiB mod 64KiB", "bytes_per_param_per_step": sum(bpp[k] for k in kernel_ms)},
+                   "hbm_layout": "same-phase" if args.same_phase else "moments +32KiB mod 64KiB", "bytes_per_param_per_step": sum(bpp[k] for k in kernel_ms)},
         "hbm_gbps_step": round(step_bytes / ms_per_step / 1e6, 1),
         "hbm_frac_of_peak_step": round(step_bytes / ms_per_step / 1e6 / HBM_PEAK_GBPS, 4),
         "copy_kernel_gbps": round(copy_gbps, 1),

@@ -131,7 +131,6 @@ typedef struct gxpo_config {
     uint32_t window;          /* w: number of past norms the gate statistics use, 2..GXPO_MAX_WINDOW */
     uint32_t gate_min_count;  /* gate is evaluated once the buffer holds this many norms; 0 = window */
     uint32_t gate_ddof;       /* 0 population / 1 sample standard deviation */
-    uint32_t waves_per_block; /* launch shape: 0 = library default, else 1, 2 or 4 */
     uint32_t diagnostics;     /* 1: also accumulate the mechanism diagnostics (gxpo_get_diagnostics) inside
                                  the extrapolation pass and the slow step; g0 is then re-read by the slow
                                  step (+4 or +2 bytes per parameter) and must stay intact until it has run */
@@ -258,7 +257,7 @@ int gxpo_set_state(gxpo_ctx *ctx, const gxpo_state *in);
  * gate_min_count, window, copy_mask) between two training steps, e.g. for a
  * learning-rate or alpha schedule.  Takes effect from the next call on.  What
  * shapes the context's tables and workspace must equal what gxpo_init was
- * given (optimizer, grad_dtype, fuse_step2, waves_per_block, diagnostics,
+ * given (optimizer, grad_dtype, fuse_step2, diagnostics,
  * explicit_steps, and whether clip_norm is zero): GXPO_ERR_INVALID_ARG
  * otherwise.  Phase must be IDLE (GXPO_ERR_BAD_STATE).  A smaller window keeps
  * the most recent norms.  Launches nothing. */
@@ -298,8 +297,7 @@ int gxpo_host_gate_step(const gxpo_config *cfg, gxpo_state *state, double norm, 
 /* How the launch grid covers a ragged tensor list: writes the first block
  * index of every tensor plus the total into block_start[n_tensors + 1] (host)
  * and returns the elements each block covers through *elems_per_block. */
-int gxpo_plan_blocks(const uint64_t *numel, uint32_t n_tensors, uint32_t waves_per_block,
-                     uint32_t *block_start, uint32_t *elems_per_block);
+int gxpo_plan_blocks(const uint64_t *numel, uint32_t n_tensors, uint32_t *block_start, uint32_t *elems_per_block);
 
 /* Where to put the caller-owned buffers in HBM.  Every pass streams several
  * parameter-sized arrays at the same element offset; on MI355X the achieved

@@ -59,7 +59,7 @@ class gxpo_config(ctypes.Structure):
     _fields_ = [("struct_size", ctypes.c_uint32), ("optimizer", ctypes.c_uint32), ("grad_dtype", ctypes.c_uint32),
                 ("K", ctypes.c_uint32), ("fuse_step2", ctypes.c_uint32), ("copy_mask", ctypes.c_uint32),
                 ("window", ctypes.c_uint32), ("gate_min_count", ctypes.c_uint32), ("gate_ddof", ctypes.c_uint32),
-                ("waves_per_block", ctypes.c_uint32), ("diagnostics", ctypes.c_uint32), ("explicit_steps", ctypes.c_uint32),
+                ("diagnostics", ctypes.c_uint32), ("explicit_steps", ctypes.c_uint32),
                 ("lr", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
                 ("adam_eps", ctypes.c_double), ("weight_decay", ctypes.c_double),
                 ("alpha", ctypes.c_double), ("delta", ctypes.c_double), ("r_max", ctypes.c_double),
@@ -127,7 +127,7 @@ _lib.gxpo_host_gate_step.restype = ctypes.c_int
 _lib.gxpo_host_gate_step.argtypes = [ctypes.POINTER(gxpo_config), ctypes.POINTER(gxpo_state), ctypes.c_double,
                                      ctypes.POINTER(gxpo_gate_info)]
 _lib.gxpo_plan_blocks.restype = ctypes.c_int
-_lib.gxpo_plan_blocks.argtypes = [ctypes.POINTER(ctypes.c_uint64), ctypes.c_uint32, ctypes.c_uint32,
+_lib.gxpo_plan_blocks.argtypes = [ctypes.POINTER(ctypes.c_uint64), ctypes.c_uint32,
                                   ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_uint32)]
 _lib.gxpo_layout_hint.restype = ctypes.c_int
 _lib.gxpo_layout_hint.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64)]
@@ -143,7 +143,7 @@ class GxpoError(RuntimeError):
 
 
 def make_config(*, optimizer="adamw", grad_dtype="f32", K=8, fuse_step2=True, copy_mask=7, window=10,
-                gate_min_count=0, gate_ddof=0, waves_per_block=0, diagnostics=False, explicit_steps=0, lr=1e-6, beta1=0.9, beta2=0.999,
+                gate_min_count=0, gate_ddof=0, diagnostics=False, explicit_steps=0, lr=1e-6, beta1=0.9, beta2=0.999,
                 adam_eps=1e-8, weight_decay=0.01, alpha=0.5, delta=1e-8, r_max=math.inf, clip_norm=0.0, tau=3.0,
                 gate_eps=1e-8) -> gxpo_config:
     c = gxpo_config()
@@ -151,7 +151,7 @@ def make_config(*, optimizer="adamw", grad_dtype="f32", K=8, fuse_step2=True, co
     c.optimizer = {"gd": GXPO_OPT_GD, "adamw": GXPO_OPT_ADAMW}.get(optimizer, optimizer)
     c.grad_dtype = {"f32": GXPO_GRAD_F32, "bf16": GXPO_GRAD_BF16}.get(grad_dtype, grad_dtype)
     c.K, c.fuse_step2, c.copy_mask = int(K), int(bool(fuse_step2)), int(copy_mask)
-    c.window, c.gate_min_count, c.gate_ddof, c.waves_per_block = int(window), int(gate_min_count), int(gate_ddof), int(waves_per_block)
+    c.window, c.gate_min_count, c.gate_ddof = int(window), int(gate_min_count), int(gate_ddof)
     c.diagnostics, c.explicit_steps = int(diagnostics), int(explicit_steps)
     c.lr, c.beta1, c.beta2, c.adam_eps, c.weight_decay = lr, beta1, beta2, adam_eps, weight_decay
     c.alpha, c.delta, c.r_max, c.clip_norm, c.tau, c.gate_eps = alpha, delta, r_max, clip_norm, tau, gate_eps
@@ -337,13 +337,13 @@ def new_state() -> gxpo_state:
     return st
 
 
-def gxpo_plan_blocks(numels: Sequence[int], waves_per_block: int = 0):
+def gxpo_plan_blocks(numels: Sequence[int]):
     """Returns (block_start list of len n + 1, elems_per_block)."""
     n = len(numels)
     arr = (ctypes.c_uint64 * max(n, 1))(*numels)
     out = (ctypes.c_uint32 * (n + 1))()
     epb = ctypes.c_uint32(0)
-    rc = _lib.gxpo_plan_blocks(arr, n, waves_per_block, out, ctypes.byref(epb))
+    rc = _lib.gxpo_plan_blocks(arr, n, out, ctypes.byref(epb))
     if rc != GXPO_OK:
         raise GxpoError(rc, "gxpo_plan_blocks rejected its arguments")
     return list(out), epb.value

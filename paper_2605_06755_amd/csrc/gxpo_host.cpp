@@ -26,7 +26,6 @@ std::string format(const char *fmt, va_list ap) {
     return std::string(buf);
 }
 
-constexpr uint32_t kDefaultWavesPerBlock = 1;
 constexpr int kGradRoles = 3;        // g0, g1, g_slow
 constexpr int kStageSlots = 8;       // pinned staging slots for pointer-table uploads
 enum { kRoleG0 = 0, kRoleG1 = 1, kRoleSlow = 2 };
@@ -38,7 +37,6 @@ struct Interval { uintptr_t lo, hi; uint32_t t; const char *what; };
 struct gxpo_ctx {
     gxpo_config cfg{};
     uint32_t n = 0;
-    uint32_t wpb = kDefaultWavesPerBlock;
     int device = -1;
     std::vector<gxpo_tensor> tensors;
     std::vector<gxpo_tensor_options> options;   // parameter groups, all {1, 1} unless set
@@ -123,8 +121,6 @@ int check_config(const gxpo_config *c, std::string &msg) {
     if (c->window < 2 || c->window > GXPO_MAX_WINDOW) return bad("window must be in [2, GXPO_MAX_WINDOW]");
     if (c->gate_min_count == 1 || c->gate_min_count > c->window) return bad("gate_min_count must be 0 or in [2, window]");
     if (c->gate_ddof > 1) return bad("gate_ddof must be 0 or 1");
-    if (c->waves_per_block != 0 && c->waves_per_block != 1 && c->waves_per_block != 2 && c->waves_per_block != 4)
-        return bad("waves_per_block must be 0, 1, 2 or 4");
     if (c->diagnostics > 1) return bad("diagnostics must be 0 or 1");
     if (c->explicit_steps == 1 || c->explicit_steps > 4096) return bad("explicit_steps must be 0 or in [2, 4096]");
     if (c->explicit_steps && c->diagnostics) return bad("diagnostics need the extrapolation (explicit_steps == 0)");
@@ -144,10 +140,8 @@ int check_config(const gxpo_config *c, std::string &msg) {
     return GXPO_OK;
 }
 
-uint32_t resolve_wpb(uint32_t requested) { return requested ? requested : kDefaultWavesPerBlock; }
-
-int plan_blocks(const uint64_t *numel, uint32_t n, uint32_t wpb, std::vector<uint32_t> &start, std::string &msg) {
-    const uint64_t epb = (uint64_t)wpb * kWaveElems;
+int plan_blocks(const uint64_t *numel, uint32_t n, std::vector<uint32_t> &start, std::string &msg) {
+    const uint64_t epb = kWaveElems;
     start.assign((size_t)n + 1, 0);
     uint64_t total = 0;
     for (uint32_t t = 0; t < n; ++t) {
@@ -160,18 +154,27 @@ int plan_blocks(const uint64_t *numel, uint32_t n, uint32_t wpb, std::vector<uin
     return GXPO_OK;
 }
 
-// Is [p, p + bytes) inside one device allocation of the current GPU?
+// Is every byte of [p, p + bytes) device memory of the current GPU?  Usually the range lies in one
+// allocation; a buffer assembled from physical chunks mapped back to back into one reserved
+// address range (HIP's virtual-memory API) is a run of adjacent allocations, which is walked.
 int check_device_range(const gxpo_ctx *ctx, const void *p, uint64_t bytes, const char *what, uint32_t t) {
-    hipDeviceptr_t base = nullptr;
-    size_t size = 0;
-    hipError_t e = hipMemGetAddressRange(&base, &size, (hipDeviceptr_t)p);
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
-        return fail(ctx, GXPO_ERR_INVALID_ARG, "tensor %u: %s is not a device allocation (%s)", t, what, hipGetErrorString(e));
+    const char *q = (const char *)p, *const end = q + bytes;
+    for (int hops = 0; q < end; ++hops) {
+        hipDeviceptr_t base = nullptr;
+        size_t size = 0;
+        hipError_t e = hipMemGetAddressRange(&base, &size, (hipDeviceptr_t)q);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            if (hops == 0)
+                return fail(ctx, GXPO_ERR_INVALID_ARG, "tensor %u: %s is not a device allocation (%s)", t, what, hipGetErrorString(e));
+            return fail(ctx, GXPO_ERR_INVALID_ARG, "tensor %u: %s + numel runs past the end of its device allocation", t, what);
+        }
+        const char *b = (const char *)base;
+        if (q < b || q >= b + size || size == 0)
+            return fail(ctx, GXPO_ERR_INVALID_ARG, "tensor %u: %s + numel runs past the end of its device allocation", t, what);
+        q = b + size;                              // first byte after this allocation
+        if (hops > (1 << 20)) return fail(ctx, GXPO_ERR_INVALID_ARG, "tensor %u: %s spans too many allocations", t, what);
     }
-    const char *b = (const char *)base, *q = (const char *)p;
-    if (q < b || (uint64_t)(q - b) + bytes > (uint64_t)size)
-        return fail(ctx, GXPO_ERR_INVALID_ARG, "tensor %u: %s + numel runs past the end of its device allocation", t, what);
     return GXPO_OK;
 }
 
@@ -237,8 +240,9 @@ int stage_grads(gxpo_ctx *ctx, int role, const void *const *grads, hipStream_t s
     bool changed = false;
     for (uint32_t t = 0; t < n; ++t) {
         const void *g = grads[t];
-        if (g == sh[t]) continue;
+        // NULL first: the shadow table starts out all NULL, so a NULL entry would otherwise pass as "unchanged"
         if (!g) return fail(ctx, GXPO_ERR_INVALID_ARG, "gradient pointer of tensor %u is NULL", t);
+        if (g == sh[t]) continue;
         if ((uintptr_t)g % align) return fail(ctx, GXPO_ERR_ALIGNMENT, "gradient pointer of tensor %u is not %u-byte aligned", t, (unsigned)align);
         int rc = check_device_range(ctx, g, ctx->tensors[t].numel * gbytes, "gradient", t);
         if (rc != GXPO_OK) return rc;
@@ -265,7 +269,7 @@ int stage_grads(gxpo_ctx *ctx, int role, const void *const *grads, hipStream_t s
 // Gradient clipping: norm of the staged gradient list -> its clipping factor on the device.
 int clip_prepass(gxpo_ctx *ctx, const GradArg &g, int acc, int clip_index, hipStream_t s) {
     if (!ctx->d_clip) return GXPO_OK;
-    GXPO_HIP(ctx, launch_sumsq(ctx->layout(), ctx->wpb, (int)ctx->cfg.grad_dtype, g, ctx->d_partial, acc, s));
+    GXPO_HIP(ctx, launch_sumsq(ctx->layout(), (int)ctx->cfg.grad_dtype, g, ctx->d_partial, acc, s));
     GXPO_HIP(ctx, launch_finalize(ctx->d_partial, ctx->n_blocks, ctx->d_seg, ctx->n_segs, ctx->d_tensor_seg_start, ctx->n,
                                   ctx->d_seg_sum, ctx->d_result, acc, 1, s));
     GXPO_HIP(ctx, launch_clip_coefficient(ctx->d_result, ctx->n, acc, ctx->cfg.clip_norm, ctx->d_clip, clip_index, s));
@@ -306,17 +310,14 @@ int gxpo_validate_config(const gxpo_config *cfg, char *msg, size_t cap) {
     return rc;
 }
 
-int gxpo_plan_blocks(const uint64_t *numel, uint32_t n_tensors, uint32_t waves_per_block, uint32_t *block_start,
-                     uint32_t *elems_per_block) {
+int gxpo_plan_blocks(const uint64_t *numel, uint32_t n_tensors, uint32_t *block_start, uint32_t *elems_per_block) {
     if (!numel || !block_start || n_tensors == 0) return GXPO_ERR_INVALID_ARG;
-    if (waves_per_block != 0 && waves_per_block != 1 && waves_per_block != 2 && waves_per_block != 4) return GXPO_ERR_INVALID_ARG;
-    const uint32_t wpb = resolve_wpb(waves_per_block);
     std::vector<uint32_t> start;
     std::string msg;
-    int rc = plan_blocks(numel, n_tensors, wpb, start, msg);
+    int rc = plan_blocks(numel, n_tensors, start, msg);
     if (rc != GXPO_OK) return rc;
     std::copy(start.begin(), start.end(), block_start);
-    if (elems_per_block) *elems_per_block = wpb * kWaveElems;
+    if (elems_per_block) *elems_per_block = kWaveElems;
     return GXPO_OK;
 }
 
@@ -395,9 +396,8 @@ int gxpo_init(gxpo_ctx **out, const gxpo_config *cfg, const gxpo_tensor *tensors
         if (x.model_copy && (uintptr_t)x.model_copy % 8)
             return fail(nullptr, GXPO_ERR_ALIGNMENT, "tensor %u: model_copy is not 8-byte aligned", t);
     }
-    const uint32_t wpb = resolve_wpb(cfg->waves_per_block);
     std::vector<uint32_t> blk_start;
-    rc = plan_blocks(numel.data(), n_tensors, wpb, blk_start, msg);
+    rc = plan_blocks(numel.data(), n_tensors, blk_start, msg);
     if (rc != GXPO_OK) return fail(nullptr, rc, "%s", msg.c_str());
 
     // buffers must not overlap one another
@@ -432,7 +432,6 @@ int gxpo_init(gxpo_ctx **out, const gxpo_config *cfg, const gxpo_tensor *tensors
     if (!ctx) return fail(nullptr, GXPO_ERR_NOMEM, "out of host memory");
     ctx->cfg = *cfg;
     ctx->n = n_tensors;
-    ctx->wpb = wpb;
     ctx->n_acc = (cfg->diagnostics || cfg->clip_norm > 0.0) ? (uint32_t)kNumAcc : 1u;
     ctx->device = device;
     ctx->tensors.assign(tensors, tensors + n_tensors);
@@ -544,7 +543,7 @@ int gxpo_fast_steps(gxpo_ctx *ctx, int which, const void *const *grads, void *st
         const int wc = ((which == 0 || ctx->cfg.explicit_steps) && copy_at_probe) ? 1 : 0;
         // fused schedule: the probe pass only previews the step, the moments are advanced by gxpo_extrapolate
         const int write_moments = fused ? 0 : 1;
-        GXPO_HIP(ctx, launch_step(ctx->layout(), ctx->wpb, (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, src, kSrcProbe,
+        GXPO_HIP(ctx, launch_step(ctx->layout(), (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, src, kSrcProbe,
                                   write_moments, wc, nullptr, GradArg{}, ctx->d_clip, which == 0 ? kClipG0 : kClipG1, s));
         if (fused) {
             ctx->pending_g0.assign(grads, grads + ctx->n);
@@ -567,7 +566,7 @@ int gxpo_extrapolate(gxpo_ctx *ctx, const void *const *g0, const void *const *g1
         if (rc0 != GXPO_OK) return rc0;
         if (ctx->st.phase != GXPO_PHASE_FAST2) return fail(ctx, GXPO_ERR_BAD_STATE, "gxpo_extrapolate called in phase %u", ctx->st.phase);
         const int wc0 = (ctx->cfg.copy_mask & GXPO_COPY_AT_TILDE) ? 1 : 0;
-        GXPO_HIP(ctx, launch_reposition(ctx->layout(), ctx->wpb, (float)ctx->cfg.alpha, wc0, (hipStream_t)stream));
+        GXPO_HIP(ctx, launch_reposition(ctx->layout(), (float)ctx->cfg.alpha, wc0, (hipStream_t)stream));
         ctx->st.phase = GXPO_PHASE_REPOSITIONED;
         return GXPO_OK;
     }
@@ -594,10 +593,10 @@ int gxpo_extrapolate(gxpo_ctx *ctx, const void *const *g0, const void *const *g1
     if (ctx->cfg.fuse_step2) {
         const StepParams p1 = make_step_params(ctx->cfg, ctx->pending_step1);
         const StepParams p2 = make_step_params(ctx->cfg, ctx->pending_step2);
-        GXPO_HIP(ctx, launch_fused_steps_extrapolate(ctx->layout(), ctx->wpb, (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g0, d_g1,
+        GXPO_HIP(ctx, launch_fused_steps_extrapolate(ctx->layout(), (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g0, d_g1,
                                                      p1, p2, e, wc, diag, ctx->d_clip, s));
     } else {
-        GXPO_HIP(ctx, launch_extrapolate(ctx->layout(), ctx->wpb, (int)ctx->cfg.grad_dtype, d_g0, d_g1, e, wc, diag, ctx->d_clip, s));
+        GXPO_HIP(ctx, launch_extrapolate(ctx->layout(), (int)ctx->cfg.grad_dtype, d_g0, d_g1, e, wc, diag, ctx->d_clip, s));
     }
     if (diag)
         GXPO_HIP(ctx, launch_finalize(ctx->d_partial, ctx->n_blocks, ctx->d_seg, ctx->n_segs, ctx->d_tensor_seg_start, ctx->n,
@@ -631,7 +630,7 @@ int gxpo_slow_step(gxpo_ctx *ctx, const void *const *g_slow, void *stream) {
     rc = clip_prepass(ctx, d_g, kAccSlowSq, kClipSlow, s);
     if (rc != GXPO_OK) return rc;
     double *partial = (ctx->d_clip && !cos_valid) ? nullptr : ctx->d_partial;
-    GXPO_HIP(ctx, launch_step(ctx->layout(), ctx->wpb, (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, kSrcTheta, kSrcTheta, 1, wc,
+    GXPO_HIP(ctx, launch_step(ctx->layout(), (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, kSrcTheta, kSrcTheta, 1, wc,
                               partial, dot, ctx->d_clip, kClipSlow, s));
     if (partial)
         GXPO_HIP(ctx, launch_finalize(ctx->d_partial, ctx->n_blocks, ctx->d_seg, ctx->n_segs, ctx->d_tensor_seg_start, ctx->n,
@@ -680,7 +679,7 @@ int gxpo_fallback_step(gxpo_ctx *ctx, const void *const *g0, void *stream) {
     const int wc = (ctx->cfg.copy_mask & GXPO_COPY_AT_FINAL) ? 1 : 0;
     rc = clip_prepass(ctx, d_g, kAccClipG0, kClipG0, s);
     if (rc != GXPO_OK) return rc;
-    GXPO_HIP(ctx, launch_step(ctx->layout(), ctx->wpb, (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, kSrcTheta, kSrcTheta, 1, wc,
+    GXPO_HIP(ctx, launch_step(ctx->layout(), (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, kSrcTheta, kSrcTheta, 1, wc,
                               nullptr, GradArg{}, ctx->d_clip, kClipG0, s));
     st.optim_steps = step_no;
     st.backward_passes += 1;
@@ -760,11 +759,11 @@ int gxpo_update_config(gxpo_ctx *ctx, const gxpo_config *cfg) {
     if (ctx->st.phase != GXPO_PHASE_IDLE) return fail(ctx, GXPO_ERR_BAD_STATE, "gxpo_update_config: a training step is in progress");
     const gxpo_config &o = ctx->cfg;
     const bool same_shape = cfg->optimizer == o.optimizer && cfg->grad_dtype == o.grad_dtype && cfg->fuse_step2 == o.fuse_step2 &&
-                            resolve_wpb(cfg->waves_per_block) == ctx->wpb && cfg->diagnostics == o.diagnostics &&
+                            cfg->diagnostics == o.diagnostics &&
                             cfg->explicit_steps == o.explicit_steps && (cfg->clip_norm > 0.0) == (o.clip_norm > 0.0);
     if (!same_shape)
         return fail(ctx, GXPO_ERR_INVALID_ARG,
-                    "gxpo_update_config: optimizer, grad_dtype, fuse_step2, waves_per_block, diagnostics, explicit_steps and "
+                    "gxpo_update_config: optimizer, grad_dtype, fuse_step2, diagnostics, explicit_steps and "
                     "clipping on/off are fixed at gxpo_init");
     gxpo_state &st = ctx->st;
     if (st.window_len > cfg->window) {       // keep the most recent norms

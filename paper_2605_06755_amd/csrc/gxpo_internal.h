@@ -106,13 +106,13 @@ __host__ __device__ inline size_t partial_pitch(uint32_t n_blocks) { return (siz
 // All launchers enqueue on `stream` and return the launch status.
 // d_partial: nullptr = no reduction; otherwise sum g^2 goes to accumulator kAccSlowSq and, when
 // d_g0_for_dot holds a list, sum g0*g to kAccG0Slow.
-hipError_t launch_step(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype,
+hipError_t launch_step(const Layout &L, int optimizer, int grad_dtype,
                        const GradArg &d_grads, const StepParams &p,
                        int src, int dst, int write_moments, int write_copy, double *d_partial,
                        const GradArg &d_g0_for_dot, const float *d_clip, int clip_index, hipStream_t stream);
 
 // sum of squares of one gradient list into accumulator `acc` (read-only pass, 4 or 2 B/param)
-hipError_t launch_sumsq(const Layout &L, uint32_t wpb, int grad_dtype, const GradArg &d_grads, double *d_partial, int acc,
+hipError_t launch_sumsq(const Layout &L, int grad_dtype, const GradArg &d_grads, double *d_partial, int acc,
                         hipStream_t stream);
 
 // d_clip[clip_index] = min(1, max_norm / (sqrt(result of accumulator acc) + 1e-6))
@@ -121,16 +121,16 @@ hipError_t launch_clip_coefficient(const double *d_result, uint32_t n_tensors, i
 
 // d_diag_partial (both extrapolation launchers): nullptr, or the partial arrays; then the pass
 // also fills accumulators kAccG0Sq .. kAccDK.
-hipError_t launch_extrapolate(const Layout &L, uint32_t wpb, int grad_dtype,
+hipError_t launch_extrapolate(const Layout &L, int grad_dtype,
                               const GradArg &d_g0, const GradArg &d_g1,
                               const ExtrapParams &e, int write_copy, double *d_diag_partial, const float *d_clip,
                               hipStream_t stream);
 
 // theta <- theta + alpha (theta_probe - theta), nothing else (explicit lookahead).
-hipError_t launch_reposition(const Layout &L, uint32_t wpb, float alpha, int write_copy, hipStream_t stream);
+hipError_t launch_reposition(const Layout &L, float alpha, int write_copy, hipStream_t stream);
 
 // p1 / p2: constants of the first / second fast step (both are applied here).
-hipError_t launch_fused_steps_extrapolate(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype,
+hipError_t launch_fused_steps_extrapolate(const Layout &L, int optimizer, int grad_dtype,
                                           const GradArg &d_g0, const GradArg &d_g1,
                                           const StepParams &p1, const StepParams &p2, const ExtrapParams &e,
                                           int write_copy, double *d_diag_partial, const float *d_clip, hipStream_t stream);

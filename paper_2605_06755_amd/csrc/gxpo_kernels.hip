@@ -3,11 +3,14 @@
 // Every pass is a pure HBM stream: no element needs a neighbour, nothing is
 // reused, so the kernels are built around how MI355X moves bytes best:
 //
-//  * one-shot blocks: a block is WPB wavefronts, each lane owns 4 consecutive
-//    elements (one 128-bit access per fp32 stream) and the block retires after
-//    a single load -> compute -> store round.  Blocks are dispatched in index
-//    order, so the set of DRAM pages in flight stays a narrow moving front;
-//    measured on this part that beats grid-stride loops by ~20 %.
+//  * one-shot blocks of one wavefront: each lane owns 4 consecutive elements
+//    (one 128-bit access per fp32 stream, one 64-bit access per bf16 stream)
+//    and the block retires after a single load -> compute -> store round.
+//    Blocks are dispatched in index order, so the set of DRAM pages in flight
+//    stays a narrow moving front; measured on this part that beats grid-stride
+//    loops by ~20 %, blocks of 2 or 4 wavefronts by 3-8 %, and lanes that own
+//    8 elements (two 128-bit accesses per fp32 stream, one per bf16 stream)
+//    by 4-6 %.
 //  * buffer instructions with the streaming cache policy (sc1 + nt): the data
 //    is touched once per pass, there is nothing for L2 / MALL to keep.  The
 //    buffer descriptor of each stream covers exactly the block's span, so the
@@ -125,8 +128,8 @@ struct Span {
     bool full;
 };
 
-template <int WPB> __device__ __forceinline__ Span locate(const Layout &L, uint32_t b) {
-    constexpr uint32_t kBlockElems = WPB * kWaveElems;
+__device__ __forceinline__ Span locate(const Layout &L, uint32_t b) {
+    constexpr uint32_t kBlockElems = kWaveElems;
     uint32_t t = 0;
     if (L.n_tensors > 1) {
         t = L.coarse[b >> kCoarseShift];
@@ -237,45 +240,25 @@ __device__ __forceinline__ double wave_sum(double x) {
     return __hiloint2double(hi, lo);
 }
 
-// Adds the N per-lane values over the block and stores them as this block's
-// partials of accumulators first_acc .. first_acc + N - 1 (fixed order: lane
-// butterfly, then wavefronts in index order).
-template <int WPB, int N>
+// Adds the N per-lane values over the block (one wavefront) and stores them as this block's
+// partials of accumulators first_acc .. first_acc + N - 1 (fixed order: the lane butterfly).
+template <int N>
 __device__ __forceinline__ void store_block_sums(double (&acc)[N], double *__restrict__ partial, int first_acc, uint32_t n_blocks,
                                                  uint32_t block) {
     const size_t pitch = partial_pitch(n_blocks);
     const uint32_t slot = partial_slot(block, partial_stride(n_blocks));
 #pragma unroll
     for (int a = 0; a < N; ++a) acc[a] = wave_sum(acc[a]);
-    if (WPB == 1) {
-        if (threadIdx.x == 0) {
+    if (threadIdx.x == 0) {
 #pragma unroll
-            for (int a = 0; a < N; ++a) partial[(size_t)(first_acc + a) * pitch + slot] = acc[a];
-        }
-    } else {
-        __shared__ double wave_part[N][WPB];
-        if ((threadIdx.x & 63) == 0) {
-#pragma unroll
-            for (int a = 0; a < N; ++a) wave_part[a][threadIdx.x >> 6] = acc[a];
-        }
-        __syncthreads();
-        if (threadIdx.x == 0) {
-#pragma unroll
-            for (int a = 0; a < N; ++a) {
-                double total = 0.0;
-#pragma unroll
-                for (int w = 0; w < WPB; ++w) total += wave_part[a][w];
-                partial[(size_t)(first_acc + a) * pitch + slot] = total;
-            }
-        }
-        __syncthreads();        // the staging array may be reused by a following call
+        for (int a = 0; a < N; ++a) partial[(size_t)(first_acc + a) * pitch + slot] = acc[a];
     }
 }
 
 // Per-lane accumulators of the extrapolation-pass diagnostics.  The two gradient norms must
 // match an fp64 reference to ~1e-12 and stay in fp64.  The other statistics are means and
 // ratios of fp32 quantities (r, scale and the displacements are formed in fp32 to begin
-// with): they are summed in fp32 inside a block (256 * WPB terms, pairwise over the lanes)
+// with): they are summed in fp32 inside a block (256 terms, pairwise over the lanes)
 // and in fp64 from the block partial on; the active count is an integer.  That keeps the
 // diagnostics from turning the pass ALU-bound (fp64 adds and 64-bit lane exchanges are the
 // expensive part of a block's reduction).
@@ -325,8 +308,7 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t x) {
 }
 
 // Block totals of the eight extrapolation-pass accumulators -> this block's partials of
-// accumulators kAccG0Sq .. kAccDK (fixed order: lanes, then wavefronts in index order).
-template <int WPB>
+// accumulators kAccG0Sq .. kAccDK (fixed order: the lane butterfly).
 __device__ __forceinline__ void store_extrap_diag(const ExtrapDiag &d, double *__restrict__ partial, uint32_t n_blocks, uint32_t block) {
     double acc[kNumExtrapAcc];
     acc[kAccG0Sq - kAccG0Sq] = wave_sum(d.g0_sq);
@@ -339,27 +321,9 @@ __device__ __forceinline__ void store_extrap_diag(const ExtrapDiag &d, double *_
     acc[kAccDK - kAccG0Sq] = (double)wave_sum(d.dK_sq);
     const size_t pitch = partial_pitch(n_blocks);
     const uint32_t slot = partial_slot(block, partial_stride(n_blocks));
-    if (WPB == 1) {
-        if (threadIdx.x == 0) {
+    if (threadIdx.x == 0) {
 #pragma unroll
-            for (int a = 0; a < kNumExtrapAcc; ++a) partial[(size_t)(kAccG0Sq + a) * pitch + slot] = acc[a];
-        }
-    } else {
-        __shared__ double wave_part[kNumExtrapAcc][WPB];
-        if ((threadIdx.x & 63) == 0) {
-#pragma unroll
-            for (int a = 0; a < kNumExtrapAcc; ++a) wave_part[a][threadIdx.x >> 6] = acc[a];
-        }
-        __syncthreads();
-        if (threadIdx.x == 0) {
-#pragma unroll
-            for (int a = 0; a < kNumExtrapAcc; ++a) {
-                double total = 0.0;
-#pragma unroll
-                for (int w = 0; w < WPB; ++w) total += wave_part[a][w];
-                partial[(size_t)(kAccG0Sq + a) * pitch + slot] = total;
-            }
-        }
+        for (int a = 0; a < kNumExtrapAcc; ++a) partial[(size_t)(kAccG0Sq + a) * pitch + slot] = acc[a];
     }
 }
 
@@ -373,11 +337,11 @@ __device__ __forceinline__ void store_extrap_diag(const ExtrapDiag &d, double *_
 // dropped because the fused pass recomputes them from the same inputs
 // (20 B/param: 16 read, 4 written; 18 when only the bf16 copy is written).
 // ============================================================================
-template <int WPB, int OPT, int GDT>
-__global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, GradArg grads, StepParams p_all, int src, int dst,
+template <int OPT, int GDT>
+__global__ __launch_bounds__(64) void k_optim_step(Layout L, GradArg grads, StepParams p_all, int src, int dst,
                                                        int write_moments, int write_copy, double *__restrict__ partial,
                                                        GradArg dot_with, const float *__restrict__ clip, int clip_index) {
-    const Span s = locate<WPB>(L, blockIdx.x);
+    const Span s = locate(L, blockIdx.x);
     const StepParams p = for_tensor(p_all, s.rec);
     const uint32_t elem = threadIdx.x * kLaneElems;
     const uint32_t bytes = s.cnt * 4u;
@@ -424,10 +388,10 @@ __global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, GradArg grads
             const f32x4 o = load_grad<GDT>(grad_rsrc<GDT>(other, s.e0, s.cnt), elem, s.full);
 #pragma unroll
             for (int k = 0; k < 4; ++k) acc[1] = fma((double)o[k], (double)g[k], acc[1]);
-            store_block_sums<WPB, 2>(acc, partial, kAccSlowSq, L.n_blocks, blockIdx.x);
+            store_block_sums<2>(acc, partial, kAccSlowSq, L.n_blocks, blockIdx.x);
         } else {
             double only[1] = {acc[0]};
-            store_block_sums<WPB, 1>(only, partial, kAccSlowSq, L.n_blocks, blockIdx.x);
+            store_block_sums<1>(only, partial, kAccSlowSq, L.n_blocks, blockIdx.x);
         }
     }
 }
@@ -437,11 +401,11 @@ __global__ __launch_bounds__(64 * WPB) void k_optim_step(Layout L, GradArg grads
 //   theta <- theta + alpha * scale * (theta_probe - theta)
 // 20 B/param with fp32 gradients (16 read, 4 written).
 // ============================================================================
-template <int WPB, int GDT, bool DIAG>
-__global__ __launch_bounds__(64 * WPB) void k_extrapolate(Layout L, GradArg g0s, GradArg g1s, ExtrapParams e,
+template <int GDT, bool DIAG>
+__global__ __launch_bounds__(64) void k_extrapolate(Layout L, GradArg g0s, GradArg g1s, ExtrapParams e,
                                                         int write_copy, double *__restrict__ diag_partial,
                                                         const float *__restrict__ clip) {
-    const Span s = locate<WPB>(L, blockIdx.x);
+    const Span s = locate(L, blockIdx.x);
     const uint32_t elem = threadIdx.x * kLaneElems;
     const uint32_t bytes = s.cnt * 4u;
     const auto r_th = span_rsrc(s.rec.theta + s.e0, bytes);
@@ -466,16 +430,15 @@ __global__ __launch_bounds__(64 * WPB) void k_extrapolate(Layout L, GradArg g0s,
         const auto r_c = span_rsrc((unsigned short *)s.rec.copy + s.e0, s.cnt * 2u);
         store_bf16(r_c, elem, s.full, th0);
     }
-    if (DIAG) store_extrap_diag<WPB>(diag, diag_partial, L.n_blocks, blockIdx.x);
+    if (DIAG) store_extrap_diag(diag, diag_partial, L.n_blocks, blockIdx.x);
 }
 
 // ============================================================================
 // Reposition alone (explicit lookahead): theta <- theta + alpha (theta_probe - theta).
 // 12 B/param (8 read, 4 written).
 // ============================================================================
-template <int WPB>
-__global__ __launch_bounds__(64 * WPB) void k_reposition(Layout L, float alpha, int write_copy) {
-    const Span s = locate<WPB>(L, blockIdx.x);
+__global__ __launch_bounds__(64) void k_reposition(Layout L, float alpha, int write_copy) {
+    const Span s = locate(L, blockIdx.x);
     const uint32_t elem = threadIdx.x * kLaneElems;
     const uint32_t bytes = s.cnt * 4u;
     const auto r_th = span_rsrc(s.rec.theta + s.e0, bytes);
@@ -506,12 +469,12 @@ __global__ __launch_bounds__(64 * WPB) void k_reposition(Layout L, float alpha, 
 // write and re-read of m, v (16 B) and the re-read of theta^{t,1} (4 B):
 // 32 B/param with fp32 gradients (20 read, 12 written).
 // ============================================================================
-template <int WPB, int OPT, int GDT, bool DIAG>
-__global__ __launch_bounds__(64 * WPB) void k_fused_steps_extrapolate(Layout L, GradArg g0s, GradArg g1s, StepParams p1_all,
+template <int OPT, int GDT, bool DIAG>
+__global__ __launch_bounds__(64) void k_fused_steps_extrapolate(Layout L, GradArg g0s, GradArg g1s, StepParams p1_all,
                                                                     StepParams p2_all, ExtrapParams e, int write_copy,
                                                                     double *__restrict__ diag_partial,
                                                                     const float *__restrict__ clip) {
-    const Span s = locate<WPB>(L, blockIdx.x);
+    const Span s = locate(L, blockIdx.x);
     const StepParams p1 = for_tensor(p1_all, s.rec), p2 = for_tensor(p2_all, s.rec);
     const uint32_t elem = threadIdx.x * kLaneElems;
     const uint32_t bytes = s.cnt * 4u;
@@ -553,7 +516,7 @@ __global__ __launch_bounds__(64 * WPB) void k_fused_steps_extrapolate(Layout L, 
         const auto r_c = span_rsrc((unsigned short *)s.rec.copy + s.e0, s.cnt * 2u);
         store_bf16(r_c, elem, s.full, th0);
     }
-    if (DIAG) store_extrap_diag<WPB>(diag, diag_partial, L.n_blocks, blockIdx.x);
+    if (DIAG) store_extrap_diag(diag, diag_partial, L.n_blocks, blockIdx.x);
 }
 
 // ============================================================================
@@ -565,8 +528,8 @@ __global__ __launch_bounds__(64 * WPB) void k_fused_steps_extrapolate(Layout L, 
 // partial per plan block, so the reduction that follows is the same.
 constexpr uint32_t kSumsqGroup = 4;
 
-template <int WPB, int GDT>
-__global__ __launch_bounds__(64 * WPB) void k_sumsq(Layout L, GradArg grads, double *__restrict__ partial, int acc_index) {
+template <int GDT>
+__global__ __launch_bounds__(64) void k_sumsq(Layout L, GradArg grads, double *__restrict__ partial, int acc_index) {
     const uint32_t elem = threadIdx.x * kLaneElems;
     const uint32_t first = blockIdx.x * kSumsqGroup;
     f32x4 g[kSumsqGroup];
@@ -574,7 +537,7 @@ __global__ __launch_bounds__(64 * WPB) void k_sumsq(Layout L, GradArg grads, dou
     for (uint32_t i = 0; i < kSumsqGroup; ++i) {
         g[i] = f32x4{0, 0, 0, 0};
         if (first + i < L.n_blocks) {
-            const Span s = locate<WPB>(L, first + i);
+            const Span s = locate(L, first + i);
             g[i] = load_grad<GDT>(grad_rsrc<GDT>(grad_ptr(grads, L, s.tensor), s.e0, s.cnt), elem, s.full);
         }
     }
@@ -584,7 +547,7 @@ __global__ __launch_bounds__(64 * WPB) void k_sumsq(Layout L, GradArg grads, dou
             double acc[1] = {0.0};
 #pragma unroll
             for (int k = 0; k < 4; ++k) acc[0] = fma((double)g[i][k], (double)g[i][k], acc[0]);
-            store_block_sums<WPB, 1>(acc, partial, acc_index, L.n_blocks, first + i);
+            store_block_sums<1>(acc, partial, acc_index, L.n_blocks, first + i);
         }
     }
 }
@@ -670,99 +633,57 @@ __global__ __launch_bounds__(64) void k_stream_copy(const float *__restrict__ sr
     store_f32(r_d, elem, true, load_f32(r_s, elem, true));
 }
 
-template <int WPB>
-hipError_t step_wpb(const Layout &L, int optimizer, int grad_dtype, const GradArg &g, const StepParams &p, int src, int dst,
-                    int write_moments, int write_copy, double *partial, const GradArg &dot, const float *clip, int clip_index,
-                    hipStream_t st) {
-    const dim3 grid(L.n_blocks), block(64 * WPB);
-    if (optimizer == 0 && grad_dtype == 0) k_optim_step<WPB, 0, 0><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial, dot, clip, clip_index);
-    else if (optimizer == 0) k_optim_step<WPB, 0, 1><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial, dot, clip, clip_index);
-    else if (grad_dtype == 0) k_optim_step<WPB, 1, 0><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial, dot, clip, clip_index);
-    else k_optim_step<WPB, 1, 1><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial, dot, clip, clip_index);
-    return hipGetLastError();
-}
-
-template <int WPB, bool DIAG>
-hipError_t extrap_wpb(const Layout &L, int grad_dtype, const GradArg &g0, const GradArg &g1, const ExtrapParams &e,
-                      int write_copy, double *diag, const float *clip, hipStream_t st) {
-    const dim3 grid(L.n_blocks), block(64 * WPB);
-    if (grad_dtype == 0) k_extrapolate<WPB, 0, DIAG><<<grid, block, 0, st>>>(L, g0, g1, e, write_copy, diag, clip);
-    else k_extrapolate<WPB, 1, DIAG><<<grid, block, 0, st>>>(L, g0, g1, e, write_copy, diag, clip);
-    return hipGetLastError();
-}
-
-template <int WPB, bool DIAG>
-hipError_t fused_wpb(const Layout &L, int optimizer, int grad_dtype, const GradArg &g0, const GradArg &g1,
-                     const StepParams &p1, const StepParams &p2, const ExtrapParams &e, int write_copy, double *diag,
-                     const float *clip, hipStream_t st) {
-    const dim3 grid(L.n_blocks), block(64 * WPB);
-    if (optimizer == 0 && grad_dtype == 0) k_fused_steps_extrapolate<WPB, 0, 0, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag, clip);
-    else if (optimizer == 0) k_fused_steps_extrapolate<WPB, 0, 1, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag, clip);
-    else if (grad_dtype == 0) k_fused_steps_extrapolate<WPB, 1, 0, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag, clip);
-    else k_fused_steps_extrapolate<WPB, 1, 1, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag, clip);
-    return hipGetLastError();
-}
-
 }  // namespace
 
-hipError_t launch_step(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype, const GradArg &d_grads,
-                       const StepParams &p, int src, int dst, int write_moments, int write_copy, double *d_partial,
-                       const GradArg &d_g0_for_dot, const float *d_clip, int clip_index, hipStream_t stream) {
-    switch (wpb) {
-        case 1: return step_wpb<1>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_moments, write_copy, d_partial, d_g0_for_dot, d_clip, clip_index, stream);
-        case 2: return step_wpb<2>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_moments, write_copy, d_partial, d_g0_for_dot, d_clip, clip_index, stream);
-        case 4: return step_wpb<4>(L, optimizer, grad_dtype, d_grads, p, src, dst, write_moments, write_copy, d_partial, d_g0_for_dot, d_clip, clip_index, stream);
-    }
-    return hipErrorInvalidValue;
-}
-
-hipError_t launch_extrapolate(const Layout &L, uint32_t wpb, int grad_dtype, const GradArg &d_g0, const GradArg &d_g1,
-                              const ExtrapParams &e, int write_copy, double *d_diag_partial, const float *d_clip,
-                              hipStream_t stream) {
-    const bool diag = d_diag_partial != nullptr;
-    switch (wpb) {
-        case 1: return diag ? extrap_wpb<1, true>(L, grad_dtype, d_g0, d_g1, e, write_copy, d_diag_partial, d_clip, stream)
-                            : extrap_wpb<1, false>(L, grad_dtype, d_g0, d_g1, e, write_copy, nullptr, d_clip, stream);
-        case 2: return diag ? extrap_wpb<2, true>(L, grad_dtype, d_g0, d_g1, e, write_copy, d_diag_partial, d_clip, stream)
-                            : extrap_wpb<2, false>(L, grad_dtype, d_g0, d_g1, e, write_copy, nullptr, d_clip, stream);
-        case 4: return diag ? extrap_wpb<4, true>(L, grad_dtype, d_g0, d_g1, e, write_copy, d_diag_partial, d_clip, stream)
-                            : extrap_wpb<4, false>(L, grad_dtype, d_g0, d_g1, e, write_copy, nullptr, d_clip, stream);
-    }
-    return hipErrorInvalidValue;
-}
-
-hipError_t launch_fused_steps_extrapolate(const Layout &L, uint32_t wpb, int optimizer, int grad_dtype, const GradArg &d_g0,
-                                          const GradArg &d_g1, const StepParams &p1, const StepParams &p2,
-                                          const ExtrapParams &e, int write_copy, double *d_diag_partial, const float *d_clip,
-                                          hipStream_t stream) {
-    const bool diag = d_diag_partial != nullptr;
-    switch (wpb) {
-        case 1: return diag ? fused_wpb<1, true>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, d_diag_partial, d_clip, stream)
-                            : fused_wpb<1, false>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, nullptr, d_clip, stream);
-        case 2: return diag ? fused_wpb<2, true>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, d_diag_partial, d_clip, stream)
-                            : fused_wpb<2, false>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, nullptr, d_clip, stream);
-        case 4: return diag ? fused_wpb<4, true>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, d_diag_partial, d_clip, stream)
-                            : fused_wpb<4, false>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, nullptr, d_clip, stream);
-    }
-    return hipErrorInvalidValue;
-}
-
-template <int WPB>
-hipError_t sumsq_wpb(const Layout &L, int grad_dtype, const GradArg &g, double *partial, int acc, hipStream_t st) {
-    const dim3 grid((L.n_blocks + kSumsqGroup - 1) / kSumsqGroup), block(64 * WPB);
-    if (grad_dtype == 0) k_sumsq<WPB, 0><<<grid, block, 0, st>>>(L, g, partial, acc);
-    else k_sumsq<WPB, 1><<<grid, block, 0, st>>>(L, g, partial, acc);
+hipError_t launch_step(const Layout &L, int optimizer, int grad_dtype, const GradArg &g, const StepParams &p, int src, int dst,
+                       int write_moments, int write_copy, double *partial, const GradArg &dot, const float *clip, int clip_index,
+                       hipStream_t st) {
+    const dim3 grid(L.n_blocks), block(64);
+    if (optimizer == 0 && grad_dtype == 0) k_optim_step<0, 0><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial, dot, clip, clip_index);
+    else if (optimizer == 0) k_optim_step<0, 1><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial, dot, clip, clip_index);
+    else if (grad_dtype == 0) k_optim_step<1, 0><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial, dot, clip, clip_index);
+    else k_optim_step<1, 1><<<grid, block, 0, st>>>(L, g, p, src, dst, write_moments, write_copy, partial, dot, clip, clip_index);
     return hipGetLastError();
 }
 
-hipError_t launch_sumsq(const Layout &L, uint32_t wpb, int grad_dtype, const GradArg &d_grads, double *d_partial, int acc,
-                        hipStream_t stream) {
-    switch (wpb) {
-        case 1: return sumsq_wpb<1>(L, grad_dtype, d_grads, d_partial, acc, stream);
-        case 2: return sumsq_wpb<2>(L, grad_dtype, d_grads, d_partial, acc, stream);
-        case 4: return sumsq_wpb<4>(L, grad_dtype, d_grads, d_partial, acc, stream);
+hipError_t launch_extrapolate(const Layout &L, int grad_dtype, const GradArg &g0, const GradArg &g1, const ExtrapParams &e,
+                              int write_copy, double *diag, const float *clip, hipStream_t st) {
+    const dim3 grid(L.n_blocks), block(64);
+    if (diag) {
+        if (grad_dtype == 0) k_extrapolate<0, true><<<grid, block, 0, st>>>(L, g0, g1, e, write_copy, diag, clip);
+        else k_extrapolate<1, true><<<grid, block, 0, st>>>(L, g0, g1, e, write_copy, diag, clip);
+    } else {
+        if (grad_dtype == 0) k_extrapolate<0, false><<<grid, block, 0, st>>>(L, g0, g1, e, write_copy, nullptr, clip);
+        else k_extrapolate<1, false><<<grid, block, 0, st>>>(L, g0, g1, e, write_copy, nullptr, clip);
     }
-    return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+namespace {
+template <bool DIAG>
+hipError_t fused_launch(const Layout &L, int optimizer, int grad_dtype, const GradArg &g0, const GradArg &g1, const StepParams &p1,
+                        const StepParams &p2, const ExtrapParams &e, int write_copy, double *diag, const float *clip, hipStream_t st) {
+    const dim3 grid(L.n_blocks), block(64);
+    if (optimizer == 0 && grad_dtype == 0) k_fused_steps_extrapolate<0, 0, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag, clip);
+    else if (optimizer == 0) k_fused_steps_extrapolate<0, 1, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag, clip);
+    else if (grad_dtype == 0) k_fused_steps_extrapolate<1, 0, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag, clip);
+    else k_fused_steps_extrapolate<1, 1, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag, clip);
+    return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_fused_steps_extrapolate(const Layout &L, int optimizer, int grad_dtype, const GradArg &d_g0, const GradArg &d_g1,
+                                          const StepParams &p1, const StepParams &p2, const ExtrapParams &e, int write_copy,
+                                          double *d_diag_partial, const float *d_clip, hipStream_t stream) {
+    return d_diag_partial ? fused_launch<true>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, d_diag_partial, d_clip, stream)
+                          : fused_launch<false>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, nullptr, d_clip, stream);
+}
+
+hipError_t launch_sumsq(const Layout &L, int grad_dtype, const GradArg &g, double *partial, int acc, hipStream_t st) {
+    const dim3 grid((L.n_blocks + kSumsqGroup - 1) / kSumsqGroup), block(64);
+    if (grad_dtype == 0) k_sumsq<0><<<grid, block, 0, st>>>(L, g, partial, acc);
+    else k_sumsq<1><<<grid, block, 0, st>>>(L, g, partial, acc);
+    return hipGetLastError();
 }
 
 hipError_t launch_clip_coefficient(const double *d_result, uint32_t n_tensors, int acc, double max_norm, float *d_clip,
@@ -771,14 +692,8 @@ hipError_t launch_clip_coefficient(const double *d_result, uint32_t n_tensors, i
     return hipGetLastError();
 }
 
-hipError_t launch_reposition(const Layout &L, uint32_t wpb, float alpha, int write_copy, hipStream_t stream) {
-    const dim3 grid(L.n_blocks);
-    switch (wpb) {
-        case 1: k_reposition<1><<<grid, dim3(64), 0, stream>>>(L, alpha, write_copy); break;
-        case 2: k_reposition<2><<<grid, dim3(128), 0, stream>>>(L, alpha, write_copy); break;
-        case 4: k_reposition<4><<<grid, dim3(256), 0, stream>>>(L, alpha, write_copy); break;
-        default: return hipErrorInvalidValue;
-    }
+hipError_t launch_reposition(const Layout &L, float alpha, int write_copy, hipStream_t stream) {
+    k_reposition<<<dim3(L.n_blocks), dim3(64), 0, stream>>>(L, alpha, write_copy);
     return hipGetLastError();
 }
 

@@ -1,0 +1,315 @@
+"""Rank-aware placement of the engine's buffers in MI355X's HBM.
+
+What was measured on this part (profiles/hbm_rank_placement.md): the 288 GiB of
+HBM3E behave as three regions of 96 GiB of physical memory -- the three ranks of
+the 12-high stacks.  A pass that reads several streams at the same element
+offset runs ~4 % slower when one of its read streams lies in another rank than
+the rest (every switch between ranks on a channel costs bus time), while a
+stream that is only written is best kept in a rank the pass does not read.  A
+plain allocation of tens of GiB is backed by power-of-two physical blocks that
+land in whichever rank has room, so with parameter-sized buffers of 6-30 GiB
+the streams of a pass end up in different ranks by accident: that is the "large
+buffers lose 3 %" effect.
+
+This module is allocation plumbing that removes the accident.  It takes
+physical memory in chunks through HIP's virtual-memory API (hipMemCreate),
+finds out by timing which chunks share a rank (the engine's own fallback step
+is the probe: parameters and moments in a reference chunk, the gradient in the
+candidate), and then maps the chunks into one contiguous address range per
+buffer so that, slab by slab, the streams a pass reads together sit in the same
+rank and the write-only streams (theta_probe, the bf16 model copy) in another.
+Every buffer stays an ordinary contiguous device array; the engine sees plain
+pointers and knows nothing of this.
+"""
+from __future__ import annotations
+
+import ctypes
+from typing import Dict, List, Optional, Sequence
+
+import torch
+
+from . import binding as _B
+
+CHUNK_BYTES = 512 << 20
+SLAB_ELEMS = 1 << 28              # co-location unit: 2 chunks of an fp32 buffer, 1 chunk of a bf16 buffer
+_HIP_MEM_ALLOCATION_TYPE_PINNED = 1
+_HIP_MEM_LOCATION_TYPE_DEVICE = 1
+_HIP_MEM_ACCESS_READ_WRITE = 3
+
+
+class _Loc(ctypes.Structure):
+    _fields_ = [("type", ctypes.c_int), ("id", ctypes.c_int)]
+
+
+class _AllocFlags(ctypes.Structure):
+    _fields_ = [("compressionType", ctypes.c_ubyte), ("gpuDirectRDMACapable", ctypes.c_ubyte), ("usage", ctypes.c_ushort)]
+
+
+class _Prop(ctypes.Structure):
+    _fields_ = [("type", ctypes.c_int), ("requestedHandleType", ctypes.c_int), ("location", _Loc),
+                ("win32HandleMetaData", ctypes.c_void_p), ("allocFlags", _AllocFlags)]
+
+
+class _Access(ctypes.Structure):
+    _fields_ = [("location", _Loc), ("flags", ctypes.c_int)]
+
+
+class ArenaUnavailable(RuntimeError):
+    """The virtual-memory API is missing or refused a call; callers fall back to plain allocations."""
+
+
+_hip = None
+
+
+def _runtime():
+    global _hip
+    if _hip is None:
+        try:
+            _hip = ctypes.CDLL("libamdhip64.so")
+            _hip.hipGetErrorString.restype = ctypes.c_char_p
+            for name in ("hipMemCreate", "hipMemAddressReserve", "hipMemMap", "hipMemSetAccess", "hipMemUnmap", "hipMemRelease",
+                         "hipMemAddressFree"):
+                getattr(_hip, name)
+        except (OSError, AttributeError) as e:
+            raise ArenaUnavailable(f"HIP virtual-memory API not available: {e}")
+    return _hip
+
+
+def _ck(rc: int, what: str):
+    if rc != 0:
+        raise ArenaUnavailable(f"{what} failed: {_runtime().hipGetErrorString(rc).decode()} ({rc})")
+
+
+class _View:
+    """What torch wraps: a typed window of mapped device memory that keeps its arena alive."""
+
+    def __init__(self, arena, ptr: int, numel: int, typestr: str):
+        self._arena = arena
+        self.__cuda_array_interface__ = {"shape": (numel,), "typestr": typestr, "data": (ptr, False), "version": 3, "strides": None}
+
+
+_TYPESTR = {torch.float32: ("<f4", 4), torch.bfloat16: (None, 2), torch.uint8: ("|u1", 1), torch.int16: ("<i2", 2)}
+
+
+class RankedArena:
+    """Physical chunks of one GPU's HBM, labelled by rank, and the buffers mapped from them."""
+
+    def __init__(self, device: torch.device, n_chunks: int, chunk_bytes: int = CHUNK_BYTES):
+        hip = _runtime()
+        self.device = torch.device(device)
+        self.dev_index = self.device.index if self.device.index is not None else torch.cuda.current_device()
+        self.chunk_bytes = chunk_bytes
+        self.handles: List[Optional[ctypes.c_void_p]] = []
+        self.labels: List[int] = []
+        self._ranges = []                        # (va, bytes) reserved
+        self._mapped = []                        # (va, bytes) mapped, one per chunk
+        self._scan_va = None
+        self._closed = False
+        prop = _Prop()
+        prop.type = _HIP_MEM_ALLOCATION_TYPE_PINNED
+        prop.location = _Loc(_HIP_MEM_LOCATION_TYPE_DEVICE, self.dev_index)
+        self._access = _Access(_Loc(_HIP_MEM_LOCATION_TYPE_DEVICE, self.dev_index), _HIP_MEM_ACCESS_READ_WRITE)
+        try:
+            for _ in range(n_chunks):
+                h = ctypes.c_void_p()
+                _ck(hip.hipMemCreate(ctypes.byref(h), ctypes.c_size_t(chunk_bytes), ctypes.byref(prop), ctypes.c_ulonglong(0)), "hipMemCreate")
+                self.handles.append(h)
+        except ArenaUnavailable:
+            self.close()
+            raise
+
+    # ---- address ranges ------------------------------------------------------------------------
+    def _reserve(self, nbytes: int) -> int:
+        va = ctypes.c_void_p()
+        _ck(_runtime().hipMemAddressReserve(ctypes.byref(va), ctypes.c_size_t(nbytes), ctypes.c_size_t(2 << 20), None, ctypes.c_ulonglong(0)),
+            "hipMemAddressReserve")
+        self._ranges.append((va.value, nbytes))
+        return va.value
+
+    def _map(self, va: int, chunk: int):
+        hip = _runtime()
+        _ck(hip.hipMemMap(ctypes.c_void_p(va), ctypes.c_size_t(self.chunk_bytes), ctypes.c_size_t(0), self.handles[chunk], ctypes.c_ulonglong(0)), "hipMemMap")
+        self._mapped.append((va, self.chunk_bytes))
+        _ck(hip.hipMemSetAccess(ctypes.c_void_p(va), ctypes.c_size_t(self.chunk_bytes), ctypes.byref(self._access), ctypes.c_size_t(1)), "hipMemSetAccess")
+
+    def _unmap_all(self):
+        hip = _runtime()
+        for va, nbytes in self._mapped:
+            hip.hipMemUnmap(ctypes.c_void_p(va), ctypes.c_size_t(nbytes))
+        self._mapped = []
+        for va, nbytes in self._ranges:
+            hip.hipMemAddressFree(ctypes.c_void_p(va), ctypes.c_size_t(nbytes))
+        self._ranges = []
+
+    def _tensor(self, ptr: int, numel: int, dtype) -> torch.Tensor:
+        if dtype == torch.bfloat16:          # the array interface has no bf16: wrap as int16, reinterpret
+            return torch.as_tensor(_View(self, ptr, numel, "<i2"), device=self.device).view(torch.bfloat16)
+        return torch.as_tensor(_View(self, ptr, numel, _TYPESTR[dtype][0]), device=self.device)
+
+    # ---- which chunks share a rank ----------------------------------------------------------------
+    def classify(self, verbose: bool = False) -> List[int]:
+        """Labels every chunk with a class id such that chunks of one class behave as one rank: the
+        engine's fallback step (reads theta, m, v, g; writes theta, m, v) is timed with theta, m, v in a
+        reference chunk and g in each candidate; candidates in the reference's rank run measurably
+        faster.  Repeats with a new reference among the chunks still unlabelled."""
+        n = len(self.handles)
+        cb = self.chunk_bytes
+        va = self._reserve(n * cb)
+        for i in range(n):
+            self._map(va + i * cb, i)
+        E = cb // 16                                       # four fp32 windows per chunk
+        win = lambda chunk, k: self._tensor(va + chunk * cb + k * E * 4 + (32768 if k in (1, 2) else 0), E - 16384, torch.float32)
+        cfg = _B.make_config(K=2, lr=1e-9, weight_decay=0.0, delta=0.0)
+        labels = [-1] * n
+        next_label = 0
+        todo = list(range(n))
+        grads = {}
+
+        def measure(ctx, c, launches):
+            if c not in grads:
+                grads[c] = win(c, 3)
+                grads[c].normal_(std=0.05)
+            g = grads[c]
+            _B.gxpo_fallback_step(ctx, [g])
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(launches):
+                _B.gxpo_fallback_step(ctx, [g])
+            b.record()
+            b.synchronize()
+            return launches * 28.0 * g.numel() / a.elapsed_time(b) / 1e6
+
+        while todo and next_label < 6:
+            ref = todo[0]
+            th, m, v = win(ref, 0), win(ref, 1), win(ref, 2)
+            th.normal_(std=0.02)
+            m.zero_()
+            v.fill_(1e-4)
+            ctx = _B.gxpo_init(cfg, [dict(theta=th, m=m, v=v)])
+            st = _B.gxpo_get_state(ctx)
+            st.s_star = 0
+            _B.gxpo_set_state(ctx, st)
+            # disturbances only ever make a measurement slower, so the best of several counts
+            rate = {c: max(measure(ctx, c, 4), measure(ctx, c, 4)) for c in todo}
+            lo_c, hi_c = min(rate.values()), max(rate.values())
+            for _ in range(8):                              # two-means on a line
+                cut = (lo_c + hi_c) / 2
+                lows = [r for r in rate.values() if r <= cut]
+                highs = [r for r in rate.values() if r > cut]
+                if not lows or not highs:
+                    break
+                lo_c, hi_c = sum(lows) / len(lows), sum(highs) / len(highs)
+            if hi_c - lo_c > 0.025 * hi_c:
+                cut = (lo_c + hi_c) / 2
+                for c in todo:                              # the slow cluster's upper tail gets more chances
+                    tries = 0
+                    while lo_c + 0.5 * (cut - lo_c) < rate[c] <= cut and tries < 3:
+                        rate[c] = max(rate[c], measure(ctx, c, 8))
+                        tries += 1
+            else:
+                cut = float("-inf")                         # one cluster: everything shares the reference's rank
+            _B.gxpo_destroy(ctx)
+            same = [c for c in todo if rate[c] > cut or c == ref]
+            for c in same:
+                labels[c] = next_label
+            if verbose:
+                print(f"[hbm_arena] reference chunk {ref}: {len(same)} of {len(todo)} chunks share its rank "
+                      f"(cluster centres {lo_c:.0f} / {hi_c:.0f} GB/s)", flush=True)
+            todo = [c for c in todo if labels[c] < 0]
+            next_label += 1
+        for c in todo:                                      # more clusters than ranks can be: lump the rest together
+            labels[c] = next_label
+        grads.clear()
+        torch.cuda.synchronize(self.device)
+        self._unmap_all()
+        self.labels = labels
+        return labels
+
+    # ---- buffers ---------------------------------------------------------------------------------------
+    def build(self, specs: Sequence[dict]) -> Dict[str, torch.Tensor]:
+        """specs: dicts with name, numel, dtype, phase_bytes, group ('read' or 'write').  All buffers
+        index the same elements.  Slab by slab, the chunks of every 'read' buffer come from one rank;
+        'write' buffers take theirs from another rank where there is room.  Returns name -> tensor."""
+        if not self.labels:
+            raise ArenaUnavailable("classify() has not run")
+        cb = self.chunk_bytes
+        free: Dict[int, List[int]] = {}
+        for i, lab in enumerate(self.labels):
+            if self.handles[i] is not None:
+                free.setdefault(lab, []).append(i)
+        for lst in free.values():
+            lst.reverse()                                  # pop() hands chunks out in creation order
+        esize = lambda s: torch.empty((), dtype=s["dtype"]).element_size()
+        per_slab = {s["name"]: SLAB_ELEMS * esize(s) // cb for s in specs}
+        need_chunks = {s["name"]: -(-(s["numel"] * esize(s) + s.get("phase_bytes", 0)) // cb) for s in specs}
+        n_slabs = max(-(-need_chunks[s["name"]] // per_slab[s["name"]]) for s in specs)
+        plan = {s["name"]: [] for s in specs}               # chunk ids in address order
+        wants = lambda s, slab: max(0, min(per_slab[s["name"]], need_chunks[s["name"]] - slab * per_slab[s["name"]]))
+
+        def take(label_order, count):
+            out = []
+            for lab in label_order:
+                while free.get(lab) and len(out) < count:
+                    out.append(free[lab].pop())
+                if len(out) == count:
+                    break
+            if len(out) < count:
+                raise ArenaUnavailable("not enough chunks for the requested buffers")
+            return out
+
+        room = lambda: sorted(free, key=lambda lab: -len(free[lab]))
+        # first the streams that are read together: one rank per slab, staying in a rank while it has room
+        self.slab_rank, current = [], None
+        for slab in range(n_slabs):
+            read_need = sum(wants(s, slab) for s in specs if s["group"] == "read")
+            if current is None or len(free.get(current, [])) < read_need:
+                fits = [lab for lab in room() if len(free[lab]) >= read_need]
+                current = fits[0] if fits else room()[0]
+            self.slab_rank.append(current)
+            order = [current] + [lab for lab in room() if lab != current]
+            for s in specs:
+                if s["group"] == "read" and wants(s, slab):
+                    plan[s["name"]] += take(order, wants(s, slab))
+        # then the write-only streams, from what is left, away from the rank their slab is read from
+        for slab in range(n_slabs):
+            order = [lab for lab in room() if lab != self.slab_rank[slab]] + [self.slab_rank[slab]]
+            for s in specs:
+                if s["group"] != "read" and wants(s, slab):
+                    plan[s["name"]] += take(order, wants(s, slab))
+        out = {}
+        for s in specs:
+            chunks = plan[s["name"]]
+            assert len(chunks) == need_chunks[s["name"]]
+            va = self._reserve(len(chunks) * cb)
+            for k, c in enumerate(chunks):
+                self._map(va + k * cb, c)
+            out[s["name"]] = self._tensor(va + s.get("phase_bytes", 0), s["numel"], s["dtype"])
+        used = {c for chunks in plan.values() for c in chunks}
+        hip = _runtime()
+        for i, h in enumerate(self.handles):               # give back what the buffers did not need
+            if i not in used and h is not None:
+                hip.hipMemRelease(h)
+                self.handles[i] = None
+        self.plan = plan
+        return out
+
+    def close(self):
+        if self._closed:
+            return
+        self._closed = True
+        try:
+            torch.cuda.synchronize(self.device)
+        except Exception:
+            pass
+        self._unmap_all()
+        hip = _runtime()
+        for i, h in enumerate(self.handles):
+            if h is not None:
+                hip.hipMemRelease(h)
+                self.handles[i] = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

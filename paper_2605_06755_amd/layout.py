@@ -15,9 +15,12 @@ plumbing for callers that want the fast layout.
 """
 from __future__ import annotations
 
+import sys
+
 import torch
 
 from . import binding as _B
+from .hbm_arena import CHUNK_BYTES, ArenaUnavailable, RankedArena
 
 # the library is the one place that states the placement
 MOMENT_PHASE_BYTES, PHASE_PERIOD_BYTES = _B.gxpo_layout_hint(_B.GXPO_BUF_M)
@@ -39,14 +42,44 @@ def alloc_phased(numel: int, dtype, device, phase_bytes: int = 0, fill=None) -> 
     return out
 
 
+RANKED_MIN_BYTES = 8 << 30          # below this everything lands in one rank anyway
+_last_placement = {"kind": None, "detail": None}
+
+
+def last_placement() -> dict:
+    """{'kind': 'ranked' | 'phased' | 'arena', 'detail': ...} of the most recent alloc_engine_state call."""
+    return dict(_last_placement)
+
+
 def alloc_engine_state(numel: int, device, *, adam: bool = True, model_copy: bool = False, grad_dtype=torch.float32,
-                       n_grad_buffers: int = 3, arena: bool = False, phases_kib=None):
+                       n_grad_buffers: int = 3, arena: bool = False, phases_kib=None, placement: str = "auto",
+                       with_probe: bool = True, verbose: bool = False):
     """Flat buffers for one engine context in the fast layout: a dict with
     theta, theta_probe, (m, v), (model_copy) and a list of gradient buffers.
-    `phases_kib` overrides the placement for experiments: a dict name -> KiB
+
+    placement: "ranked" = rank-aware placement through HIP's virtual-memory API
+    (hbm_arena.py); "phased" = one plain allocation per buffer with the 64 KiB
+    phase rule only; "auto" = ranked for workloads of 8 GiB and more where the
+    API is available, phased otherwise.  `last_placement()` tells which one
+    the most recent call used.
+    `phases_kib` overrides the phases for experiments: a dict name -> KiB
     (names theta, theta_probe, m, v, model_copy, g0, g1, g2)."""
     if arena:
+        _last_placement.update(kind="arena", detail=None)
         return _alloc_arena(numel, device, adam, model_copy, grad_dtype, n_grad_buffers)
+    _last_placement.update(kind="phased", detail=None)
+    if placement not in ("auto", "ranked", "phased"):
+        raise ValueError(placement)
+    if placement != "phased":
+        gs = torch.empty((), dtype=grad_dtype).element_size()
+        total = numel * (4 * (1 + int(with_probe) + 2 * int(adam)) + 2 * int(model_copy) + gs * n_grad_buffers)
+        if placement == "ranked" or total >= RANKED_MIN_BYTES:
+            try:
+                return _alloc_ranked(numel, device, adam, model_copy, grad_dtype, n_grad_buffers, phases_kib, with_probe, verbose)
+            except ArenaUnavailable as e:
+                if placement == "ranked":
+                    raise
+                print(f"[layout] rank-aware placement not available ({e}); using plain phased allocations", file=sys.stderr)
     ph = {"theta": 0, "theta_probe": 0, "m": MOMENT_PHASE_BYTES // 1024, "v": MOMENT_PHASE_BYTES // 1024, "model_copy": 0}
     ph.update(phases_kib or {})
     out = {"theta": alloc_phased(numel, torch.float32, device, ph["theta"] * 1024),
@@ -57,6 +90,51 @@ def alloc_engine_state(numel: int, device, *, adam: bool = True, model_copy: boo
     if model_copy:
         out["model_copy"] = alloc_phased(numel, torch.bfloat16, device, ph["model_copy"] * 1024)
     grads = [alloc_phased(numel, grad_dtype, device, ph.get(f"g{i}", 0) * 1024) for i in range(n_grad_buffers)]
+    if not with_probe:
+        del out["theta_probe"]
+    return out, grads
+
+
+def _alloc_ranked(numel, device, adam, model_copy, grad_dtype, n_grad_buffers, phases_kib, with_probe, verbose):
+    """All buffers from one RankedArena: slab by slab, theta, m, v and the gradients share a rank;
+    theta_probe and the bf16 copy (only ever written by the engine) come from another."""
+    ph = {"theta": 0, "theta_probe": 0, "m": MOMENT_PHASE_BYTES // 1024, "v": MOMENT_PHASE_BYTES // 1024, "model_copy": 0}
+    ph.update(phases_kib or {})
+    specs = [dict(name="theta", numel=numel, dtype=torch.float32, group="read", phase_bytes=ph["theta"] * 1024)]
+    if adam:
+        specs += [dict(name=k, numel=numel, dtype=torch.float32, group="read", phase_bytes=ph[k] * 1024) for k in ("m", "v")]
+    specs += [dict(name=f"g{i}", numel=numel, dtype=grad_dtype, group="read", phase_bytes=ph.get(f"g{i}", 0) * 1024)
+              for i in range(n_grad_buffers)]
+    if with_probe:
+        specs.append(dict(name="theta_probe", numel=numel, dtype=torch.float32, group="write", phase_bytes=ph["theta_probe"] * 1024))
+    if model_copy:
+        specs.append(dict(name="model_copy", numel=numel, dtype=torch.bfloat16, group="write", phase_bytes=ph["model_copy"] * 1024))
+    cb = CHUNK_BYTES
+    need = sum(-(-(s["numel"] * torch.empty((), dtype=s["dtype"]).element_size() + s["phase_bytes"]) // cb) for s in specs)
+    torch.cuda.empty_cache()
+    free, _ = torch.cuda.mem_get_info(device)
+    # spare chunks give the placement a choice of ranks; leave room for the caller's temporaries
+    budget = (free - (12 << 30)) // cb
+    if budget < need:
+        raise ArenaUnavailable(f"{need} chunks needed, room for {budget}")
+    n_chunks = int(min(budget, need + max(24, need // 3)))
+    ar = RankedArena(device, n_chunks)
+    try:
+        labels = ar.classify(verbose=verbose)
+        bufs = ar.build(specs)
+    except Exception:
+        ar.close()
+        raise
+    if verbose:
+        counts = {lab: labels.count(lab) for lab in sorted(set(labels))}
+        print(f"[layout] {n_chunks} chunks of {cb >> 20} MiB in ranks {counts}; read streams per slab in ranks {ar.slab_rank}", file=sys.stderr)
+    counts = {lab: labels.count(lab) for lab in sorted(set(labels))}
+    _last_placement.update(kind="ranked", detail={"chunk_mib": cb >> 20, "chunks_per_rank": counts, "slab_rank": list(ar.slab_rank)})
+    out = {k: bufs[k] for k in ("theta", "theta_probe", "m", "v", "model_copy") if k in bufs}
+    if adam:
+        out["m"].zero_()
+        out["v"].zero_()
+    grads = [bufs[f"g{i}"] for i in range(n_grad_buffers)]
     return out, grads
 
 

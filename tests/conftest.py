@@ -7,12 +7,50 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+_library_state = {"tried": False, "error": None}
+
+
+def _needs_library(path) -> bool:
+    """Does this test module load libgxpo.so (through the binding or the plain-C driver)?"""
+    try:
+        text = path.read_text()
+    except OSError:
+        return False
+    return "import binding" in text or "gxpo_harness" in text or "abi_driver" in text
+
+
+def _library_error():
+    """Build libgxpo.so if it is missing or older than its sources -- once, and only when a module that needs
+    it is about to be collected, so the oracle's own tests run where there is no hipcc."""
+    if not _library_state["tried"]:
+        _library_state["tried"] = True
+        try:
+            from paper_2605_06755_amd import build as lib_build
+            lib_build.ensure_built()
+        except Exception as e:      # no hipcc, or the build failed: report it, keep the CPU-only oracle tests running
+            _library_state["error"] = f"{type(e).__name__}: {e}"
+    return _library_state["error"]
+
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run through the GPU box)")
-    # the tests load what is built; they build only if nothing is there
-    from paper_2605_06755_amd import build as lib_build
-    lib_build.ensure_built()
+
+
+class LibraryModule(pytest.Module):
+    """A test module that loads libgxpo.so: the library is built (if need be) when the module is really
+    collected, not when its directory is listed, and the module is skipped where it cannot be built."""
+
+    def collect(self):
+        err = _library_error()
+        if err:
+            pytest.skip(f"libgxpo.so is not available ({err.splitlines()[0]})", allow_module_level=True)
+        return super().collect()
+
+
+def pytest_pycollect_makemodule(module_path, parent):
+    if module_path.name.startswith("test_") and _needs_library(module_path):
+        return LibraryModule.from_parent(parent, path=module_path)
+    return None
 
 
 @pytest.fixture(scope="session")

@@ -77,14 +77,13 @@ def test_surrogate_config1_lockstep_and_closed_form(fused, alpha):
 # ---------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("fused", [True, False])
 @pytest.mark.parametrize("grad_dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("wpb", [0, 4])
-def test_adamw_ragged_lockstep(fused, grad_dtype, wpb):
+def test_adamw_ragged_lockstep(fused, grad_dtype):
     numels = RAGGED
     P = sum(numels)
     problem = synth.policy_problem(P, seed=1, sigma=0.05, device="cuda")
     cfg = B.make_config(optimizer="adamw", grad_dtype=grad_dtype, K=8, alpha=0.5, delta=1.75e-3, lr=1e-6,
                         weight_decay=0.01, fuse_step2=fused, tau=3.0, window=10, gate_min_count=2,
-                        waves_per_block=wpb, copy_mask=7)
+                        copy_mask=7)
     dev, ctx, orc, grads = build(numels, cfg, problem, with_copy=True)
     step_id = [0]
     noise = lambda: synth.step_noise(problem, step_id[0])
@@ -272,12 +271,11 @@ def test_broad_retention_spread_with_clamp(K):
 # ---------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("fused", [True, False])
 @pytest.mark.parametrize("grad_dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("wpb", [0, 4])
-def test_mechanism_diagnostics_policy_like(fused, grad_dtype, wpb):
+def test_mechanism_diagnostics_policy_like(fused, grad_dtype):
     numels = RAGGED
     problem = synth.policy_problem(sum(numels), seed=21, sigma=0.05, device="cuda")
     cfg = B.make_config(grad_dtype=grad_dtype, K=5, alpha=0.5, delta=1.75e-3, lr=1e-4, fuse_step2=fused, gate_min_count=2,
-                        waves_per_block=wpb, diagnostics=True)
+                        diagnostics=True)
     dev, ctx, orc, grads = build(numels, cfg, problem)
     step_id = [0]
     grad_fn = quad_trainer(problem, numels, step_noise=lambda: synth.step_noise(problem, step_id[0]))
@@ -867,7 +865,7 @@ def test_hyper_parameter_schedule_through_update_config():
     st = B.gxpo_get_state(ctx)
     assert st.window_len == 2 and list(st.window[:2]) == orc.gate.buffer
     # what shapes the workspace cannot change; nothing changes in the middle of a step
-    for bad in (dict(optimizer="gd"), dict(grad_dtype="bf16"), dict(fuse_step2=False), dict(waves_per_block=4),
+    for bad in (dict(optimizer="gd"), dict(grad_dtype="bf16"), dict(fuse_step2=False),
                 dict(diagnostics=1), dict(explicit_steps=3), dict(clip_norm=1.0)):
         with pytest.raises(B.GxpoError) as e:
             B.gxpo_update_config(ctx, B.make_config(**{**base, **schedule[0], **bad}))
@@ -1040,3 +1038,141 @@ def test_stream_copy_reference_kernel():
         B.gxpo_stream_copy(dst[:n], src)
         torch.cuda.synchronize()
         assert torch.equal(dst[:n], src) and bool((dst[n:] == 7.0).all())
+
+
+# ---------------------------------------------------------------------------------------------
+# the fused schedule's replay: theta^{t,1}, m, v bit for bit what the unfused passes store
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("optimizer", ["adamw", "gd"])
+@pytest.mark.parametrize("grad_dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("clip_norm", [0.0, 5.0])
+def test_fused_replay_is_bit_identical_to_the_unfused_passes(optimizer, grad_dtype, clip_norm):
+    """Same inputs through fuse_step2 = 1 and = 0, three steps.  What the header promises bit for bit:
+    theta^{t,1} as the probe pass previews it equals what the unfused first fast step stores, and m, v after
+    gxpo_extrapolate (fused: both moment updates applied in the replay) equal m, v after the unfused second
+    fast step.  theta~ is NOT promised bit-equal: the unfused path rounds theta^{t,2} to fp32 before the
+    displacement is formed, the fused pass forms (theta^{t,1} - theta^t) - update_2 without that rounding;
+    the two may differ by that one rounding times alpha * scale, which is what is asserted."""
+    numels = RAGGED
+    P = sum(numels)
+    problem = synth.policy_problem(P, seed=31, sigma=0.05, device="cuda")
+    common = dict(optimizer=optimizer, grad_dtype=grad_dtype, K=5, alpha=0.5, delta=1.75e-3, lr=1e-3 if optimizer == "gd" else 1e-4,
+                  weight_decay=0.01, gate_min_count=2, clip_norm=clip_norm, copy_mask=7, r_max=4.0)
+    runs = {}
+    for fused in (True, False):
+        cfg = B.make_config(fuse_step2=fused, **common)
+        dev, ctx, orc, grads = build(numels, cfg, problem, with_copy=True)
+        runs[fused] = (dev, ctx, orc, grads)
+    grad_fn = quad_trainer(problem, numels, step_noise=lambda: synth.step_noise(problem, step_id[0]))
+    step_id = [0]
+    adam = optimizer == "adamw"
+    bits = lambda dev, key: [x.clone() for x in dev.views[key]]
+    raw = lambda x: x.view(torch.int32) if x.element_size() == 4 else x.view(torch.int16)
+    same = lambda a, b: all(torch.equal(raw(x), raw(y)) for x, y in zip(a, b))
+    for step in range(3):
+        step_id[0] = step
+        snap = {}
+        for k in runs[False][0].views:                       # both schedules start every step from the same state
+            for dst, src in zip(runs[False][0].views[k], runs[True][0].views[k]):
+                dst.copy_(src)
+        for fused in (True, False):
+            dev, ctx, orc, (g0b, g1b, gsb) = runs[fused]
+            st = B.gxpo_get_state(ctx)
+            H.sync_oracle_to_device(orc, dev, st.optim_steps)
+            grad_fn(dev.views["theta"], g0b)
+            B.gxpo_fast_steps(ctx, 0, g0b)
+            snap[fused, "th1"] = bits(dev, "theta_probe")
+            snap[fused, "copy1"] = bits(dev, "model_copy")
+            orc.fast_step_1([H.f64(g) for g in g0b])
+            grad_fn(dev.views["theta_probe"], g1b)
+            B.gxpo_fast_steps(ctx, 1, g1b)
+            orc.fast_step_2([H.f64(g) for g in g1b])
+            snap[fused, "theta_before"] = bits(dev, "theta")
+            B.gxpo_extrapolate(ctx, g0b, g1b)
+            orc.extrapolate([H.f64(g) for g in g0b], [H.f64(g) for g in g1b])
+            snap[fused, "tilde"] = bits(dev, "theta")
+            if adam:
+                snap[fused, "m"], snap[fused, "v"] = bits(dev, "m"), bits(dev, "v")
+            snap[fused, "scale"] = [s.copy() for s in orc.scale]
+            snap[fused, "th2"] = [t.copy() for t in orc._theta_2]
+            snap[fused, "g"] = [g.clone() for g in g0b + g1b]
+        # identical inputs went in
+        assert same(snap[True, "g"], snap[False, "g"]) and same(snap[True, "theta_before"], snap[False, "theta_before"])
+        # the promise
+        assert same(snap[True, "th1"], snap[False, "th1"]), f"step {step}: previewed theta^(t,1) differs from the stored one"
+        assert all(torch.equal(a.view(torch.int16), b.view(torch.int16)) for a, b in zip(snap[True, "copy1"], snap[False, "copy1"]))
+        if adam:
+            assert same(snap[True, "m"], snap[False, "m"]), f"step {step}: m after the replay differs"
+            assert same(snap[True, "v"], snap[False, "v"]), f"step {step}: v after the replay differs"
+        # theta~: one fp32 rounding of theta^{t,2}, multiplied by alpha * scale
+        for a, b, sc, th0, th2 in zip(snap[True, "tilde"], snap[False, "tilde"], snap[True, "scale"], snap[True, "theta_before"],
+                                      snap[True, "th2"]):
+            a64, b64 = H.f64(a), H.f64(b)
+            mag = np.maximum(np.maximum(np.abs(b64), np.abs(H.f64(th0))), np.abs(th2))      # the iterates' magnitude sets the ulp
+            bound = 2.0 ** -23 * mag * (1.0 + common["alpha"] * np.abs(sc))
+            assert np.all(np.abs(a64 - b64) <= bound), f"step {step}: theta~ differs by more than the rounding of theta^(t,2)"
+        # finish the step on both (slow step from each schedule's own theta~)
+        for fused in (True, False):
+            dev, ctx, orc, (g0b, g1b, gsb) = runs[fused]
+            grad_fn(dev.views["theta"], gsb)
+            B.gxpo_slow_step(ctx, gsb)
+            B.gxpo_gate(ctx)
+    for fused in (True, False):
+        B.gxpo_destroy(runs[fused][1])
+
+
+# ---------------------------------------------------------------------------------------------
+# a NULL entry in a gradient list is refused on the host, whatever has been staged before
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("fused", [True, False])
+@pytest.mark.parametrize("n_tensors", [1, 3])
+def test_null_gradient_entry_is_refused_before_any_launch(fused, n_tensors):
+    import ctypes
+    numels = [4099, 1000, 257][:n_tensors]
+    problem = synth.policy_problem(sum(numels), seed=41, sigma=0.05, device="cuda")
+    cfg = B.make_config(K=5, alpha=0.5, delta=1.75e-3, lr=1e-4, fuse_step2=fused, gate_min_count=2)
+    dev, ctx, orc, (g0b, g1b, gsb) = build(numels, cfg, problem)
+    for g in g0b + g1b + gsb:
+        g.normal_(std=0.05)
+    stream = B._stream_ptr(None)
+
+    def ptrs(bufs, null_at=None):
+        return (ctypes.c_void_p * n_tensors)(*[None if i == null_at else b.data_ptr() for i, b in enumerate(bufs)])
+
+    def state_bits():
+        torch.cuda.synchronize()
+        return {k: torch.cat([x.view(torch.int32).reshape(-1) for x in v]).clone() for k, v in dev.views.items()}
+
+    def refused(call, label):
+        before, phase = state_bits(), B.gxpo_get_state(ctx).phase
+        rc = call()
+        assert rc == B.GXPO_ERR_INVALID_ARG, f"{label}: rc {rc}"
+        assert "NULL" in B.gxpo_last_error(ctx) or "differs" in B.gxpo_last_error(ctx), B.gxpo_last_error(ctx)
+        after = state_bits()
+        assert B.gxpo_get_state(ctx).phase == phase, f"{label}: the state machine moved"
+        assert all(torch.equal(before[k], after[k]) for k in before), f"{label}: a buffer was written"
+
+    last = n_tensors - 1
+    # first use of every role, with nothing staged yet
+    refused(lambda: B._lib.gxpo_fast_steps(ctx.handle, 0, ptrs(g0b, null_at=last), stream), "g0, first use")
+    B.gxpo_fast_steps(ctx, 0, g0b)
+    refused(lambda: B._lib.gxpo_fast_steps(ctx.handle, 1, ptrs(g1b, null_at=0), stream), "g1, first use")
+    B.gxpo_fast_steps(ctx, 1, g1b)
+    refused(lambda: B._lib.gxpo_extrapolate(ctx.handle, ptrs(g0b, null_at=last), ptrs(g1b), stream), "extrapolate g0")
+    refused(lambda: B._lib.gxpo_extrapolate(ctx.handle, ptrs(g0b), ptrs(g1b, null_at=0), stream), "extrapolate g1")
+    B.gxpo_extrapolate(ctx, g0b, g1b)
+    refused(lambda: B._lib.gxpo_slow_step(ctx.handle, ptrs(gsb, null_at=last), stream), "g_slow, first use")
+    B.gxpo_slow_step(ctx, gsb)
+    B.gxpo_gate(ctx)
+    # and again once every role has valid pointers staged
+    refused(lambda: B._lib.gxpo_fast_steps(ctx.handle, 0, ptrs(g0b, null_at=0), stream), "g0, second step")
+    B.gxpo_destroy(ctx)
+    # the fallback step's gradient on a context that has staged nothing
+    dev, ctx, orc, (g0b, g1b, gsb) = build(numels, cfg, problem)
+    st = B.gxpo_get_state(ctx)
+    st.s_star = 0
+    B.gxpo_set_state(ctx, st)
+    refused(lambda: B._lib.gxpo_fallback_step(ctx.handle, ptrs(g0b, null_at=last), stream), "fallback, first use")
+    B.gxpo_fallback_step(ctx, g0b)
+    torch.cuda.synchronize()
+    B.gxpo_destroy(ctx)

@@ -87,7 +87,6 @@ def test_default_config_is_valid():
     (dict(gate_eps=0.0), B.GXPO_ERR_INVALID_ARG),
     (dict(beta1=1.0), B.GXPO_ERR_INVALID_ARG),
     (dict(beta2=-0.1), B.GXPO_ERR_INVALID_ARG),
-    (dict(waves_per_block=3), B.GXPO_ERR_INVALID_ARG),
     (dict(copy_mask=8), B.GXPO_ERR_INVALID_ARG),
     (dict(diagnostics=2), B.GXPO_ERR_INVALID_ARG),
     (dict(explicit_steps=1), B.GXPO_ERR_INVALID_ARG),
@@ -152,12 +151,11 @@ def test_layout_hint():
 
 
 # ---- block plan ---------------------------------------------------------------------------------
-@pytest.mark.parametrize("wpb", [0, 1, 2, 4])
-def test_block_plan_covers_every_element_exactly_once(wpb):
+def test_block_plan_covers_every_element_exactly_once():
     rng = np.random.default_rng(0)
     numels = [1, 255, 256, 257, 4096, 1023, 5, 100000] + [int(x) for x in rng.integers(1, 50000, size=40)]
-    start, epb = B.gxpo_plan_blocks(numels, wpb)
-    assert epb == 256 * (wpb or 1)
+    start, epb = B.gxpo_plan_blocks(numels)
+    assert epb == 256
     assert start[0] == 0 and len(start) == len(numels) + 1
     for t, n in enumerate(numels):
         nb = start[t + 1] - start[t]
