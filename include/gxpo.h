@@ -279,6 +279,33 @@ typedef struct gxpo_tensor_options {
 } gxpo_tensor_options;
 int gxpo_set_tensor_options(gxpo_ctx *ctx, const gxpo_tensor_options *opts);
 
+/* ---- for callers that cannot allocate ------------------------------------------------- */
+
+/* gxpo_slow_step() without a context, for callers that cannot call hipMalloc:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * allocation.  One flat tensor:
+ *     theta <- OptimStep(theta, g_slow) taken as optimizer step number `optim_step`
+ *     (1-based: the value gxpo_state.optim_steps would have after the step),
+ *     *sum_sq_out_device <- sum of squares of g_slow, fp64, fixed order
+ * with the same kernels and the same order of additions as gxpo_slow_step() on a
+ * one-tensor context, so theta, m, v and the sum are bit-identical to that call's.
+ * The per-block partial sums live in a device array that is part of the library
+ * image (8 MiB per GPU, held until the process ends) instead of a workspace from
+ * gxpo_init(): nothing is allocated or freed, here or inside.  Limits: numel <=
+ * GXPO_NOALLOC_MAX_NUMEL (GXPO_ERR_INVALID_ARG beyond), clip_norm == 0 and
+ * diagnostics == 0 (GXPO_ERR_UNSUPPORTED otherwise).  `cfg` and `tensor` are host
+ * pointers (theta_probe is ignored; model_copy is written if copy_mask has
+ * GXPO_COPY_AT_FINAL); g_slow and sum_sq_out_device (one double, 8-byte aligned)
+ * are device pointers; pointers are checked like everywhere else.  All calls on
+ * one GPU share the one array: calls that may overlap in time on a GPU (different
+ * streams, different threads) race on it -- keep them on one stream or order
+ * them.  The caller reads the sum after the stream has reached this point and
+ * runs the gate with gxpo_host_gate_step(cfg, state, sqrt(sum)).
+ * Errors are reported through gxpo_last_error(NULL). */
+#define GXPO_NOALLOC_MAX_NUMEL ((uint64_t)268435456)        /* 2^20 blocks of 256 elements */
+int gxpo_slow_step_noalloc(const gxpo_config *cfg, const gxpo_tensor *tensor, int64_t optim_step,
+                           const void *g_slow, double *sum_sq_out_device, void *stream);
+
 /* Message of the last failure on `ctx`, or of the last failed gxpo_init on
  * this thread when ctx is NULL.  Never NULL; valid until the next call. */
 const char *gxpo_last_error(const gxpo_ctx *ctx);

@@ -45,7 +45,7 @@ EXPORTED_SYMBOLS = [
     "gxpo_init", "gxpo_destroy", "gxpo_fast_steps", "gxpo_extrapolate", "gxpo_slow_step", "gxpo_gate",
     "gxpo_fallback_step", "gxpo_tensor_norms", "gxpo_get_diagnostics", "gxpo_get_state", "gxpo_set_state", "gxpo_last_error",
     "gxpo_validate_config", "gxpo_host_gate_step", "gxpo_plan_blocks", "gxpo_stream_copy", "gxpo_update_config",
-    "gxpo_set_tensor_options", "gxpo_layout_hint",
+    "gxpo_set_tensor_options", "gxpo_layout_hint", "gxpo_slow_step_noalloc",
 ]
 
 
@@ -131,6 +131,10 @@ _lib.gxpo_plan_blocks.argtypes = [ctypes.POINTER(ctypes.c_uint64), ctypes.c_uint
                                   ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_uint32)]
 _lib.gxpo_layout_hint.restype = ctypes.c_int
 _lib.gxpo_layout_hint.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64)]
+_lib.gxpo_slow_step_noalloc.restype = ctypes.c_int
+_lib.gxpo_slow_step_noalloc.argtypes = [ctypes.POINTER(gxpo_config), ctypes.POINTER(gxpo_tensor), ctypes.c_int64, ctypes.c_void_p,
+                                        ctypes.c_void_p, ctypes.c_void_p]
+GXPO_NOALLOC_MAX_NUMEL = 1 << 28
 _lib.gxpo_stream_copy.restype = ctypes.c_int
 _lib.gxpo_stream_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p]
 
@@ -356,6 +360,23 @@ def gxpo_layout_hint(buffer_kind: int):
     if rc != GXPO_OK:
         raise GxpoError(rc, "gxpo_layout_hint rejected its arguments")
     return phase.value, period.value
+
+
+def gxpo_slow_step_noalloc(cfg: gxpo_config, tensor: dict, optim_step: int, g_slow: torch.Tensor, sum_sq_out: torch.Tensor,
+                           stream=None) -> None:
+    """tensor: dict with theta and optionally m, v, model_copy (torch tensors); sum_sq_out: one float64 on the device."""
+    numel = tensor["theta"].numel()
+    rec = gxpo_tensor()
+    rec.numel = numel
+    rec.theta = _dev_ptr(tensor["theta"], torch.float32, numel)
+    rec.m = _dev_ptr(tensor.get("m"), torch.float32, numel)
+    rec.v = _dev_ptr(tensor.get("v"), torch.float32, numel)
+    rec.model_copy = _dev_ptr(tensor.get("model_copy"), torch.bfloat16, numel)
+    gdt = torch.float32 if cfg.grad_dtype == GXPO_GRAD_F32 else torch.bfloat16
+    rc = _lib.gxpo_slow_step_noalloc(ctypes.byref(cfg), ctypes.byref(rec), int(optim_step), _dev_ptr(g_slow, gdt, numel),
+                                     _dev_ptr(sum_sq_out, torch.float64, 1), _stream_ptr(stream))
+    if rc != GXPO_OK:
+        raise GxpoError(rc, _lib.gxpo_last_error(None).decode())
 
 
 def gxpo_stream_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

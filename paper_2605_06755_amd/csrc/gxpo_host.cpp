@@ -802,6 +802,58 @@ int gxpo_set_tensor_options(gxpo_ctx *ctx, const gxpo_tensor_options *opts) {
     return GXPO_OK;
 }
 
+int gxpo_slow_step_noalloc(const gxpo_config *cfg, const gxpo_tensor *tensor, int64_t optim_step, const void *g_slow,
+                           double *sum_sq_out_device, void *stream) {
+    std::string msg;
+    int rc = check_config(cfg, msg);
+    if (rc != GXPO_OK) return fail(nullptr, rc, "gxpo_slow_step_noalloc: %s", msg.c_str());
+    if (cfg->clip_norm > 0.0 || cfg->diagnostics)
+        return fail(nullptr, GXPO_ERR_UNSUPPORTED, "gxpo_slow_step_noalloc: clipping and diagnostics need the workspace of a context");
+    if (!tensor || !g_slow || !sum_sq_out_device) return fail(nullptr, GXPO_ERR_INVALID_ARG, "gxpo_slow_step_noalloc: NULL argument");
+    if (optim_step < 1) return fail(nullptr, GXPO_ERR_INVALID_ARG, "gxpo_slow_step_noalloc: optim_step must be >= 1");
+    const gxpo_tensor &x = *tensor;
+    const bool adam = cfg->optimizer == GXPO_OPT_ADAMW;
+    if (x.numel == 0) return fail(nullptr, GXPO_ERR_INVALID_ARG, "gxpo_slow_step_noalloc: numel is 0");
+    if (x.numel > GXPO_NOALLOC_MAX_NUMEL)
+        return fail(nullptr, GXPO_ERR_INVALID_ARG, "gxpo_slow_step_noalloc: numel %llu exceeds the built-in workspace (at most %llu elements); use a context",
+                    (unsigned long long)x.numel, (unsigned long long)GXPO_NOALLOC_MAX_NUMEL);
+    if (!x.theta) return fail(nullptr, GXPO_ERR_INVALID_ARG, "gxpo_slow_step_noalloc: theta is NULL");
+    if (adam && (!x.m || !x.v)) return fail(nullptr, GXPO_ERR_INVALID_ARG, "gxpo_slow_step_noalloc: AdamW needs m and v");
+    if (!adam && (x.m || x.v)) return fail(nullptr, GXPO_ERR_INVALID_ARG, "gxpo_slow_step_noalloc: m and v must be NULL for plain GD");
+    const bool wc = (cfg->copy_mask & GXPO_COPY_AT_FINAL) && x.model_copy;
+    const uint64_t gbytes = cfg->grad_dtype == GXPO_GRAD_F32 ? 4u : 2u;
+    // every buffer the kernels touch: alignment, device range, and no overlap between any two
+    struct Buf { const void *p; uint64_t bytes; uintptr_t align; const char *what; };
+    const Buf bufs[6] = {{x.theta, x.numel * 4, 16, "theta"},
+                         {x.m, x.numel * 4, 16, "m"},
+                         {x.v, x.numel * 4, 16, "v"},
+                         {wc ? x.model_copy : nullptr, x.numel * 2, 8, "model_copy"},
+                         {g_slow, x.numel * gbytes, cfg->grad_dtype == GXPO_GRAD_F32 ? (uintptr_t)16 : (uintptr_t)8, "g_slow"},
+                         {sum_sq_out_device, 8, 8, "sum_sq_out"}};
+    for (const Buf &b : bufs) {
+        if (!b.p) continue;
+        if ((uintptr_t)b.p % b.align) return fail(nullptr, GXPO_ERR_ALIGNMENT, "gxpo_slow_step_noalloc: %s is not %u-byte aligned", b.what, (unsigned)b.align);
+        rc = check_device_range(nullptr, b.p, b.bytes, b.what, 0);
+        if (rc != GXPO_OK) return rc;
+    }
+    for (int i = 0; i < 6; ++i)
+        for (int j = i + 1; j < 6; ++j) {
+            if (!bufs[i].p || !bufs[j].p) continue;
+            const uintptr_t a = (uintptr_t)bufs[i].p, b = (uintptr_t)bufs[j].p;
+            if (a < b + bufs[j].bytes && b < a + bufs[i].bytes)
+                return fail(nullptr, GXPO_ERR_INVALID_ARG, "gxpo_slow_step_noalloc: %s overlaps %s", bufs[i].what, bufs[j].what);
+        }
+    Layout L{};
+    L.n_tensors = 1;
+    L.n_blocks = (uint32_t)((x.numel + kWaveElems - 1) / kWaveElems);
+    L.single = TensorRec{x.theta, nullptr, x.m, x.v, wc ? x.model_copy : nullptr, x.numel, 1.0f, 1.0f};
+    const StepParams p = make_step_params(*cfg, optim_step);
+    hipError_t e = launch_slow_step_noalloc(L, (int)cfg->optimizer, (int)cfg->grad_dtype, GradArg{nullptr, g_slow}, p, wc ? 1 : 0,
+                                            sum_sq_out_device, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(nullptr, e, "gxpo_slow_step_noalloc");
+    return GXPO_OK;
+}
+
 int gxpo_stream_copy(void *dst_device, const void *src_device, uint64_t bytes, void *stream) {
     if (!dst_device || !src_device) return fail(nullptr, GXPO_ERR_INVALID_ARG, "gxpo_stream_copy: NULL pointer");
     if (bytes % 16 || (uintptr_t)dst_device % 16 || (uintptr_t)src_device % 16)

@@ -143,4 +143,10 @@ hipError_t launch_finalize(const double *d_partial, uint32_t n_blocks, const Seg
 
 hipError_t launch_stream_copy(void *dst, const void *src, uint64_t bytes, hipStream_t stream);
 
+// Slow step + sum of squares of one flat tensor with the reduction workspace in a file-scope device
+// array (no allocation anywhere): at most kNoAllocMaxBlocks blocks.  The sum lands in *d_sum_sq_out.
+constexpr uint32_t kNoAllocMaxBlocks = 1u << 20;
+hipError_t launch_slow_step_noalloc(const Layout &L, int optimizer, int grad_dtype, const GradArg &g, const StepParams &p,
+                                    int write_copy, double *d_sum_sq_out, hipStream_t stream);
+
 }  // namespace gxpo

@@ -575,7 +575,9 @@ __global__ __launch_bounds__(kFinalThreads) void k_reduce_runs(const double *__r
     const uint32_t stride = partial_stride(n_blocks);
     const double *partial = partial_all + (size_t)(first_acc + blockIdx.y) * partial_pitch(n_blocks);
     double *seg_sum = seg_sum_all + (size_t)(first_acc + blockIdx.y) * gridDim.x;
-    const SegRec sr = seg[blockIdx.x];
+    // no table: a single tensor, whose runs follow from the block count alone
+    const uint32_t run_first = blockIdx.x * kSegPartials;
+    const SegRec sr = seg ? seg[blockIdx.x] : SegRec{run_first, n_blocks - run_first < kSegPartials ? n_blocks - run_first : kSegPartials};
     double acc = 0.0;
     for (uint32_t i = threadIdx.x; i < sr.count; i += kFinalThreads) acc += partial[partial_slot(sr.first + i, stride)];
     acc = wave_sum(acc);
@@ -601,7 +603,9 @@ __global__ __launch_bounds__(kFinalThreads) void k_reduce_tensors(const double *
     const uint32_t t = blockIdx.x * (kFinalThreads / 64) + (threadIdx.x >> 6);
     if (t >= n_tensors) return;                          // whole wavefronts leave together
     double acc = 0.0;
-    for (uint32_t i = tensor_seg_start[t] + lane; i < tensor_seg_start[t + 1]; i += 64) acc += seg_sum[i];
+    const uint32_t run_lo = tensor_seg_start ? tensor_seg_start[t] : 0u;           // no table: one tensor owning every run
+    const uint32_t run_hi = tensor_seg_start ? tensor_seg_start[t + 1] : n_segs;
+    for (uint32_t i = run_lo + lane; i < run_hi; i += 64) acc += seg_sum[i];
     acc = wave_sum(acc);
     if (lane == 0) {
         result[1 + t] = acc;
@@ -710,6 +714,50 @@ hipError_t launch_finalize(const double *d_partial, uint32_t n_blocks, const Seg
     if (e != hipSuccess || n_tensors == 1) return e;
     k_reduce_total<<<dim3(n_acc), dim3(64), 0, stream>>>(n_tensors, first_acc, d_result);
     return hipGetLastError();
+}
+
+// ============================================================================
+// Slow step + norm for callers that cannot allocate: the reduction workspace is
+// a file-scope device array instead of memory from gxpo_init.  Each GPU holds
+// its own copy of the array at its own address; the address is looked up once
+// per device and kept.  Nothing in the array has to start at zero: every block
+// of a launch writes its own partial, the reduction reads exactly the partials,
+// run sums and results the launch wrote, so what an earlier (larger) call left
+// behind is never read.
+// ============================================================================
+constexpr size_t kNoAllocRuns = (kNoAllocMaxBlocks + kSegPartials - 1) / kSegPartials;
+constexpr size_t kNoAllocDoubles = (size_t)8 * ((kNoAllocMaxBlocks + 7u) >> 3) + kNoAllocRuns + 2;
+static __device__ __align__(256) double scratch[kNoAllocDoubles];
+
+namespace {
+constexpr int kMaxDevices = 64;
+double *g_scratch_ptr[kMaxDevices];            // device address of `scratch` on each GPU, nullptr until looked up
+}  // namespace
+
+hipError_t launch_slow_step_noalloc(const Layout &L, int optimizer, int grad_dtype, const GradArg &g, const StepParams &p,
+                                    int write_copy, double *d_sum_sq_out, hipStream_t stream) {
+    if (L.n_tensors != 1 || L.n_blocks == 0 || L.n_blocks > kNoAllocMaxBlocks) return hipErrorInvalidValue;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    double *ws = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (!ws) {
+        // `scratch` names the array for the host only; kernels need this GPU's address of it
+        e = hipGetSymbolAddress((void **)&ws, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ws) return hipErrorInvalidSymbol;
+        __atomic_store_n(&g_scratch_ptr[dev], ws, __ATOMIC_RELEASE);
+    }
+    double *partial = ws;
+    double *run_sum = ws + partial_pitch(kNoAllocMaxBlocks);
+    double *result = run_sum + kNoAllocRuns;
+    e = launch_step(L, optimizer, grad_dtype, g, p, kSrcTheta, kSrcTheta, 1, write_copy, partial, GradArg{}, nullptr, 0, stream);
+    if (e != hipSuccess) return e;
+    const uint32_t n_runs = (L.n_blocks + kSegPartials - 1) / kSegPartials;
+    e = launch_finalize(partial, L.n_blocks, nullptr, n_runs, nullptr, 1, run_sum, result, kAccSlowSq, 1, stream);
+    if (e != hipSuccess) return e;
+    return hipMemcpyAsync(d_sum_sq_out, result, sizeof(double), hipMemcpyDeviceToDevice, stream);
 }
 
 hipError_t launch_stream_copy(void *dst, const void *src, uint64_t bytes, hipStream_t stream) {
