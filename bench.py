@@ -8,15 +8,21 @@ are produced once, before the timed region, by the synthetic trainer at the
 points the algorithm asks for them (theta, theta^{t,1}, theta~) and are then
 reused: computing gradients is the trainer's work, not the engine's.
 
-Prints ONE JSON line (throughput, per-kernel roofline, CPU baseline).  `--workload` selects a
-parity-test configuration instead of the default one for ad-hoc measurements.
+Prints ONE JSON line.  `value`, `config`, `roofline` and `cpu_baseline` belong to
+the headline workload (configs[1], the one the metric is quoted on).  Without
+`--workload` the same timed loop is then run on the other large configurations
+(configs[2], [3], [4]; for [4] also the fallback step) and reported under
+`workloads`; `--workload X` measures X alone (that is what the profiles use).
 """
 from __future__ import annotations
 
 import argparse
+import gc
+import hashlib
 import json
 import math
 import os
+import statistics
 import sys
 import time
 
@@ -25,6 +31,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published peak
+HEADLINE = "c2"
+ALSO = ["c5", "c4", "c3"]       # the other large configurations, measured after the headline
 
 
 def parse_args():
@@ -32,10 +40,11 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "lora"])
+    ap.add_argument("--workload", default=None, choices=["c1", "c2", "c3", "c4", "c4flat", "c5", "lora"],
+                    help="measure this workload alone (default: configs[1] as the headline, then configs[2..4] under 'workloads')")
     ap.add_argument("--unfused", action="store_true", help="run the second fast step and the extrapolation as two passes")
     ap.add_argument("--same-phase", action="store_true", help="plain torch allocations instead of the phased HBM layout")
-    ap.add_argument("--arena", action="store_true", help="carve all buffers from one allocation")
+    ap.add_argument("--arena", action="store_true", help="carve all buffers from one plain allocation")
     ap.add_argument("--placement", default="auto", choices=["auto", "ranked", "phased"],
                     help="ranked: rank-aware placement through HIP's virtual-memory API; phased: one plain allocation per buffer")
     ap.add_argument("--phases", default="", help="experiment: KiB phases (mod 64) of theta,theta_probe,m,v,g0,g1,g2[,model_copy]")
@@ -45,7 +54,7 @@ def parse_args():
     ap.add_argument("--clip-norm", type=float, default=0.0, help="global-norm gradient clipping threshold (0 = off)")
     ap.add_argument("--diagnostics", action="store_true", help="also accumulate the mechanism diagnostics in the passes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample", type=int, default=1 << 26, help="elements of the workload the oracle is timed on")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 28, help="elements of the workload the oracle is timed on")
     return ap.parse_args()
 
 
@@ -67,6 +76,10 @@ def workload_spec(name: str):
         return dict(label="Llama-3.1-8B ragged layout, 290 tensors, P=8.03e9, bf16 grads, fp32 state",
                     layout=synth.llama31_8b_layout(), optimizer="adamw", grad_dtype="bf16", copy=False, seed=3,
                     cfg=dict(K=8, alpha=0.5, delta=1.75e-3, lr=1e-6))
+    if name == "c4flat":
+        return dict(label="the Llama-3.1-8B workload's 8.03e9 parameters as ONE flat tensor, bf16 grads (shows what the ragged list costs)",
+                    layout=[("flat", sum(n for _, n in synth.llama31_8b_layout()))], optimizer="adamw", grad_dtype="bf16", copy=False,
+                    seed=3, cfg=dict(K=8, alpha=0.5, delta=1.75e-3, lr=1e-6))
     if name == "c5":
         return dict(label="gate-transition buffer, flat fp32, P=3.2e9, AdamW; active and fallback steps",
                     layout=[("flat", synth.GATE_STRESS_PARAMS)], optimizer="adamw", grad_dtype="f32", copy=False, seed=4,
@@ -76,6 +89,10 @@ def workload_spec(name: str):
                     layout=synth.qwen25_7b_lora_layout(), optimizer="adamw", grad_dtype="f32", copy=False, seed=5,
                     cfg=dict(K=10, alpha=0.5, delta=1.75e-3, lr=1e-6))
     raise ValueError(name)
+
+
+def workload_title(name: str, spec) -> str:
+    return (f"configs[{int(name[1]) - 1}]: " if name[0] == "c" and name[1:].isdigit() else "") + spec["label"]
 
 
 def bytes_per_param(spec, fused: bool):
@@ -98,26 +115,16 @@ def bytes_per_param(spec, fused: bool):
     return out
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print(f"bench.py: this build runs on one GPU only (asked for --gpus {args.gpus}); "
-              "sharding over data-parallel ranks is not implemented", file=sys.stderr)
-        sys.exit(2)
-
+def measure(name: str, args, want_cpu_inputs: bool = False):
+    """Allocates the workload's buffers, runs the live step, the warm-up and the timed loop, returns the
+    measurements and releases everything again."""
     import torch
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible; the GXPO engine has no CPU path", file=sys.stderr)
-        sys.exit(2)
-    from paper_2605_06755_amd import build as lib_build
-    lib_build.ensure_built()                     # loads what is built; builds only if nothing is there
     from paper_2605_06755_amd import binding as B
     from paper_2605_06755_amd import layout as layout_mod
     from paper_2605_06755_amd import synth
 
     dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    spec = workload_spec(args.workload)
+    spec = workload_spec(name)
     fused = not args.unfused and not args.explicit_steps
     if args.no_probe:
         if not (spec["copy"] and fused):
@@ -135,7 +142,7 @@ def main():
     if args.phases:
         names = ["theta", "theta_probe", "m", "v", "g0", "g1", "g2", "model_copy"]
         phases = {n: int(x) for n, x in zip(names, args.phases.split(","))}
-    # ---- device buffers (caller-owned), in the layout paper_2605_06755_amd/layout.py describes ---------
+    # ---- device buffers (caller-owned), placed as paper_2605_06755_amd/layout.py describes ----------------
     if args.same_phase:
         flat = {"theta": torch.empty(padded, dtype=torch.float32, device=dev),
                 "theta_probe": torch.empty(padded, dtype=torch.float32, device=dev)}
@@ -145,10 +152,13 @@ def main():
         if spec["copy"]:
             flat["model_copy"] = torch.empty(padded, dtype=torch.bfloat16, device=dev)
         gflat = [torch.empty(padded, dtype=gdt, device=dev) for _ in range(3)]
+        placement = {"kind": "same-phase", "detail": None}
     else:
         flat, gflat = layout_mod.alloc_engine_state(padded, dev, adam=adam, model_copy=spec["copy"], grad_dtype=gdt,
-                                                    arena=args.arena, phases_kib=phases, placement=args.placement, verbose=True)
-    print("base addresses:", {k: hex(v.data_ptr()) for k, v in flat.items()}, [hex(g.data_ptr()) for g in gflat], file=sys.stderr)
+                                                    arena=args.arena, phases_kib=phases, placement=args.placement,
+                                                    probe_is_read=not fused, verbose=True)
+        placement = layout_mod.last_placement()
+    print(f"[{name}] base addresses:", {k: hex(v.data_ptr()) for k, v in flat.items()}, [hex(g.data_ptr()) for g in gflat], file=sys.stderr)
     views = {k: synth.split_like(v, layout, 4) for k, v in flat.items()}
     g0, g1, gs = (synth.split_like(g, layout, 4) for g in gflat)
     tensors = [{k: views[k][i] for k in views if not (spec.get("no_probe") and k == "theta_probe")}
@@ -167,7 +177,6 @@ def main():
     ctx = B.gxpo_init(cfg, tensors)
 
     # ---- one live step: gradients evaluated where Algorithm 1 asks for them ----------------------------
-    S = min(args.cpu_sample, numels[0])
     quad.grad(flat["theta"], 0, gflat[0])
     B.gxpo_fast_steps(ctx, 0, g0)
     quad.grad(flat["model_copy"].float() if spec.get("no_probe") else flat["theta_probe"], 0, gflat[1])
@@ -185,48 +194,58 @@ def main():
     # the gradient buffers are the same every step: marshal their pointer lists once
     g0, g1, gs = B.GradList(ctx, g0), B.GradList(ctx, g1), B.GradList(ctx, gs)
 
-    def active_step(events=None):
-        if args.explicit_steps:
-            calls = tuple((f"fast_step_{j + 1}", (lambda j=j: B.gxpo_fast_steps(ctx, j, g0 if j == 0 else g1)))
-                          for j in range(args.explicit_steps))
-            calls += (("reposition", lambda: B.gxpo_extrapolate(ctx)), ("slow_step", lambda: B.gxpo_slow_step(ctx, gs)))
-        else:
-            calls = (("fast_step_1", lambda: B.gxpo_fast_steps(ctx, 0, g0)),
-                     ("fast_step_2", lambda: B.gxpo_fast_steps(ctx, 1, g1)),
-                     ("fused_steps_extrapolate" if fused else "extrapolate", lambda: B.gxpo_extrapolate(ctx, g0, g1)),
-                     ("slow_step", lambda: B.gxpo_slow_step(ctx, gs)))
-        for name, fn in calls:
-            if events is None or (fused and name == "fast_step_2" and not args.clip_norm > 0):
+    if args.explicit_steps:
+        calls = tuple((f"fast_step_{j + 1}", (lambda j=j: B.gxpo_fast_steps(ctx, j, g0 if j == 0 else g1)))
+                      for j in range(args.explicit_steps))
+        calls += (("reposition", lambda: B.gxpo_extrapolate(ctx)), ("slow_step", lambda: B.gxpo_slow_step(ctx, gs)))
+    else:
+        calls = (("fast_step_1", lambda: B.gxpo_fast_steps(ctx, 0, g0)),
+                 ("fast_step_2", lambda: B.gxpo_fast_steps(ctx, 1, g1)),
+                 ("fused_steps_extrapolate" if fused else "extrapolate", lambda: B.gxpo_extrapolate(ctx, g0, g1)),
+                 ("slow_step", lambda: B.gxpo_slow_step(ctx, gs)))
+
+    def active_step(events=None, step_events=None):
+        # events are recorded on torch's current stream, which is the stream the binding launches on
+        if step_events is not None:
+            a = torch.cuda.Event(enable_timing=True)
+            a.record()
+        for cname, fn in calls:
+            if events is None or (fused and cname == "fast_step_2" and not args.clip_norm > 0):
                 fn()
                 continue
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
+            ka, kb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ka.record()
             fn()
+            kb.record()
+            events.setdefault(cname, []).append((ka, kb))
+        if step_events is not None:
+            b = torch.cuda.Event(enable_timing=True)
             b.record()
-            events.setdefault(name, []).append((a, b))
+            step_events.append((a, b))
         return B.gxpo_gate(ctx)
 
     # the interpreter's cyclic collector is not part of the path: a full collection (tens of ms with torch
     # loaded) landing inside the timed region would leave the GPU idle behind the gate's synchronisation
-    import gc
     gc.collect()
     gc.disable()
     for _ in range(args.warmup):
         active_step()
     torch.cuda.synchronize()
-    events = {}
+    events, step_events = {}, []
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        info = active_step(events)
+        info = active_step(events, step_events)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     gc.enable()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    kernel_ms = {k: sum(a.elapsed_time(b) for a, b in v) / len(v) for k, v in events.items()}
+    step_ms = [a.elapsed_time(b) for a, b in step_events]
+    kernel_ms = {k: statistics.median(a.elapsed_time(b) for a, b in v) for k, v in events.items()}
+    kernel_ms_mean = {k: sum(a.elapsed_time(b) for a, b in v) / len(v) for k, v in events.items()}
     bpp = bytes_per_param(spec, fused)
     if args.explicit_steps:
         full = bpp["slow_step"]
-        bpp = {f"fast_step_{j + 1}": full - (0 if spec["copy"] else 0) for j in range(args.explicit_steps)}
+        bpp = {f"fast_step_{j + 1}": full for j in range(args.explicit_steps)}
         bpp.update(reposition=12 + (2 if spec["copy"] else 0), slow_step=full, fallback_step=full)
     gbytes = 4 if spec["grad_dtype"] == "f32" else 2
     if args.diagnostics:
@@ -237,11 +256,11 @@ def main():
         for k in ("fast_step_1", "fast_step_2", "slow_step", "fallback_step"):   # norm pre-pass: the gradient is read twice
             if k in bpp:
                 bpp[k] += gbytes
-    step_bytes = sum(bpp[k] for k in kernel_ms) * P
-    kernels = {k: {"ms": round(ms, 4), "bytes_per_param": bpp[k], "gbps": round(bpp[k] * P / ms / 1e6, 1)}
+    step_bpp = sum(bpp[k] for k in kernel_ms)
+    kernels = {k: {"ms": round(ms, 4), "ms_mean": round(kernel_ms_mean[k], 4), "bytes_per_param": bpp[k],
+                   "gbps": round(bpp[k] * P / ms / 1e6, 1), "frac_of_peak": round(bpp[k] * P / ms / 1e6 / HBM_PEAK_GBPS, 4)}
                for k, ms in kernel_ms.items()}
     dominant = max(kernel_ms, key=lambda k: bpp[k])
-    achieved = bpp[dominant] * P / kernel_ms[dominant] / 1e6
 
     # ---- plain copy on the same box, same access pattern (context for the roofline fraction) ------------
     n_copy = min(padded, 1 << 30)
@@ -257,79 +276,162 @@ def main():
 
     # ---- fallback-phase throughput (reported for the gate-transition workload) ---------------------------
     fallback = None
-    if args.workload == "c5":
+    if name == "c5":
         st = B.gxpo_get_state(ctx)
         st.s_star = st.t
         B.gxpo_set_state(ctx, st)
         for _ in range(args.warmup):
             B.gxpo_fallback_step(ctx, g0)
         torch.cuda.synchronize()
+        fev = []
         tf0 = time.perf_counter()
         for _ in range(args.steps):
+            fa, fb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            fa.record()
             B.gxpo_fallback_step(ctx, g0)
+            fb.record()
+            fev.append((fa, fb))
         torch.cuda.synchronize()
         fms = (time.perf_counter() - tf0) * 1e3 / args.steps
-        fallback = {"ms_per_step": round(fms, 4), "gparams_per_s": round(P / fms / 1e6, 2),
-                    "gbps": round(bpp["fallback_step"] * P / fms / 1e6, 1),
+        fmed = statistics.median(x.elapsed_time(y) for x, y in fev)
+        fallback = {"ms_per_step": round(fms, 4), "ms_per_step_median_events": round(fmed, 4), "gparams_per_s": round(P / fms / 1e6, 2),
+                    "bytes_per_param": bpp["fallback_step"], "gbps": round(bpp["fallback_step"] * P / fms / 1e6, 1),
                     "frac_of_peak": round(bpp["fallback_step"] * P / fms / 1e6 / HBM_PEAK_GBPS, 4)}
 
-    # ---- traffic measured with hardware counters, if a summary for this workload is committed ---------------
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"traffic_{dominant}_{args.workload}.json")
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
-        except Exception:
-            traffic = None
-
-    # ---- the oracle on the host cores, bounded sample ------------------------------------------------------------
-    cpu_baseline = None
-    if not args.no_cpu_baseline:
+    if placement["kind"] == "ranked":
+        hbm_layout = "rank-aware placement (read streams of a slab in one DRAM rank), moments +32KiB mod 64KiB"
+    elif placement["kind"] == "same-phase":
+        hbm_layout = "same-phase"
+    else:
+        hbm_layout = "moments +32KiB mod 64KiB"
+    res = {
+        "workload": workload_title(name, spec), "params": P, "tensors": len(numels), "grad_dtype": spec["grad_dtype"],
+        "fused_step2": fused, "hbm_layout": hbm_layout, "bytes_per_param_per_step": step_bpp,
+        "ms_per_step": round(ms_per_step, 4), "ms_per_step_median_events": round(statistics.median(step_ms), 4),
+        "ms_per_step_min_max_events": [round(min(step_ms), 4), round(max(step_ms), 4)],
+        "gparams_per_s": round(P / ms_per_step / 1e6, 3),
+        "hbm_gbps_step": round(step_bpp * P / ms_per_step / 1e6, 1),
+        "hbm_frac_of_peak_step": round(step_bpp * P / ms_per_step / 1e6 / HBM_PEAK_GBPS, 4),
+        "copy_kernel_gbps": round(copy_gbps, 1), "kernels": kernels, "dominant_kernel": dominant,
+        "gate": {"norm": info.norm, "z": None if math.isnan(info.z) else info.z, "tripped": bool(info.tripped),
+                 "live_step_norm": live_info.norm},
+    }
+    if fallback:
+        res["fallback_step"] = fallback
+    if args.diagnostics:
+        d = B.gxpo_get_diagnostics(ctx)
+        res["diagnostics"] = {k: getattr(d, k) for k, _ in d._fields_}
+    cpu_inputs = None
+    if want_cpu_inputs:
         # sampled only now, after every GPU measurement: large device-to-host copies ahead of
         # the timed region were seen to cost the following kernels a few percent
+        S = min(args.cpu_sample, numels[0])
         cpu_inputs = {"theta": views["theta"][0][:S].cpu(), "g0": g0.tensors[0][:S].cpu(), "g1": g1.tensors[0][:S].cpu(),
-                      "gs": gs.tensors[0][:S].cpu()}
-        cpu_baseline = time_oracle(spec, cfg, cpu_inputs, S)
+                      "gs": gs.tensors[0][:S].cpu(), "S": S, "spec": spec, "cfg": cfg}
+    # ---- release everything before the next workload ---------------------------------------------------------
+    B.gxpo_destroy(ctx)
+    del ctx, calls, g0, g1, gs, tensors, views, flat, gflat, quad, events, step_events, active_step
+    gc.collect()
+    torch.cuda.empty_cache()
+    return res, cpu_inputs
+
+
+def kernel_source_stamp() -> str:
+    """Identifies the kernel source a hardware-counter figure was taken on."""
+    with open(os.path.join(ROOT, "paper_2605_06755_amd", "csrc", "gxpo_kernels.hip"), "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()[:16]
+
+
+def counter_traffic(kernel: str, workload: str):
+    """HBM bytes per launch of `kernel` on `workload` from the committed rocprofv3 --pmc summary, if that summary was
+    taken on the kernel source that is in the tree now; else None (the counters cannot be read from inside this run)."""
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{kernel}_{workload}.json")
+    if not os.path.exists(tpath):
+        return None, "no committed counter summary for this kernel and workload"
+    try:
+        rec = json.load(open(tpath))
+    except Exception:
+        return None, "counter summary unreadable"
+    if rec.get("kernel_source_sha256_16") != kernel_source_stamp():
+        return None, "the committed counter summary was taken on an older kernel source"
+    return rec.get("hbm_bytes_per_launch"), f"profiles/{os.path.basename(tpath)} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, same kernel source)"
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU only (asked for --gpus {args.gpus}); "
+              "sharding over data-parallel ranks is not implemented", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the GXPO engine has no CPU path", file=sys.stderr)
+        sys.exit(2)
+    from paper_2605_06755_amd import build as lib_build
+    lib_build.ensure_built()                     # loads what is built; builds only if nothing is there
+    torch.cuda.set_device(torch.device("cuda:0"))
+
+    head_name = args.workload or HEADLINE
+    head, cpu_inputs = measure(head_name, args, want_cpu_inputs=not args.no_cpu_baseline)
+    others = {}
+    if args.workload is None:
+        for name in ALSO:
+            try:
+                others[name], _ = measure(name, args)
+            except Exception as e:        # a workload that does not fit this box must not cost the headline its line
+                others[name] = {"error": f"{type(e).__name__}: {e}"}
+                gc.collect()
+                torch.cuda.empty_cache()
+
+    dominant = head["dominant_kernel"]
+    dk = head["kernels"][dominant]
+    traffic, traffic_source = counter_traffic(dominant, head_name)
+    cpu_baseline = None
+    if cpu_inputs is not None:
+        cpu_baseline = time_oracle(cpu_inputs)
 
     out = {
         "metric": "GXPO active-step Gparams/s and achieved HBM GB/s (% of peak) on 1 MI355X",
-        "value": round(P / ms_per_step / 1e6, 3),
+        "value": head["gparams_per_s"],
         "unit": "Gparams/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step": head["ms_per_step"],
+        "ms_per_step_median_events": head["ms_per_step_median_events"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": (f"configs[{int(args.workload[1]) - 1}]: " if args.workload[0] == "c" else "") + spec["label"], "params": P,
-                   "tensors": len(numels), "grad_dtype": spec["grad_dtype"], "fused_step2": fused,
-                   "hbm_layout": "same-phase" if args.same_phase else "moments +32KiB mod 64KiB", "bytes_per_param_per_step": sum(bpp[k] for k in kernel_ms)},
-        "hbm_gbps_step": round(step_bytes / ms_per_step / 1e6, 1),
-        "hbm_frac_of_peak_step": round(step_bytes / ms_per_step / 1e6 / HBM_PEAK_GBPS, 4),
-        "copy_kernel_gbps": round(copy_gbps, 1),
-        "kernels": kernels,
-        "gate": {"norm": info.norm, "z": None if math.isnan(info.z) else info.z, "tripped": bool(info.tripped),
-                 "live_step_norm": live_info.norm},
-        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic},
+        "config": {"workload": head["workload"], "params": head["params"], "tensors": head["tensors"],
+                   "grad_dtype": head["grad_dtype"], "fused_step2": head["fused_step2"], "hbm_layout": head["hbm_layout"],
+                   "bytes_per_param_per_step": head["bytes_per_param_per_step"]},
+        "hbm_gbps_step": head["hbm_gbps_step"],
+        "hbm_frac_of_peak_step": head["hbm_frac_of_peak_step"],
+        "copy_kernel_gbps": head["copy_kernel_gbps"],
+        "kernels": head["kernels"],
+        "gate": head["gate"],
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": dk["gbps"], "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(dk["gbps"] / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "traffic_source": traffic_source, "timing": "median of per-launch HIP-event durations over the timed steps"},
         "cpu_baseline": cpu_baseline,
     }
-    if fallback:
-        out["fallback_step"] = fallback
-    if args.diagnostics:
-        d = B.gxpo_get_diagnostics(ctx)
-        out["diagnostics"] = {k: getattr(d, k) for k, _ in d._fields_}
+    for k in ("fallback_step", "diagnostics"):
+        if k in head:
+            out[k] = head[k]
+    if others:
+        out["workloads"] = others
     print(json.dumps(out))
 
 
-def time_oracle(spec, cfg, inputs, S):
+def time_oracle(inputs):
     """The fp64 oracle, as it stands, on the first S elements of the same
     buffers: one active step (five calls), repeated until ~10 s have passed."""
     import torch
     from oracle import gxpo_oracle as O
+    spec, cfg, S = inputs["spec"], inputs["cfg"], inputs["S"]
     oc = O.GXPOConfig(
         optim=O.OptimConfig(spec["optimizer"], lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.adam_eps,
                             weight_decay=cfg.weight_decay),

@@ -38,8 +38,10 @@
  *    when gxpo_init() ran; that GPU must be current on every later call.
  *    "host" pointers are ordinary process memory.  Every device range is
  *    checked with hipMemGetAddressRange before a kernel may touch it, so the
- *    buffers must lie in allocations that call can resolve (hipMalloc and
- *    allocators built on it).
+ *    buffers must lie in allocations that call can resolve: hipMalloc and
+ *    allocators built on it, or physical chunks mapped back to back into one
+ *    reserved address range with HIP's virtual-memory API (a buffer may span
+ *    several such adjacent mappings).
  *  - The caller owns every parameter-sized buffer (theta, theta_probe, m, v,
  *    model_copy, gradients) and keeps it alive and un-aliased while the
  *    context lives; the context owns only its small tables and the reduction
@@ -129,7 +131,11 @@ typedef struct gxpo_config {
                                  them would have given).  0: each call runs its own pass. */
     uint32_t copy_mask;       /* GXPO_COPY_AT_* bits; ignored for tensors without model_copy */
     uint32_t window;          /* w: number of past norms the gate statistics use, 2..GXPO_MAX_WINDOW */
-    uint32_t gate_min_count;  /* gate is evaluated once the buffer holds this many norms; 0 = window */
+    uint32_t gate_min_count;  /* gate is evaluated once the buffer holds this many norms.  0 = window: the text's
+                                 reading (Section 2.3: during warm-up the buffer is only filled; Eq. (10) speaks of
+                                 the past w norms).  2 reproduces Algorithm 1 as printed, which evaluates the rule
+                                 as soon as len(B) > 1 -- then an instability at t < w can already trip the gate,
+                                 and s* and the budget 3 s* + (T - s*) follow the listing. */
     uint32_t gate_ddof;       /* 0 population / 1 sample standard deviation */
     uint32_t diagnostics;     /* 1: also accumulate the mechanism diagnostics (gxpo_get_diagnostics) inside
                                  the extrapolation pass and the slow step; g0 is then re-read by the slow

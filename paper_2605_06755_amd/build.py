@@ -68,6 +68,20 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+PROBE_SRC = os.path.join(CSRC, "hbm_probe.hip")
+PROBE = os.path.join(PKG, "hbm_probe")
+
+
+def build_probe(verbose: bool = False) -> str:
+    """hbm_probe: the stand-alone bandwidth measurements behind the launch shape, cache policy, phases and
+    rank-aware placement (see the comment at the top of its source).  Not needed to use the library."""
+    cmd = [_hipcc(), *[f for f in DEVICE_FLAGS if f != "-fPIC"], PROBE_SRC, "-o", PROBE]
+    if verbose:
+        print(" ".join(cmd), file=sys.stderr)
+    _run(cmd)
+    return PROBE
+
+
 ABI_DRIVER_SRC = os.path.join(ROOT, "tests", "abi", "abi_driver.c")
 ABI_DRIVER = os.path.join(ROOT, "tests", "abi", "abi_driver")
 
@@ -126,3 +140,4 @@ def ensure_built() -> None:
 if __name__ == "__main__":
     print(build_library(verbose=True))
     print(build_abi_driver(verbose=True))
+    print(build_probe(verbose=True))

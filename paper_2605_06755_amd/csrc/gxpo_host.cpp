@@ -830,12 +830,9 @@ int gxpo_slow_step_noalloc(const gxpo_config *cfg, const gxpo_tensor *tensor, in
                          {wc ? x.model_copy : nullptr, x.numel * 2, 8, "model_copy"},
                          {g_slow, x.numel * gbytes, cfg->grad_dtype == GXPO_GRAD_F32 ? (uintptr_t)16 : (uintptr_t)8, "g_slow"},
                          {sum_sq_out_device, 8, 8, "sum_sq_out"}};
-    for (const Buf &b : bufs) {
-        if (!b.p) continue;
-        if ((uintptr_t)b.p % b.align) return fail(nullptr, GXPO_ERR_ALIGNMENT, "gxpo_slow_step_noalloc: %s is not %u-byte aligned", b.what, (unsigned)b.align);
-        rc = check_device_range(nullptr, b.p, b.bytes, b.what, 0);
-        if (rc != GXPO_OK) return rc;
-    }
+    for (const Buf &b : bufs)
+        if (b.p && (uintptr_t)b.p % b.align)
+            return fail(nullptr, GXPO_ERR_ALIGNMENT, "gxpo_slow_step_noalloc: %s is not %u-byte aligned", b.what, (unsigned)b.align);
     for (int i = 0; i < 6; ++i)
         for (int j = i + 1; j < 6; ++j) {
             if (!bufs[i].p || !bufs[j].p) continue;
@@ -843,6 +840,11 @@ int gxpo_slow_step_noalloc(const gxpo_config *cfg, const gxpo_tensor *tensor, in
             if (a < b + bufs[j].bytes && b < a + bufs[i].bytes)
                 return fail(nullptr, GXPO_ERR_INVALID_ARG, "gxpo_slow_step_noalloc: %s overlaps %s", bufs[i].what, bufs[j].what);
         }
+    for (const Buf &b : bufs) {
+        if (!b.p) continue;
+        rc = check_device_range(nullptr, b.p, b.bytes, b.what, 0);
+        if (rc != GXPO_OK) return rc;
+    }
     Layout L{};
     L.n_tensors = 1;
     L.n_blocks = (uint32_t)((x.numel + kWaveElems - 1) / kWaveElems);

@@ -1,0 +1,329 @@
+// hbm_probe -- stand-alone measurements behind the engine's launch shape, cache policy, buffer
+// phases and rank-aware placement on MI355X (gfx950).  Not part of libgxpo.so: a small program
+// that streams synthetic arrays with the engine's access pattern and prints GB/s, so that every
+// design choice quoted in the documentation can be re-measured with one command:
+//
+//     hbm_probe shape      one-wave one-shot blocks vs wider blocks, 8 elements per lane, grid-stride loops
+//     hbm_probe policy     cache-policy bits of the buffer accesses, and plain global accesses
+//     hbm_probe phase      base addresses of the streams modulo 64 KiB
+//     hbm_probe ranks      one read stream moved across a 200 GiB allocation (DRAM rank regions)
+//     hbm_probe bf16       the fused pass with two bf16 gradient streams: 64-bit vs 128-bit accesses
+//
+// The pass modelled is the AdamW-shaped step: read theta, m, v, g; write theta', m, v (28 B per
+// element with fp32 gradients), arithmetic reduced to a few multiply-adds (the real arithmetic
+// changes the time by < 0.2 %).  Arrays hold pseudo-random data (all-zero data streams faster).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#define CK(x)                                                                                   \
+    do {                                                                                        \
+        hipError_t e_ = (x);                                                                    \
+        if (e_ != hipSuccess) {                                                                 \
+            printf("HIP error %s at %s:%d\n", hipGetErrorString(e_), __FILE__, __LINE__);      \
+            exit(1);                                                                            \
+        }                                                                                       \
+    } while (0)
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef unsigned u4 __attribute__((ext_vector_type(4)));
+typedef unsigned u2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void *base, unsigned bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+template <int POL> __device__ __forceinline__ f4 ld(__amdgpu_buffer_rsrc_t r, int off) {
+    return __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, POL));
+}
+template <int POL> __device__ __forceinline__ void st(__amdgpu_buffer_rsrc_t r, int off, f4 v) {
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, v), r, off, 0, POL);
+}
+__device__ __forceinline__ void math(f4 &T, f4 &M, f4 &V, f4 G) {
+    M = M * 0.9f + G;
+    V = V * 0.99f + G * G;
+    T = T + M * 1e-6f + V * 1e-7f;
+}
+__device__ __forceinline__ unsigned span_bytes(size_t n, size_t e0, unsigned block_elems) {
+    const size_t rem = n - e0;
+    return (unsigned)(rem < block_elems ? rem : block_elems) * 4u;
+}
+
+// one-shot blocks of WPB wavefronts, EPL elements per lane (EPL 8: two 128-bit accesses, 1 KiB apart), policy POL
+template <int WPB, int EPL, int POL>
+__global__ __launch_bounds__(64 * WPB) void k_step(const float *th_in, float *th_out, float *m, float *v, const float *g, size_t n) {
+    constexpr unsigned BE = 64 * WPB * EPL;
+    const size_t e0 = (size_t)blockIdx.x * BE;
+    if (e0 >= n) return;
+    const unsigned bytes = span_bytes(n, e0, BE);
+    const auto rt = rsrc(th_in + e0, bytes), ro = rsrc(th_out + e0, bytes), rm = rsrc(m + e0, bytes), rv = rsrc(v + e0, bytes),
+               rg = rsrc(g + e0, bytes);
+    f4 T[EPL / 4], M[EPL / 4], V[EPL / 4], G[EPL / 4];
+#pragma unroll
+    for (int j = 0; j < EPL / 4; ++j) {
+        const int off = (j * 64 * WPB + threadIdx.x) * 16;
+        T[j] = ld<POL>(rt, off), M[j] = ld<POL>(rm, off), V[j] = ld<POL>(rv, off), G[j] = ld<POL>(rg, off);
+    }
+#pragma unroll
+    for (int j = 0; j < EPL / 4; ++j) {
+        const int off = (j * 64 * WPB + threadIdx.x) * 16;
+        math(T[j], M[j], V[j], G[j]);
+        st<POL>(ro, off, T[j]), st<POL>(rm, off, M[j]), st<POL>(rv, off, V[j]);
+    }
+}
+
+// persistent blocks that walk the arrays with a grid stride
+template <int WPB>
+__global__ __launch_bounds__(64 * WPB) void k_step_stride(const float *th_in, float *th_out, float *m, float *v, const float *g, size_t n) {
+    constexpr unsigned BE = 64 * WPB * 4;
+    for (size_t e0 = (size_t)blockIdx.x * BE; e0 < n; e0 += (size_t)gridDim.x * BE) {
+        const unsigned bytes = span_bytes(n, e0, BE);
+        const auto rt = rsrc(th_in + e0, bytes), ro = rsrc(th_out + e0, bytes), rm = rsrc(m + e0, bytes), rv = rsrc(v + e0, bytes),
+                   rg = rsrc(g + e0, bytes);
+        const int off = threadIdx.x * 16;
+        f4 T = ld<18>(rt, off), M = ld<18>(rm, off), V = ld<18>(rv, off), G = ld<18>(rg, off);
+        math(T, M, V, G);
+        st<18>(ro, off, T), st<18>(rm, off, M), st<18>(rv, off, V);
+    }
+}
+
+// plain global accesses (no buffer descriptors); NT selects non-temporal builtins
+template <bool NT>
+__global__ __launch_bounds__(64) void k_step_global(const f4 *th_in, f4 *th_out, f4 *m, f4 *v, const f4 *g, size_t n4) {
+    const size_t i = (size_t)blockIdx.x * 64 + threadIdx.x;
+    if (i >= n4) return;
+    f4 T, M, V, G;
+    if (NT) {
+        T = __builtin_nontemporal_load(th_in + i), M = __builtin_nontemporal_load(m + i), V = __builtin_nontemporal_load(v + i),
+        G = __builtin_nontemporal_load(g + i);
+    } else {
+        T = th_in[i], M = m[i], V = v[i], G = g[i];
+    }
+    math(T, M, V, G);
+    if (NT) {
+        __builtin_nontemporal_store(T, th_out + i), __builtin_nontemporal_store(M, m + i), __builtin_nontemporal_store(V, v + i);
+    } else {
+        th_out[i] = T, m[i] = M, v[i] = V;
+    }
+}
+
+// in-place step: read theta, m, v, g; write theta, m, v (the slow step's shape)
+__global__ __launch_bounds__(64) void k_slow(float *th, float *m, float *v, const float *g, size_t n) {
+    const size_t e0 = (size_t)blockIdx.x * 256;
+    if (e0 >= n) return;
+    const unsigned bytes = span_bytes(n, e0, 256);
+    const int off = threadIdx.x * 16;
+    const auto rt = rsrc(th + e0, bytes), rm = rsrc(m + e0, bytes), rv = rsrc(v + e0, bytes);
+    f4 T = ld<18>(rt, off), M = ld<18>(rm, off), V = ld<18>(rv, off), G = ld<18>(rsrc(g + e0, bytes), off);
+    math(T, M, V, G);
+    st<18>(rt, off, T), st<18>(rm, off, M), st<18>(rv, off, V);
+}
+
+__global__ __launch_bounds__(64) void k_copy(const float *src, float *dst, size_t n) {
+    const size_t e0 = (size_t)blockIdx.x * 256;
+    if (e0 >= n) return;
+    const unsigned bytes = span_bytes(n, e0, 256);
+    st<18>(rsrc(dst + e0, bytes), threadIdx.x * 16, ld<18>(rsrc(src + e0, bytes), threadIdx.x * 16));
+}
+
+__device__ __forceinline__ f4 widen(unsigned a, unsigned b) {
+    f4 o;
+    o[0] = __builtin_bit_cast(float, a << 16), o[1] = __builtin_bit_cast(float, a & 0xffff0000u);
+    o[2] = __builtin_bit_cast(float, b << 16), o[3] = __builtin_bit_cast(float, b & 0xffff0000u);
+    return o;
+}
+// the fused pass's shape: read theta, m, v, g0, g1; write theta, m, v.  MODE 0: fp32 gradients; 1: bf16 gradients, one
+// 64-bit access per lane; 2: bf16, lanes 0..31 issue 128-bit accesses and the data is handed to the owning lanes.
+template <int MODE>
+__global__ __launch_bounds__(64) void k_fused(float *th, float *m, float *v, const void *g0, const void *g1, size_t n) {
+    const size_t e0 = (size_t)blockIdx.x * 256;
+    if (e0 >= n) return;
+    const unsigned bytes = span_bytes(n, e0, 256);
+    const int off = threadIdx.x * 16;
+    const auto rt = rsrc(th + e0, bytes), rm = rsrc(m + e0, bytes), rv = rsrc(v + e0, bytes);
+    auto grad = [&](const void *g) -> f4 {
+        if (MODE == 0) return ld<18>(rsrc((const float *)g + e0, bytes), off);
+        const auto rg = rsrc((const unsigned short *)g + e0, bytes / 2);
+        if (MODE == 1) {
+            const u2 x = __builtin_amdgcn_raw_buffer_load_b64(rg, threadIdx.x * 8, 0, 18);
+            return widen(x[0], x[1]);
+        }
+        u4 x = {0, 0, 0, 0};
+        if (threadIdx.x < 32) x = __builtin_amdgcn_raw_buffer_load_b128(rg, threadIdx.x * 16, 0, 18);
+        const int src = (threadIdx.x >> 1) * 4;
+        const unsigned a0 = __builtin_amdgcn_ds_bpermute(src, x[0]), a1 = __builtin_amdgcn_ds_bpermute(src, x[1]);
+        const unsigned a2 = __builtin_amdgcn_ds_bpermute(src, x[2]), a3 = __builtin_amdgcn_ds_bpermute(src, x[3]);
+        return (threadIdx.x & 1) ? widen(a2, a3) : widen(a0, a1);
+    };
+    f4 T = ld<18>(rt, off), M = ld<18>(rm, off), V = ld<18>(rv, off);
+    const f4 G = grad(g0), H = grad(g1);
+    math(T, M, V, G + H * 0.1f);
+    st<18>(rt, off, T), st<18>(rm, off, M), st<18>(rv, off, V);
+}
+
+__global__ void k_fill(float *p, size_t n, unsigned seed) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) {
+        unsigned x = (unsigned)i * 2654435761u + seed;
+        x ^= x >> 15, x *= 2246822519u, x ^= x >> 13;
+        p[i] = ((int)(x >> 9) - (1 << 22)) * (0.02f / (1 << 22));
+    }
+}
+
+// best of three batches of `iters` launches, in GB/s
+template <typename F> static double gbps(F launch, double bytes, int iters = 8) {
+    static hipEvent_t a, b;
+    static bool made = false;
+    if (!made) {
+        CK(hipEventCreate(&a));
+        CK(hipEventCreate(&b));
+        made = true;
+    }
+    launch();
+    double best = 0;
+    for (int r = 0; r < 3; ++r) {
+        CK(hipEventRecord(a));
+        for (int i = 0; i < iters; ++i) launch();
+        CK(hipEventRecord(b));
+        CK(hipEventSynchronize(b));
+        float ms;
+        CK(hipEventElapsedTime(&ms, a, b));
+        best = std::max(best, bytes * iters / ms / 1e6);
+    }
+    CK(hipGetLastError());
+    return best;
+}
+
+static const size_t MiB = 1ull << 20, GiB = 1ull << 30;
+static char *arena(size_t bytes) {
+    char *base;
+    CK(hipMalloc(&base, bytes + GiB));
+    base += (GiB - (size_t)base % GiB) % GiB;
+    k_fill<<<16384, 256>>>((float *)base, bytes / 4, 7);
+    CK(hipDeviceSynchronize());
+    CK(hipGetLastError());
+    return base;
+}
+static void line(const char *what, double g) {
+    printf("  %-84s %7.0f GB/s  %5.1f %% of 8 TB/s\n", what, g, g / 80.0);
+    fflush(stdout);
+}
+
+// five arrays of n elements, 2 MiB-multiple pitch, moments 32 KiB out of phase unless told otherwise
+struct Five { float *a[5]; };
+static Five place(char *base, size_t pitch, const size_t *phase) {
+    Five f;
+    for (int k = 0; k < 5; ++k) f.a[k] = (float *)(base + k * pitch + phase[k]);
+    return f;
+}
+
+static int run_shape() {
+    const size_t n = 1540000000ull, pitch = ((n * 4 + 2 * MiB - 1) / (2 * MiB) + 1) * 2 * MiB;
+    char *base = arena(pitch * 5);
+    const size_t ph[5] = {0, 0, 32768, 32768, 0};
+    const Five f = place(base, pitch, ph);
+    printf("launch shape, AdamW-shaped step (28 B/element), n = %zu fp32 per array, moments +32 KiB\n", n);
+    auto nb = [&](unsigned be) { return (unsigned)((n + be - 1) / be); };
+    line("one-shot blocks, 1 wavefront, 4 elements per lane  [the engine's shape]", gbps([&] { k_step<1, 4, 18><<<nb(256), 64>>>(f.a[0], f.a[1], f.a[2], f.a[3], f.a[4], n); }, 28.0 * n));
+    line("one-shot blocks, 2 wavefronts", gbps([&] { k_step<2, 4, 18><<<nb(512), 128>>>(f.a[0], f.a[1], f.a[2], f.a[3], f.a[4], n); }, 28.0 * n));
+    line("one-shot blocks, 4 wavefronts", gbps([&] { k_step<4, 4, 18><<<nb(1024), 256>>>(f.a[0], f.a[1], f.a[2], f.a[3], f.a[4], n); }, 28.0 * n));
+    line("one-shot blocks, 1 wavefront, 8 elements per lane (two 128-bit accesses per stream)", gbps([&] { k_step<1, 8, 18><<<nb(512), 64>>>(f.a[0], f.a[1], f.a[2], f.a[3], f.a[4], n); }, 28.0 * n));
+    for (int per_cu : {4, 8, 16, 32})
+        {
+            char what[96];
+            snprintf(what, sizeof what, "grid-stride loop, 1-wavefront blocks, %d blocks per CU", per_cu);
+            line(what, gbps([&] { k_step_stride<1><<<256 * per_cu, 64>>>(f.a[0], f.a[1], f.a[2], f.a[3], f.a[4], n); }, 28.0 * n));
+        }
+    line("grid-stride loop, 4-wavefront blocks, 8 blocks per CU", gbps([&] { k_step_stride<4><<<256 * 8, 256>>>(f.a[0], f.a[1], f.a[2], f.a[3], f.a[4], n); }, 28.0 * n));
+    line("plain copy, same shape (8 B/element)", gbps([&] { k_copy<<<nb(256), 64>>>(f.a[0], f.a[1], n); }, 8.0 * n));
+    return 0;
+}
+
+static int run_policy() {
+    const size_t n = 1540000000ull, pitch = ((n * 4 + 2 * MiB - 1) / (2 * MiB) + 1) * 2 * MiB;
+    char *base = arena(pitch * 5);
+    const size_t ph[5] = {0, 0, 32768, 32768, 0};
+    const Five f = place(base, pitch, ph);
+    const unsigned nb = (unsigned)((n + 255) / 256);
+    printf("cache policy of the accesses, AdamW-shaped step, n = %zu\n", n);
+    line("buffer accesses, sc1 + nt (streaming)  [the engine's policy]", gbps([&] { k_step<1, 4, 18><<<nb, 64>>>(f.a[0], f.a[1], f.a[2], f.a[3], f.a[4], n); }, 28.0 * n));
+    line("buffer accesses, nt only", gbps([&] { k_step<1, 4, 2><<<nb, 64>>>(f.a[0], f.a[1], f.a[2], f.a[3], f.a[4], n); }, 28.0 * n));
+    line("buffer accesses, sc1 only", gbps([&] { k_step<1, 4, 16><<<nb, 64>>>(f.a[0], f.a[1], f.a[2], f.a[3], f.a[4], n); }, 28.0 * n));
+    line("buffer accesses, default policy", gbps([&] { k_step<1, 4, 0><<<nb, 64>>>(f.a[0], f.a[1], f.a[2], f.a[3], f.a[4], n); }, 28.0 * n));
+    line("global accesses, non-temporal", gbps([&] { k_step_global<true><<<(unsigned)((n / 4 + 63) / 64), 64>>>((const f4 *)f.a[0], (f4 *)f.a[1], (f4 *)f.a[2], (f4 *)f.a[3], (const f4 *)f.a[4], n / 4); }, 28.0 * n));
+    line("global accesses, default", gbps([&] { k_step_global<false><<<(unsigned)((n / 4 + 63) / 64), 64>>>((const f4 *)f.a[0], (f4 *)f.a[1], (f4 *)f.a[2], (f4 *)f.a[3], (const f4 *)f.a[4], n / 4); }, 28.0 * n));
+    return 0;
+}
+
+static int run_phase() {
+    const size_t n = 1540000000ull, pitch = ((n * 4 + 2 * MiB - 1) / (2 * MiB) + 1) * 2 * MiB;
+    char *base = arena(pitch * 5);
+    const unsigned nb = (unsigned)((n + 255) / 256);
+    printf("base addresses modulo 64 KiB (KiB: theta_in, theta_out, m, v, g), AdamW-shaped step, n = %zu\n", n);
+    const int combos[][5] = {{0, 0, 0, 0, 0},    {0, 0, 32, 32, 0},  {0, 32, 32, 32, 0}, {0, 0, 32, 32, 32}, {0, 32, 0, 32, 0},
+                             {0, 0, 16, 48, 0},  {0, 16, 32, 48, 8}, {0, 8, 16, 24, 32}, {0, 0, 32, 0, 0},   {0, 4, 32, 36, 8}};
+    for (const auto &c : combos) {
+        size_t ph[5];
+        for (int k = 0; k < 5; ++k) ph[k] = (size_t)c[k] * 1024;
+        const Five f = place(base, pitch, ph);
+        char what[96];
+        snprintf(what, sizeof what, "phases %2d %2d %2d %2d %2d KiB%s", c[0], c[1], c[2], c[3], c[4], (c[2] == 32 && c[3] == 32 && !c[1] && !c[4]) ? "  [the layout rule]" : "");
+        line(what, gbps([&] { k_step<1, 4, 18><<<nb, 64>>>(f.a[0], f.a[1], f.a[2], f.a[3], f.a[4], n); }, 28.0 * n));
+    }
+    return 0;
+}
+
+static int run_ranks() {
+    const size_t n = 1ull << 27;                                    // 512 MiB windows
+    const int span = 200;
+    char *base = arena((size_t)(span + 8) * GiB);
+    const unsigned nb = (unsigned)(n / 256);
+    auto at = [&](int gib, size_t ph = 0) { return (float *)(base + (size_t)gib * GiB + ph); };
+    printf("one 208 GiB allocation; slow-step shape (read theta, m, v, g; write theta, m, v) on 512 MiB windows:\n"
+           "theta, m, v fixed at offsets ref, ref+1, ref+2 GiB, the gradient window at offset x.  Columns: ref = 0, 100, 195 GiB.\n"
+           "A window in the same DRAM rank as the reference runs ~4 %% faster than one in another rank.\n"
+           "   x GiB     ref 0   ref 100   ref 195   |  copy 0 -> x   all four at x..x+3\n");
+    const int refs[3] = {0, 100, 195};
+    for (int x = 3; x <= span; ++x) {
+        printf("  %5d ", x);
+        for (int r : refs) {
+            if (x >= r - 1 && x <= r + 3) {
+                printf("        - ");
+                continue;
+            }
+            printf("   %6.0f ", gbps([&] { k_slow<<<nb, 64>>>(at(r), at(r + 1, 32768), at(r + 2, 32768), at(x), n); }, 28.0 * n, 5));
+        }
+        printf("  |   %6.0f      %6.0f\n", gbps([&] { k_copy<<<nb, 64>>>(at(0), at(x), n); }, 8.0 * n, 5),
+               gbps([&] { k_slow<<<nb, 64>>>(at(x), at(x + 1, 32768), at(x + 2, 32768), at(x + 3), n); }, 28.0 * n, 5));
+        fflush(stdout);
+    }
+    return 0;
+}
+
+static int run_bf16() {
+    const size_t n = 1ull << 29, pitch = 2 * GiB + 2 * MiB;
+    char *base = arena(pitch * 5);
+    float *th = (float *)base, *m = (float *)(base + pitch + 32768), *v = (float *)(base + 2 * pitch + 32768);
+    void *g0 = base + 3 * pitch, *g1 = base + 4 * pitch;
+    const unsigned nb = (unsigned)(n / 256);
+    printf("fused pass shape (read theta, m, v, g0, g1; write theta, m, v), n = %zu\n", n);
+    line("fp32 gradients, 128-bit accesses (32 B/element)", gbps([&] { k_fused<0><<<nb, 64>>>(th, m, v, g0, g1, n); }, 32.0 * n));
+    line("bf16 gradients, one 64-bit access per lane (28 B/element)  [the engine's]", gbps([&] { k_fused<1><<<nb, 64>>>(th, m, v, g0, g1, n); }, 28.0 * n));
+    line("bf16 gradients, 128-bit accesses by half the lanes + cross-lane hand-over", gbps([&] { k_fused<2><<<nb, 64>>>(th, m, v, g0, g1, n); }, 28.0 * n));
+    return 0;
+}
+
+int main(int argc, char **argv) {
+    const char *what = argc > 1 ? argv[1] : "";
+    if (!strcmp(what, "shape")) return run_shape();
+    if (!strcmp(what, "policy")) return run_policy();
+    if (!strcmp(what, "phase")) return run_phase();
+    if (!strcmp(what, "ranks")) return run_ranks();
+    if (!strcmp(what, "bf16")) return run_bf16();
+    printf("usage: hbm_probe shape | policy | phase | ranks | bf16\n");
+    return 2;
+}

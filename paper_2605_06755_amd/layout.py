@@ -53,7 +53,7 @@ def last_placement() -> dict:
 
 def alloc_engine_state(numel: int, device, *, adam: bool = True, model_copy: bool = False, grad_dtype=torch.float32,
                        n_grad_buffers: int = 3, arena: bool = False, phases_kib=None, placement: str = "auto",
-                       with_probe: bool = True, verbose: bool = False):
+                       with_probe: bool = True, probe_is_read: bool = False, verbose: bool = False):
     """Flat buffers for one engine context in the fast layout: a dict with
     theta, theta_probe, (m, v), (model_copy) and a list of gradient buffers.
 
@@ -62,6 +62,9 @@ def alloc_engine_state(numel: int, device, *, adam: bool = True, model_copy: boo
     phase rule only; "auto" = ranked for workloads of 8 GiB and more where the
     API is available, phased otherwise.  `last_placement()` tells which one
     the most recent call used.
+    `probe_is_read`: the schedule reads theta_probe back (unfused second fast
+    step, explicit lookahead), so it is placed with the read streams; with
+    the fused schedule the engine only ever writes it.
     `phases_kib` overrides the phases for experiments: a dict name -> KiB
     (names theta, theta_probe, m, v, model_copy, g0, g1, g2)."""
     if arena:
@@ -75,7 +78,8 @@ def alloc_engine_state(numel: int, device, *, adam: bool = True, model_copy: boo
         total = numel * (4 * (1 + int(with_probe) + 2 * int(adam)) + 2 * int(model_copy) + gs * n_grad_buffers)
         if placement == "ranked" or total >= RANKED_MIN_BYTES:
             try:
-                return _alloc_ranked(numel, device, adam, model_copy, grad_dtype, n_grad_buffers, phases_kib, with_probe, verbose)
+                return _alloc_ranked(numel, device, adam, model_copy, grad_dtype, n_grad_buffers, phases_kib, with_probe,
+                                     probe_is_read, verbose)
             except ArenaUnavailable as e:
                 if placement == "ranked":
                     raise
@@ -95,7 +99,7 @@ def alloc_engine_state(numel: int, device, *, adam: bool = True, model_copy: boo
     return out, grads
 
 
-def _alloc_ranked(numel, device, adam, model_copy, grad_dtype, n_grad_buffers, phases_kib, with_probe, verbose):
+def _alloc_ranked(numel, device, adam, model_copy, grad_dtype, n_grad_buffers, phases_kib, with_probe, probe_is_read, verbose):
     """All buffers from one RankedArena: slab by slab, theta, m, v and the gradients share a rank;
     theta_probe and the bf16 copy (only ever written by the engine) come from another."""
     ph = {"theta": 0, "theta_probe": 0, "m": MOMENT_PHASE_BYTES // 1024, "v": MOMENT_PHASE_BYTES // 1024, "model_copy": 0}
@@ -106,7 +110,8 @@ def _alloc_ranked(numel, device, adam, model_copy, grad_dtype, n_grad_buffers, p
     specs += [dict(name=f"g{i}", numel=numel, dtype=grad_dtype, group="read", phase_bytes=ph.get(f"g{i}", 0) * 1024)
               for i in range(n_grad_buffers)]
     if with_probe:
-        specs.append(dict(name="theta_probe", numel=numel, dtype=torch.float32, group="write", phase_bytes=ph["theta_probe"] * 1024))
+        specs.append(dict(name="theta_probe", numel=numel, dtype=torch.float32, group="read" if probe_is_read else "write",
+                          phase_bytes=ph["theta_probe"] * 1024))
     if model_copy:
         specs.append(dict(name="model_copy", numel=numel, dtype=torch.bfloat16, group="write", phase_bytes=ph["model_copy"] * 1024))
     cb = CHUNK_BYTES

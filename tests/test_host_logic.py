@@ -233,6 +233,35 @@ def test_host_gate_hand_case_and_nan():
     assert info.tripped == 1 and info.s_star == 1 and info.evaluated == 0
 
 
+def test_gate_min_count_2_is_the_printed_algorithm_and_trips_on_an_early_spike():
+    """Algorithm 1 evaluates the rule as soon as the buffer holds more than one norm.  With gate_min_count = 2 a
+    spike at t = 2 (third step, two norms in the buffer) trips the gate: s* = 3 and, over T = 20 steps, 3 s* + (T - s*)
+    backward passes.  With the default (the text's warm-up: evaluate once w norms are there) the same spike goes
+    unseen and later steps judge against a buffer that holds it.  Oracle and library must agree on both readings."""
+    norms = [1.00, 1.02, 5.00] + [1.0 + 0.01 * ((7 * i) % 5) for i in range(17)]
+    T, w = len(norms), 10
+    for min_count, want_s_star in ((2, 3), (0, None)):
+        cfg = B.make_config(window=w, gate_min_count=min_count, tau=3.0, gate_eps=1e-8)
+        st = B.new_state()
+        orc = O.RollingGate(O.GateConfig(tau=3.0, window=w, eps=1e-8, min_count=(min_count or None)))
+        passes = 0
+        for t, x in enumerate(norms):
+            active = st.s_star < 0 or st.t < st.s_star
+            passes += 3 if active else 1
+            if not active:
+                st.t += 1                                    # what gxpo_fallback_step does to the step counter
+                continue
+            info = B.gxpo_host_gate_step(cfg, st, x)
+            ref = orc.step(t, x)
+            assert bool(info.evaluated) == ref.evaluated == (t >= (min_count or w))
+            assert (info.s_star if info.s_star >= 0 else None) == ref.s_star
+            if t == 2 and min_count == 2:
+                assert info.tripped == 1 and info.z == pytest.approx((5.0 - 1.01) / (0.01 + 1e-8))
+        assert (st.s_star if st.s_star >= 0 else None) == want_s_star
+        s = want_s_star if want_s_star is not None else T
+        assert passes == 3 * s + (T - s)
+
+
 # ---- the product path fails loudly instead of falling back ------------------------------------------
 def test_bench_refuses_more_than_one_gpu_and_a_missing_gpu():
     import subprocess
@@ -271,5 +300,5 @@ def test_product_code_never_touches_the_oracle():
                     assert not re.search(r"^\s*(from|import)\s+oracle|gxpo_oracle", text, flags=re.M), f"{f} reaches into oracle/"
     bench = open(os.path.join(ROOT, "bench.py")).read()
     uses = [i for i, line in enumerate(bench.splitlines()) if "from oracle" in line or "import oracle" in line]
-    start = bench.splitlines().index("def time_oracle(spec, cfg, inputs, S):")
+    start = bench.splitlines().index("def time_oracle(inputs):")
     assert uses and all(i > start for i in uses), "bench.py may import the oracle only inside its CPU-baseline leg"
