@@ -80,10 +80,12 @@ def alloc_engine_state(numel: int, device, *, adam: bool = True, model_copy: boo
             try:
                 return _alloc_ranked(numel, device, adam, model_copy, grad_dtype, n_grad_buffers, phases_kib, with_probe,
                                      probe_is_read, verbose)
-            except ArenaUnavailable as e:
+            except Exception as e:          # the virtual-memory API refused, or the placement probe failed
                 if placement == "ranked":
                     raise
-                print(f"[layout] rank-aware placement not available ({e}); using plain phased allocations", file=sys.stderr)
+                print(f"[layout] rank-aware placement not available ({type(e).__name__}: {e}); using plain phased allocations",
+                      file=sys.stderr)
+                torch.cuda.empty_cache()
     ph = {"theta": 0, "theta_probe": 0, "m": MOMENT_PHASE_BYTES // 1024, "v": MOMENT_PHASE_BYTES // 1024, "model_copy": 0}
     ph.update(phases_kib or {})
     out = {"theta": alloc_phased(numel, torch.float32, device, ph["theta"] * 1024),

@@ -54,7 +54,11 @@ def full_size_durations(d: str):
     for r in csv.DictReader(open(one(os.path.join(d, "**", "*_kernel_trace.csv")))):
         if "gxpo" in r["Kernel_Name"]:
             per[short(r["Kernel_Name"])].append((int(r["Grid_Size_X"]), (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e6))
+    GRID.update({k: max(g for g, _ in v) for k, v in per.items()})
     return {k: [ms for g, ms in v if g == max(g for g, _ in v)] for k, v in per.items()}
+
+
+GRID = {}          # kernel name -> largest grid it was launched on (tells the workload's kernels from the placement probe's)
 
 
 def full_size_counter(d: str, counter: str):
@@ -62,13 +66,16 @@ def full_size_counter(d: str, counter: str):
     for r in csv.DictReader(open(one(os.path.join(d, "**", "*_counter_collection.csv")))):
         if r["Counter_Name"] == counter and "gxpo" in r["Kernel_Name"]:
             per[short(r["Kernel_Name"])].append((int(r["Grid_Size"]), float(r["Counter_Value"])))
+    GRID.update({k: max(g for g, _ in v) for k, v in per.items()})
     return {k: [x for g, x in v if g == max(g for g, _ in v)] for k, v in per.items()}
 
 
 def kernel_of(call: str, names):
+    """The kernel instantiation that serves `call` in this workload: of the matching names the one launched on the largest
+    grid (the placement probe launches k_optim_step's fp32 instantiation on small windows whatever the workload's dtype)."""
     want = "k_fused_steps_extrapolate" if call.startswith("fused") else ("k_extrapolate" if call == "extrapolate" else "k_optim_step")
     hits = [n for n in names if want in n]
-    return hits[0] if hits else None
+    return max(hits, key=lambda n: GRID.get(n, 0)) if hits else None
 
 
 def main(argv):
