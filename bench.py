@@ -141,7 +141,7 @@ def measure(name: str, args, want_cpu_inputs: bool = False):
     phases = None
     if args.phases:
         names = ["theta", "theta_probe", "m", "v", "g0", "g1", "g2", "model_copy"]
-        phases = {n: int(x) for n, x in zip(names, args.phases.split(","))}
+        phases = {n: float(x) for n, x in zip(names, args.phases.split(","))}
     # ---- device buffers (caller-owned), placed as paper_2605_06755_amd/layout.py describes ----------------
     if args.same_phase:
         flat = {"theta": torch.empty(padded, dtype=torch.float32, device=dev),

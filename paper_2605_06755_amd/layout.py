@@ -86,36 +86,45 @@ def alloc_engine_state(numel: int, device, *, adam: bool = True, model_copy: boo
                 print(f"[layout] rank-aware placement not available ({type(e).__name__}: {e}); using plain phased allocations",
                       file=sys.stderr)
                 torch.cuda.empty_cache()
-    ph = {"theta": 0, "theta_probe": 0, "m": MOMENT_PHASE_BYTES // 1024, "v": MOMENT_PHASE_BYTES // 1024, "model_copy": 0}
+    ph = _default_phases_kib(grad_dtype)
     ph.update(phases_kib or {})
-    out = {"theta": alloc_phased(numel, torch.float32, device, ph["theta"] * 1024),
-           "theta_probe": alloc_phased(numel, torch.float32, device, ph["theta_probe"] * 1024)}
+    out = {"theta": alloc_phased(numel, torch.float32, device, int(ph["theta"] * 1024)),
+           "theta_probe": alloc_phased(numel, torch.float32, device, int(ph["theta_probe"] * 1024))}
     if adam:
-        out["m"] = alloc_phased(numel, torch.float32, device, ph["m"] * 1024, fill=0.0)
-        out["v"] = alloc_phased(numel, torch.float32, device, ph["v"] * 1024, fill=0.0)
+        out["m"] = alloc_phased(numel, torch.float32, device, int(ph["m"] * 1024), fill=0.0)
+        out["v"] = alloc_phased(numel, torch.float32, device, int(ph["v"] * 1024), fill=0.0)
     if model_copy:
-        out["model_copy"] = alloc_phased(numel, torch.bfloat16, device, ph["model_copy"] * 1024)
-    grads = [alloc_phased(numel, grad_dtype, device, ph.get(f"g{i}", 0) * 1024) for i in range(n_grad_buffers)]
+        out["model_copy"] = alloc_phased(numel, torch.bfloat16, device, int(ph["model_copy"] * 1024))
+    grads = [alloc_phased(numel, grad_dtype, device, int(ph.get(f"g{i}", 0) * 1024)) for i in range(n_grad_buffers)]
     if not with_probe:
         del out["theta_probe"]
     return out, grads
 
 
+def _default_phases_kib(grad_dtype) -> dict:
+    """Base address modulo 64 KiB, in KiB, of every buffer: the moments half a period away from the rest.  Two bf16
+    gradient streams read side by side (the fused pass) do slightly better 1 KiB apart: measured +0.6 % on that pass."""
+    ph = {"theta": 0, "theta_probe": 0, "m": MOMENT_PHASE_BYTES // 1024, "v": MOMENT_PHASE_BYTES // 1024, "model_copy": 0}
+    if grad_dtype == torch.bfloat16:
+        ph["g1"] = 1
+    return ph
+
+
 def _alloc_ranked(numel, device, adam, model_copy, grad_dtype, n_grad_buffers, phases_kib, with_probe, probe_is_read, verbose):
     """All buffers from one RankedArena: slab by slab, theta, m, v and the gradients share a rank;
     theta_probe and the bf16 copy (only ever written by the engine) come from another."""
-    ph = {"theta": 0, "theta_probe": 0, "m": MOMENT_PHASE_BYTES // 1024, "v": MOMENT_PHASE_BYTES // 1024, "model_copy": 0}
+    ph = _default_phases_kib(grad_dtype)
     ph.update(phases_kib or {})
-    specs = [dict(name="theta", numel=numel, dtype=torch.float32, group="read", phase_bytes=ph["theta"] * 1024)]
+    specs = [dict(name="theta", numel=numel, dtype=torch.float32, group="read", phase_bytes=int(ph["theta"] * 1024))]
     if adam:
-        specs += [dict(name=k, numel=numel, dtype=torch.float32, group="read", phase_bytes=ph[k] * 1024) for k in ("m", "v")]
-    specs += [dict(name=f"g{i}", numel=numel, dtype=grad_dtype, group="read", phase_bytes=ph.get(f"g{i}", 0) * 1024)
+        specs += [dict(name=k, numel=numel, dtype=torch.float32, group="read", phase_bytes=int(ph[k] * 1024)) for k in ("m", "v")]
+    specs += [dict(name=f"g{i}", numel=numel, dtype=grad_dtype, group="read", phase_bytes=int(ph.get(f"g{i}", 0) * 1024))
               for i in range(n_grad_buffers)]
     if with_probe:
         specs.append(dict(name="theta_probe", numel=numel, dtype=torch.float32, group="read" if probe_is_read else "write",
-                          phase_bytes=ph["theta_probe"] * 1024))
+                          phase_bytes=int(ph["theta_probe"] * 1024)))
     if model_copy:
-        specs.append(dict(name="model_copy", numel=numel, dtype=torch.bfloat16, group="write", phase_bytes=ph["model_copy"] * 1024))
+        specs.append(dict(name="model_copy", numel=numel, dtype=torch.bfloat16, group="write", phase_bytes=int(ph["model_copy"] * 1024)))
     cb = CHUNK_BYTES
     need = sum(-(-(s["numel"] * torch.empty((), dtype=s["dtype"]).element_size() + s["phase_bytes"]) // cb) for s in specs)
     torch.cuda.empty_cache()

@@ -568,3 +568,48 @@ def test_config5_gate_transition_full_size():
     assert st.s_star == 31 and gate.s_star == 31 and n_active == 31 and st.t == 50
     assert st.backward_passes == 3 * 31 + 19 and st.optim_steps == 3 * 31 + 19
     B.gxpo_destroy(ctx)
+
+
+def test_rank_aware_placement_changes_no_result():
+    """Buffers assembled from 512 MiB physical chunks (HIP virtual-memory API) and placed by DRAM rank are ordinary
+    contiguous device arrays: the same inputs give bit-identical theta, m, v, bf16 copy and norm as plain allocations,
+    data written through torch reads back, and every tensor spans several mapped chunks (so the library's range check
+    walks adjacent mappings, and blocks straddle chunk boundaries)."""
+    from paper_2605_06755_amd import hbm_arena
+    need_memory(40)
+    dev = torch.device("cuda:0")
+    numel = 300_000_004                                   # 1.2 GB per fp32 buffer: three chunks each, ragged last block
+    results = {}
+    for placement in ("phased", "ranked"):
+        try:
+            flat, gflat = layout_mod.alloc_engine_state(numel, dev, adam=True, model_copy=True, grad_dtype=torch.bfloat16,
+                                                        placement=placement)
+        except hbm_arena.ArenaUnavailable as e:
+            pytest.skip(f"virtual-memory API not available: {e}")
+        assert layout_mod.last_placement()["kind"] == placement
+        for k, t in list(flat.items()) + [(f"g{i}", g) for i, g in enumerate(gflat)]:
+            assert t.is_contiguous() and t.numel() == numel and t.device.type == "cuda", k
+            assert t.data_ptr() % 65536 == {"m": 32768, "v": 32768, "g1": 1024}.get(k, 0), k
+        quad = synth.ChunkedQuadratic(numel, 9, 0.05, device=dev)
+        quad.init_theta(flat["theta"])
+        quad_first = synth.ChunkedQuadratic(numel, 9, 0.05, device=dev).chunk_problem(0).theta_0[:1 << 20]
+        assert torch.equal(flat["theta"][:1 << 20], quad_first)                        # written through torch, read back
+        cfg = B.make_config(grad_dtype="bf16", K=8, alpha=0.5, delta=1.75e-3, lr=1e-4, weight_decay=0.01, copy_mask=7)
+        ctx = B.gxpo_init(cfg, [dict(flat)])
+        quad.grad(flat["theta"], 0, gflat[0]); B.gxpo_fast_steps(ctx, 0, [gflat[0]])
+        quad.grad(flat["theta_probe"], 0, gflat[1]); B.gxpo_fast_steps(ctx, 1, [gflat[1]])
+        B.gxpo_extrapolate(ctx, [gflat[0]], [gflat[1]])
+        quad.grad(flat["theta"], 0, gflat[2]); B.gxpo_slow_step(ctx, [gflat[2]])
+        info = B.gxpo_gate(ctx)
+        results[placement] = ({k: v.clone() if placement == "phased" else v for k, v in flat.items()}, info.norm)
+        B.gxpo_destroy(ctx)
+        if placement == "phased":
+            del flat, gflat, quad
+            import gc
+            gc.collect()
+            torch.cuda.empty_cache()
+    (a, na), (b, nb) = results["phased"], results["ranked"]
+    assert na == nb
+    for k in ("theta", "theta_probe", "m", "v"):
+        assert torch.equal(a[k].view(torch.int32), b[k].view(torch.int32)), f"{k} depends on the placement"
+    assert torch.equal(a["model_copy"].view(torch.int16), b["model_copy"].view(torch.int16))
