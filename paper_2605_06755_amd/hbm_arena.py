@@ -91,6 +91,55 @@ class _View:
 _TYPESTR = {torch.float32: ("<f4", 4), torch.bfloat16: (None, 2), torch.uint8: ("|u1", 1), torch.int16: ("<i2", 2)}
 
 
+def plan_chunks(labels: Sequence[int], specs: Sequence[dict], chunk_bytes: int = CHUNK_BYTES, available: Optional[Sequence[int]] = None):
+    """Which chunk backs which part of which buffer.  Pure bookkeeping (no GPU): `labels[i]` is the rank class of chunk
+    i, `specs` are dicts with name, numel, itemsize, group ('read' or 'write') and optionally phase_bytes; all buffers
+    index the same elements.  Per slab of SLAB_ELEMS elements the chunks of every 'read' buffer come from one class
+    (the planner stays in a class while it has room for a whole slab, then moves to the class with most room); 'write'
+    buffers are served afterwards from what is left, from another class than their slab's where possible.  Chunks are
+    handed out in index order within a class.  Returns (name -> chunk ids in address order, class of each slab)."""
+    free: Dict[int, List[int]] = {}
+    for i in (range(len(labels)) if available is None else available):
+        free.setdefault(labels[i], []).append(i)
+    for lst in free.values():
+        lst.sort(reverse=True)                             # pop() hands chunks out in creation order
+    per_slab = {s["name"]: max(1, SLAB_ELEMS * s["itemsize"] // chunk_bytes) for s in specs}
+    need = {s["name"]: -(-(s["numel"] * s["itemsize"] + s.get("phase_bytes", 0)) // chunk_bytes) for s in specs}
+    n_slabs = max(-(-need[s["name"]] // per_slab[s["name"]]) for s in specs)
+    plan = {s["name"]: [] for s in specs}
+    wants = lambda s, slab: max(0, min(per_slab[s["name"]], need[s["name"]] - slab * per_slab[s["name"]]))
+
+    def take(label_order, count):
+        out = []
+        for lab in label_order:
+            while free.get(lab) and len(out) < count:
+                out.append(free[lab].pop())
+            if len(out) == count:
+                break
+        if len(out) < count:
+            raise ArenaUnavailable("not enough chunks for the requested buffers")
+        return out
+
+    room = lambda: sorted(free, key=lambda lab: (-len(free[lab]), lab))
+    slab_rank, current = [], None
+    for slab in range(n_slabs):
+        read_need = sum(wants(s, slab) for s in specs if s["group"] == "read")
+        if current is None or len(free.get(current, [])) < read_need:
+            fits = [lab for lab in room() if len(free[lab]) >= read_need]
+            current = fits[0] if fits else room()[0]
+        slab_rank.append(current)
+        order = [current] + [lab for lab in room() if lab != current]
+        for s in specs:
+            if s["group"] == "read" and wants(s, slab):
+                plan[s["name"]] += take(order, wants(s, slab))
+    for slab in range(n_slabs):
+        order = [lab for lab in room() if lab != slab_rank[slab]] + [slab_rank[slab]]
+        for s in specs:
+            if s["group"] != "read" and wants(s, slab):
+                plan[s["name"]] += take(order, wants(s, slab))
+    return plan, slab_rank
+
+
 class RankedArena:
     """Physical chunks of one GPU's HBM, labelled by rank, and the buffers mapped from them."""
 
@@ -233,49 +282,10 @@ class RankedArena:
         if not self.labels:
             raise ArenaUnavailable("classify() has not run")
         cb = self.chunk_bytes
-        free: Dict[int, List[int]] = {}
-        for i, lab in enumerate(self.labels):
-            if self.handles[i] is not None:
-                free.setdefault(lab, []).append(i)
-        for lst in free.values():
-            lst.reverse()                                  # pop() hands chunks out in creation order
-        esize = lambda s: torch.empty((), dtype=s["dtype"]).element_size()
-        per_slab = {s["name"]: SLAB_ELEMS * esize(s) // cb for s in specs}
-        need_chunks = {s["name"]: -(-(s["numel"] * esize(s) + s.get("phase_bytes", 0)) // cb) for s in specs}
-        n_slabs = max(-(-need_chunks[s["name"]] // per_slab[s["name"]]) for s in specs)
-        plan = {s["name"]: [] for s in specs}               # chunk ids in address order
-        wants = lambda s, slab: max(0, min(per_slab[s["name"]], need_chunks[s["name"]] - slab * per_slab[s["name"]]))
-
-        def take(label_order, count):
-            out = []
-            for lab in label_order:
-                while free.get(lab) and len(out) < count:
-                    out.append(free[lab].pop())
-                if len(out) == count:
-                    break
-            if len(out) < count:
-                raise ArenaUnavailable("not enough chunks for the requested buffers")
-            return out
-
-        room = lambda: sorted(free, key=lambda lab: -len(free[lab]))
-        # first the streams that are read together: one rank per slab, staying in a rank while it has room
-        self.slab_rank, current = [], None
-        for slab in range(n_slabs):
-            read_need = sum(wants(s, slab) for s in specs if s["group"] == "read")
-            if current is None or len(free.get(current, [])) < read_need:
-                fits = [lab for lab in room() if len(free[lab]) >= read_need]
-                current = fits[0] if fits else room()[0]
-            self.slab_rank.append(current)
-            order = [current] + [lab for lab in room() if lab != current]
-            for s in specs:
-                if s["group"] == "read" and wants(s, slab):
-                    plan[s["name"]] += take(order, wants(s, slab))
-        # then the write-only streams, from what is left, away from the rank their slab is read from
-        for slab in range(n_slabs):
-            order = [lab for lab in room() if lab != self.slab_rank[slab]] + [self.slab_rank[slab]]
-            for s in specs:
-                if s["group"] != "read" and wants(s, slab):
-                    plan[s["name"]] += take(order, wants(s, slab))
+        available = [i for i, h in enumerate(self.handles) if h is not None]
+        plan, self.slab_rank = plan_chunks(self.labels, [dict(s, itemsize=torch.empty((), dtype=s["dtype"]).element_size()) for s in specs],
+                                           cb, available)
+        need_chunks = {name: len(chunks) for name, chunks in plan.items()}
         out = {}
         for s in specs:
             chunks = plan[s["name"]]

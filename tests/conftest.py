@@ -16,7 +16,7 @@ def _needs_library(path) -> bool:
         text = path.read_text()
     except OSError:
         return False
-    return "import binding" in text or "gxpo_harness" in text or "abi_driver" in text
+    return "import binding" in text or "gxpo_harness" in text or "abi_driver" in text or "hbm_arena" in text
 
 
 def _library_error():

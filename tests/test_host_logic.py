@@ -302,3 +302,65 @@ def test_product_code_never_touches_the_oracle():
     uses = [i for i, line in enumerate(bench.splitlines()) if "from oracle" in line or "import oracle" in line]
     start = bench.splitlines().index("def time_oracle(inputs):")
     assert uses and all(i > start for i in uses), "bench.py may import the oracle only inside its CPU-baseline leg"
+
+
+# ---- rank-aware placement: the chunk plan (pure bookkeeping, no GPU) --------------------------------
+def _plan_specs(numel, grad_itemsize=4, copy=True):
+    specs = [dict(name=k, numel=numel, itemsize=4, group="read", phase_bytes=ph) for k, ph in (("theta", 0), ("m", 32768), ("v", 32768))]
+    specs += [dict(name=f"g{i}", numel=numel, itemsize=grad_itemsize, group="read", phase_bytes=0) for i in range(3)]
+    specs.append(dict(name="theta_probe", numel=numel, itemsize=4, group="write", phase_bytes=0))
+    if copy:
+        specs.append(dict(name="model_copy", numel=numel, itemsize=2, group="write", phase_bytes=0))
+    return specs
+
+
+@pytest.mark.parametrize("numel,grad_itemsize,copy", [(7_600_000_000, 4, True), (8_030_257_152, 2, False), (3_200_000_000, 4, False),
+                                                       (300_000_004, 2, True)])
+def test_chunk_plan_keeps_the_read_streams_of_a_slab_in_one_rank(numel, grad_itemsize, copy):
+    from paper_2605_06755_amd import hbm_arena as A
+    cb = A.CHUNK_BYTES
+    specs = _plan_specs(numel, grad_itemsize, copy)
+    need = sum(-(-(s["numel"] * s["itemsize"] + s["phase_bytes"]) // cb) for s in specs)
+    # three ranks of 96 GiB, handed out the way a large allocation was seen to be: runs of chunks per rank, plus a few strays
+    rng = np.random.default_rng(numel % 1000)
+    labels = [0] * 128 + [1] * 192 + [2] * 64 + [0] * 64 + [2] * 100 + [3, 4]
+    order = list(range(len(labels)))
+    assert len(labels) >= need
+    plan, slab_rank = A.plan_chunks(labels, specs, cb)
+    used = [c for chunks in plan.values() for c in chunks]
+    assert len(used) == len(set(used)) == need                            # every chunk at most once, every byte backed
+    for s in specs:
+        assert len(plan[s["name"]]) == -(-(s["numel"] * s["itemsize"] + s["phase_bytes"]) // cb)
+    # per slab, all read buffers' chunks carry the slab's label (the pools are large enough here for that to hold throughout)
+    for s in specs:
+        per = max(1, A.SLAB_ELEMS * s["itemsize"] // cb)
+        for k, c in enumerate(plan[s["name"]]):
+            slab = k // per
+            if s["group"] == "read":
+                assert labels[c] == slab_rank[slab], (s["name"], k)
+    # the write-only buffers avoid their slab's rank as long as another rank has chunks left
+    wrong = sum(labels[c] == slab_rank[k // max(1, A.SLAB_ELEMS * s["itemsize"] // cb)]
+                for s in specs if s["group"] == "write" for k, c in enumerate(plan[s["name"]]))
+    assert wrong == 0
+    # few changes of rank along the buffer: the planner stays in a rank while it has room
+    assert sum(a != b for a, b in zip(slab_rank, slab_rank[1:])) <= 2
+    # chunks of a class are handed out in index order
+    for s in specs:
+        by_label = {}
+        for c in plan[s["name"]]:
+            by_label.setdefault(labels[c], []).append(c)
+        assert all(v == sorted(v) for v in by_label.values())
+
+
+def test_chunk_plan_spills_and_refuses():
+    from paper_2605_06755_amd import hbm_arena as A
+    cb = A.CHUNK_BYTES
+    specs = _plan_specs((1 << 28) - (1 << 16), 4, copy=False)    # one slab: 2 chunks per fp32 buffer (phases included), 14 in all
+    # no single class holds the 12 read chunks: the slab spills over classes instead of failing
+    plan, slab_rank = A.plan_chunks([0] * 8 + [1] * 8, specs, cb)
+    assert sum(len(v) for v in plan.values()) == 14 and len(slab_rank) == 1
+    with pytest.raises(A.ArenaUnavailable):
+        A.plan_chunks([0] * 13, specs, cb)
+    # only the listed chunks may be used
+    plan, _ = A.plan_chunks([0] * 40, specs, cb, available=list(range(20, 40)))
+    assert min(c for v in plan.values() for c in v) >= 20
