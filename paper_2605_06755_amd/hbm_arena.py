@@ -88,7 +88,7 @@ class _View:
         self.__cuda_array_interface__ = {"shape": (numel,), "typestr": typestr, "data": (ptr, False), "version": 3, "strides": None}
 
 
-_TYPESTR = {torch.float32: ("<f4", 4), torch.bfloat16: (None, 2), torch.uint8: ("|u1", 1), torch.int16: ("<i2", 2)}
+_TYPESTR = {torch.float32: "<f4", torch.uint8: "|u1", torch.int16: "<i2"}
 
 
 def plan_chunks(labels: Sequence[int], specs: Sequence[dict], chunk_bytes: int = CHUNK_BYTES, available: Optional[Sequence[int]] = None):
@@ -152,7 +152,6 @@ class RankedArena:
         self.labels: List[int] = []
         self._ranges = []                        # (va, bytes) reserved
         self._mapped = []                        # (va, bytes) mapped, one per chunk
-        self._scan_va = None
         self._closed = False
         prop = _Prop()
         prop.type = _HIP_MEM_ALLOCATION_TYPE_PINNED
@@ -193,7 +192,7 @@ class RankedArena:
     def _tensor(self, ptr: int, numel: int, dtype) -> torch.Tensor:
         if dtype == torch.bfloat16:          # the array interface has no bf16: wrap as int16, reinterpret
             return torch.as_tensor(_View(self, ptr, numel, "<i2"), device=self.device).view(torch.bfloat16)
-        return torch.as_tensor(_View(self, ptr, numel, _TYPESTR[dtype][0]), device=self.device)
+        return torch.as_tensor(_View(self, ptr, numel, _TYPESTR[dtype]), device=self.device)
 
     # ---- which chunks share a rank ----------------------------------------------------------------
     def classify(self, verbose: bool = False) -> List[int]:
