@@ -91,29 +91,58 @@ class _View:
 _TYPESTR = {torch.float32: "<f4", torch.uint8: "|u1", torch.int16: "<i2"}
 
 
-def plan_chunks(labels: Sequence[int], specs: Sequence[dict], chunk_bytes: int = CHUNK_BYTES, available: Optional[Sequence[int]] = None):
+def _scatter(chunks: List[int], seed: int) -> List[int]:
+    """A fixed pseudo-random order of `chunks` (Fisher-Yates driven by a 64-bit LCG): the same plan for the same labels."""
+    out, x = list(chunks), (seed * 0x9E3779B97F4A7C15 + 0xD1B54A32D192ED03) & (2 ** 64 - 1)
+    for i in range(len(out) - 1, 0, -1):
+        x = (x * 6364136223846793005 + 1442695040888963407) & (2 ** 64 - 1)
+        j = (x >> 33) % (i + 1)
+        out[i], out[j] = out[j], out[i]
+    return out
+
+
+def plan_chunks(labels: Sequence[int], specs: Sequence[dict], chunk_bytes: int = CHUNK_BYTES, available: Optional[Sequence[int]] = None,
+                scatter: bool = True):
     """Which chunk backs which part of which buffer.  Pure bookkeeping (no GPU): `labels[i]` is the rank class of chunk
     i, `specs` are dicts with name, numel, itemsize, group ('read' or 'write') and optionally phase_bytes; all buffers
     index the same elements.  Per slab of SLAB_ELEMS elements the chunks of every 'read' buffer come from one class
     (the planner stays in a class while it has room for a whole slab, then moves to the class with most room); 'write'
-    buffers are served afterwards from what is left, from another class than their slab's where possible.  Chunks are
-    handed out in index order within a class.  Returns (name -> chunk ids in address order, class of each slab)."""
+    buffers are served afterwards from what is left, from another class than their slab's where possible.
+    Inside a class the chunks are handed out in a fixed pseudo-random order (`scatter`) rather than in index order:
+    streams that advance in step through neighbouring or evenly spaced chunks of physical memory were measured
+    0.5-1.5 % slower than streams whose chunks have no regular relation to each other.
+    Returns (name -> chunk ids in address order, class of each slab)."""
     free: Dict[int, List[int]] = {}
     for i in (range(len(labels)) if available is None else available):
         free.setdefault(labels[i], []).append(i)
-    for lst in free.values():
-        lst.sort(reverse=True)                             # pop() hands chunks out in creation order
+    for lab in free:
+        free[lab] = _scatter(sorted(free[lab]), lab) if scatter else sorted(free[lab])
     per_slab = {s["name"]: max(1, SLAB_ELEMS * s["itemsize"] // chunk_bytes) for s in specs}
     need = {s["name"]: -(-(s["numel"] * s["itemsize"] + s.get("phase_bytes", 0)) // chunk_bytes) for s in specs}
     n_slabs = max(-(-need[s["name"]] // per_slab[s["name"]]) for s in specs)
     plan = {s["name"]: [] for s in specs}
     wants = lambda s, slab: max(0, min(per_slab[s["name"]], need[s["name"]] - slab * per_slab[s["name"]]))
+    reads = [s for s in specs if s["group"] == "read"]
+    writes = [s for s in specs if s["group"] != "read"]
+
+    # 1. which class hosts the read streams of each slab: stay while a whole slab fits, then move to the roomiest class
+    left = {lab: len(lst) for lab, lst in free.items()}
+    roomiest = lambda: sorted(left, key=lambda lab: (-left[lab], lab))
+    slab_rank, current = [], None
+    for slab in range(n_slabs):
+        read_need = sum(wants(s, slab) for s in reads)
+        if current is None or left[current] < read_need:
+            fits = [lab for lab in roomiest() if left[lab] >= read_need]
+            current = fits[0] if fits else None
+        slab_rank.append(current)                          # None: no class can hold this slab's read streams whole
+        if current is not None:
+            left[current] -= read_need
 
     def take(label_order, count):
         out = []
         for lab in label_order:
             while free.get(lab) and len(out) < count:
-                out.append(free[lab].pop())
+                out.append(free[lab].pop(0))
             if len(out) == count:
                 break
         if len(out) < count:
@@ -121,23 +150,25 @@ def plan_chunks(labels: Sequence[int], specs: Sequence[dict], chunk_bytes: int =
         return out
 
     room = lambda: sorted(free, key=lambda lab: (-len(free[lab]), lab))
-    slab_rank, current = [], None
+    # 2. the read streams, slab by slab, from the slab's class; slabs no class could hold whole spill over classes
     for slab in range(n_slabs):
-        read_need = sum(wants(s, slab) for s in specs if s["group"] == "read")
-        if current is None or len(free.get(current, [])) < read_need:
-            fits = [lab for lab in room() if len(free[lab]) >= read_need]
-            current = fits[0] if fits else room()[0]
-        slab_rank.append(current)
-        order = [current] + [lab for lab in room() if lab != current]
-        for s in specs:
-            if s["group"] == "read" and wants(s, slab):
-                plan[s["name"]] += take(order, wants(s, slab))
+        if slab_rank[slab] is None:
+            continue
+        for s in reads:
+            plan[s["name"]] += [(slab, c) for c in take([slab_rank[slab]], wants(s, slab))]
+    for slab in range(n_slabs):
+        if slab_rank[slab] is None:
+            slab_rank[slab] = room()[0]
+            for s in reads:
+                if wants(s, slab):
+                    plan[s["name"]] += [(slab, c) for c in take(room(), wants(s, slab))]
+    # 3. the write-only streams, from what is left, away from the class their slab is read from
     for slab in range(n_slabs):
         order = [lab for lab in room() if lab != slab_rank[slab]] + [slab_rank[slab]]
-        for s in specs:
-            if s["group"] != "read" and wants(s, slab):
-                plan[s["name"]] += take(order, wants(s, slab))
-    return plan, slab_rank
+        for s in writes:
+            if wants(s, slab):
+                plan[s["name"]] += [(slab, c) for c in take(order, wants(s, slab))]
+    return {name: [c for _, c in sorted(v, key=lambda x: x[0])] for name, v in plan.items()}, slab_rank
 
 
 class RankedArena:
@@ -274,7 +305,7 @@ class RankedArena:
         return labels
 
     # ---- buffers ---------------------------------------------------------------------------------------
-    def build(self, specs: Sequence[dict]) -> Dict[str, torch.Tensor]:
+    def build(self, specs: Sequence[dict], scatter: bool = True) -> Dict[str, torch.Tensor]:
         """specs: dicts with name, numel, dtype, phase_bytes, group ('read' or 'write').  All buffers
         index the same elements.  Slab by slab, the chunks of every 'read' buffer come from one rank;
         'write' buffers take theirs from another rank where there is room.  Returns name -> tensor."""
@@ -283,7 +314,7 @@ class RankedArena:
         cb = self.chunk_bytes
         available = [i for i, h in enumerate(self.handles) if h is not None]
         plan, self.slab_rank = plan_chunks(self.labels, [dict(s, itemsize=torch.empty((), dtype=s["dtype"]).element_size()) for s in specs],
-                                           cb, available)
+                                           cb, available, scatter)
         need_chunks = {name: len(chunks) for name, chunks in plan.items()}
         out = {}
         for s in specs:

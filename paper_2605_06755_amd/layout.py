@@ -58,7 +58,8 @@ def alloc_engine_state(numel: int, device, *, adam: bool = True, model_copy: boo
     theta, theta_probe, (m, v), (model_copy) and a list of gradient buffers.
 
     placement: "ranked" = rank-aware placement through HIP's virtual-memory API
-    (hbm_arena.py); "phased" = one plain allocation per buffer with the 64 KiB
+    (hbm_arena.py; "ranked-adjacent" = the same with the chunks of a rank handed
+    out in index order instead of scattered, for comparison); "phased" = one plain allocation per buffer with the 64 KiB
     phase rule only; "auto" = ranked for workloads of 8 GiB and more where the
     API is available, phased otherwise.  `last_placement()` tells which one
     the most recent call used.
@@ -71,17 +72,17 @@ def alloc_engine_state(numel: int, device, *, adam: bool = True, model_copy: boo
         _last_placement.update(kind="arena", detail=None)
         return _alloc_arena(numel, device, adam, model_copy, grad_dtype, n_grad_buffers)
     _last_placement.update(kind="phased", detail=None)
-    if placement not in ("auto", "ranked", "phased"):
+    if placement not in ("auto", "ranked", "ranked-adjacent", "phased"):
         raise ValueError(placement)
     if placement != "phased":
         gs = torch.empty((), dtype=grad_dtype).element_size()
         total = numel * (4 * (1 + int(with_probe) + 2 * int(adam)) + 2 * int(model_copy) + gs * n_grad_buffers)
-        if placement == "ranked" or total >= RANKED_MIN_BYTES:
+        if placement.startswith("ranked") or total >= RANKED_MIN_BYTES:
             try:
                 return _alloc_ranked(numel, device, adam, model_copy, grad_dtype, n_grad_buffers, phases_kib, with_probe,
-                                     probe_is_read, verbose)
+                                     probe_is_read, verbose, scatter=placement != "ranked-adjacent")
             except Exception as e:          # the virtual-memory API refused, or the placement probe failed
-                if placement == "ranked":
+                if placement.startswith("ranked"):
                     raise
                 print(f"[layout] rank-aware placement not available ({type(e).__name__}: {e}); using plain phased allocations",
                       file=sys.stderr)
@@ -110,7 +111,8 @@ def _default_phases_kib(grad_dtype) -> dict:
     return ph
 
 
-def _alloc_ranked(numel, device, adam, model_copy, grad_dtype, n_grad_buffers, phases_kib, with_probe, probe_is_read, verbose):
+def _alloc_ranked(numel, device, adam, model_copy, grad_dtype, n_grad_buffers, phases_kib, with_probe, probe_is_read, verbose,
+                  scatter=True):
     """All buffers from one RankedArena: slab by slab, theta, m, v and the gradients share a rank;
     theta_probe and the bf16 copy (only ever written by the engine) come from another."""
     ph = _default_phases_kib(grad_dtype)
@@ -137,7 +139,7 @@ def _alloc_ranked(numel, device, adam, model_copy, grad_dtype, n_grad_buffers, p
     ar = RankedArena(device, n_chunks)
     try:
         labels = ar.classify(verbose=verbose)
-        bufs = ar.build(specs)
+        bufs = ar.build(specs, scatter=scatter)
     except Exception:
         ar.close()
         raise

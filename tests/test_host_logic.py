@@ -344,12 +344,31 @@ def test_chunk_plan_keeps_the_read_streams_of_a_slab_in_one_rank(numel, grad_ite
     assert wrong == 0
     # few changes of rank along the buffer: the planner stays in a rank while it has room
     assert sum(a != b for a, b in zip(slab_rank, slab_rank[1:])) <= 2
-    # chunks of a class are handed out in index order
+    # without scattering, chunks of a class are handed out in index order; with it, in a fixed other order over the same classes
+    plain, plain_rank = A.plan_chunks(labels, specs, cb, scatter=False)
+    assert plain_rank == slab_rank
     for s in specs:
+        assert [labels[c] for c in plain[s["name"]]] == [labels[c] for c in plan[s["name"]]]
         by_label = {}
-        for c in plan[s["name"]]:
+        for c in plain[s["name"]]:
             by_label.setdefault(labels[c], []).append(c)
         assert all(v == sorted(v) for v in by_label.values())
+    again, _ = A.plan_chunks(labels, specs, cb)
+    assert again == plan                                                   # the scattered order is a function of the labels alone
+    assert any(plan[s["name"]] != plain[s["name"]] for s in specs)
+
+
+def test_scatter_is_a_permutation():
+    from paper_2605_06755_amd import hbm_arena as A
+    for n in (0, 1, 2, 7, 192):
+        for seed in (0, 1, 5):
+            out = A._scatter(list(range(100, 100 + n)), seed)
+            assert sorted(out) == list(range(100, 100 + n))
+    assert A._scatter(list(range(192)), 0) != list(range(192))
+    assert A._scatter(list(range(192)), 0) != A._scatter(list(range(192)), 1)
+    # no regular stride survives: neighbours in the scattered order are rarely neighbours in memory
+    out = A._scatter(list(range(192)), 2)
+    assert sum(abs(a - b) == 1 for a, b in zip(out, out[1:])) < 12
 
 
 def test_chunk_plan_spills_and_refuses():
