@@ -45,7 +45,7 @@ def parse_args():
     ap.add_argument("--unfused", action="store_true", help="run the second fast step and the extrapolation as two passes")
     ap.add_argument("--same-phase", action="store_true", help="plain torch allocations instead of the phased HBM layout")
     ap.add_argument("--arena", action="store_true", help="carve all buffers from one plain allocation")
-    ap.add_argument("--placement", default="auto", choices=["auto", "ranked", "ranked-adjacent", "phased"],
+    ap.add_argument("--placement", default="auto", choices=["auto", "ranked", "ranked-scatter", "ranked-adjacent", "phased"],
                     help="ranked: rank-aware placement through HIP's virtual-memory API; phased: one plain allocation per buffer")
     ap.add_argument("--phases", default="", help="experiment: KiB phases (mod 64) of theta,theta_probe,m,v,g0,g1,g2[,model_copy]")
     ap.add_argument("--no-probe", action="store_true",
@@ -299,7 +299,8 @@ def measure(name: str, args, want_cpu_inputs: bool = False):
                     "frac_of_peak": round(bpp["fallback_step"] * P / fms / 1e6 / HBM_PEAK_GBPS, 4)}
 
     if placement["kind"] == "ranked":
-        hbm_layout = "rank-aware placement (read streams of a slab in one DRAM rank), moments +32KiB mod 64KiB"
+        hbm_layout = "rank-aware placement (read streams of a slab in one DRAM rank" + (
+            ", theta/m/v chunks chosen by measurement" if (placement["detail"] or {}).get("tuned") else "") + "), moments +32KiB mod 64KiB"
     elif placement["kind"] == "same-phase":
         hbm_layout = "same-phase"
     else:

@@ -24,6 +24,7 @@ pointers and knows nothing of this.
 from __future__ import annotations
 
 import ctypes
+import sys
 from typing import Dict, List, Optional, Sequence
 
 import torch
@@ -104,8 +105,9 @@ def _scatter(chunks: List[int], seed: int) -> List[int]:
 def plan_chunks(labels: Sequence[int], specs: Sequence[dict], chunk_bytes: int = CHUNK_BYTES, available: Optional[Sequence[int]] = None,
                 scatter: bool = True):
     """Which chunk backs which part of which buffer.  Pure bookkeeping (no GPU): `labels[i]` is the rank class of chunk
-    i, `specs` are dicts with name, numel, itemsize, group ('read' or 'write') and optionally phase_bytes; all buffers
-    index the same elements.  Per slab of SLAB_ELEMS elements the chunks of every 'read' buffer come from one class
+    i, `specs` are dicts with name, numel, itemsize, group ('update' = read and written, 'read', or 'write') and
+    optionally phase_bytes; all buffers index the same elements.  Per slab of SLAB_ELEMS elements the chunks of every
+    'update' and 'read' buffer come from one class
     (the planner stays in a class while it has room for a whole slab, then moves to the class with most room); 'write'
     buffers are served afterwards from what is left, from another class than their slab's where possible.
     Inside a class the chunks are handed out in a fixed pseudo-random order (`scatter`) rather than in index order:
@@ -122,8 +124,8 @@ def plan_chunks(labels: Sequence[int], specs: Sequence[dict], chunk_bytes: int =
     n_slabs = max(-(-need[s["name"]] // per_slab[s["name"]]) for s in specs)
     plan = {s["name"]: [] for s in specs}
     wants = lambda s, slab: max(0, min(per_slab[s["name"]], need[s["name"]] - slab * per_slab[s["name"]]))
-    reads = [s for s in specs if s["group"] == "read"]
-    writes = [s for s in specs if s["group"] != "read"]
+    reads = [s for s in specs if s["group"] in ("read", "update")]
+    writes = [s for s in specs if s["group"] == "write"]
 
     # 1. which class hosts the read streams of each slab: stay while a whole slab fits, then move to the roomiest class
     left = {lab: len(lst) for lab, lst in free.items()}
@@ -169,6 +171,55 @@ def plan_chunks(labels: Sequence[int], specs: Sequence[dict], chunk_bytes: int =
             if wants(s, slab):
                 plan[s["name"]] += [(slab, c) for c in take(order, wants(s, slab))]
     return {name: [c for _, c in sorted(v, key=lambda x: x[0])] for name, v in plan.items()}, slab_rank
+
+
+def _lcg(seed: int):
+    x = (seed * 0x9E3779B97F4A7C15 + 0xD1B54A32D192ED03) & (2 ** 64 - 1)
+    while True:
+        x = (x * 6364136223846793005 + 1442695040888963407) & (2 ** 64 - 1)
+        yield x >> 33
+
+
+def choose_tuples(pools: Dict[int, List[int]], positions: Sequence[Optional[int]], width: int, candidates: int, measure, seed: int = 0):
+    """Best-of-several choice of chunk tuples, one tuple per position.  Pure bookkeeping around `measure`:
+    `positions[k]` is the class position k draws from (None: leave it alone), `pools[class]` the chunks it may use.
+    For every position up to `candidates` tuples of `width` distinct chunks are drawn from what is left of the pool,
+    `measure(k, tuple)` rates each (higher is better), the best is kept and its chunks leave the pool.  A pool that
+    runs short of `width` chunks is an error: the caller sizes the pools so that every position can be served.
+    Returns (tuples, one per position or None; ratings seen per position)."""
+    rnd = _lcg(seed)
+    left = {lab: list(v) for lab, v in pools.items()}
+    still = {lab: sum(1 for p in positions if p == lab) for lab in left}          # positions yet to serve per class
+    out, seen = [], []
+    for k, lab in enumerate(positions):
+        if lab is None:
+            out.append(None)
+            seen.append([])
+            continue
+        pool = left[lab]
+        if len(pool) < width * still[lab]:
+            raise ArenaUnavailable("pool too small for the positions that draw from it")
+        n_cand = candidates if len(pool) > width else 1
+        best, ratings, tried = None, [], set()
+        for _ in range(n_cand):
+            idx = list(range(len(pool)))
+            for i in range(width):                                                 # partial Fisher-Yates
+                j = i + next(rnd) % (len(idx) - i)
+                idx[i], idx[j] = idx[j], idx[i]
+            tup = tuple(pool[i] for i in idx[:width])
+            if tup in tried:
+                continue
+            tried.add(tup)
+            r = measure(k, tup)
+            ratings.append(r)
+            if best is None or r > best[0]:
+                best = (r, tup)
+        out.append(best[1])
+        seen.append(ratings)
+        for c in best[1]:
+            pool.remove(c)
+        still[lab] -= 1
+    return out, seen
 
 
 class RankedArena:
@@ -293,7 +344,7 @@ class RankedArena:
                 labels[c] = next_label
             if verbose:
                 print(f"[hbm_arena] reference chunk {ref}: {len(same)} of {len(todo)} chunks share its rank "
-                      f"(cluster centres {lo_c:.0f} / {hi_c:.0f} GB/s)", flush=True)
+                      f"(cluster centres {lo_c:.0f} / {hi_c:.0f} GB/s)", file=sys.stderr, flush=True)
             todo = [c for c in todo if labels[c] < 0]
             next_label += 1
         for c in todo:                                      # more clusters than ranks can be: lump the rest together
@@ -305,26 +356,29 @@ class RankedArena:
         return labels
 
     # ---- buffers ---------------------------------------------------------------------------------------
-    def build(self, specs: Sequence[dict], scatter: bool = True) -> Dict[str, torch.Tensor]:
-        """specs: dicts with name, numel, dtype, phase_bytes, group ('read' or 'write').  All buffers
-        index the same elements.  Slab by slab, the chunks of every 'read' buffer come from one rank;
-        'write' buffers take theirs from another rank where there is room.  Returns name -> tensor."""
+    def build(self, specs: Sequence[dict], scatter: bool = True, tune: int = 0, verbose: bool = False) -> Dict[str, torch.Tensor]:
+        """specs: dicts with name, numel, dtype, phase_bytes, group ('update', 'read' or 'write').  All buffers
+        index the same elements.  Slab by slab, the chunks of every 'update' and 'read' buffer come from one rank;
+        'write' buffers take theirs from another rank where there is room.  With `tune` > 0 the chunks of theta, m, v
+        are then chosen by measurement, the best of `tune` candidate triples per chunk position.  Returns name -> tensor."""
         if not self.labels:
             raise ArenaUnavailable("classify() has not run")
         cb = self.chunk_bytes
         available = [i for i, h in enumerate(self.handles) if h is not None]
         plan, self.slab_rank = plan_chunks(self.labels, [dict(s, itemsize=torch.empty((), dtype=s["dtype"]).element_size()) for s in specs],
                                            cb, available, scatter)
-        need_chunks = {name: len(chunks) for name, chunks in plan.items()}
+        self.tuned = None
+        if tune > 0:
+            self._tune_updates(plan, specs, available, tune, verbose)
         out = {}
         for s in specs:
             chunks = plan[s["name"]]
-            assert len(chunks) == need_chunks[s["name"]]
             va = self._reserve(len(chunks) * cb)
             for k, c in enumerate(chunks):
                 self._map(va + k * cb, c)
             out[s["name"]] = self._tensor(va + s.get("phase_bytes", 0), s["numel"], s["dtype"])
         used = {c for chunks in plan.values() for c in chunks}
+        assert sum(len(chunks) for chunks in plan.values()) == len(used)
         hip = _runtime()
         for i, h in enumerate(self.handles):               # give back what the buffers did not need
             if i not in used and h is not None:
@@ -332,6 +386,97 @@ class RankedArena:
                 self.handles[i] = None
         self.plan = plan
         return out
+
+    def _tune_updates(self, plan, specs, available, candidates: int, verbose: bool):
+        """Which three chunks hold theta, m and v of one chunk position decides the pass rate more than anything
+        else inside a rank: triples drawn at random from one rank measured between 75 % and 83.5 % of peak on the
+        fallback step (standard deviation one point), and no rule in the chunk numbers predicts it.  So they are
+        chosen by measurement: per position, `candidates` random triples from the rank's pool (the chunks planned
+        for theta, m, v there plus the spare ones) are timed with the engine's fallback step on windows at the
+        start of the chunks, against the gradient chunk planned for that position, and the best triple is kept.
+        Edits `plan` in place; leaves it alone when the buffers are not the AdamW set."""
+        upd = [s for s in specs if s["group"] == "update"]
+        reads = [s for s in specs if s["group"] == "read"]
+        if [s["name"] for s in upd] != ["theta", "m", "v"] or not reads or any(s["dtype"] != torch.float32 for s in upd) \
+                or any(s.get("phase_bytes", 0) >= 65536 for s in upd + reads[:1]):
+            return
+        cb, labels = self.chunk_bytes, self.labels
+        names = [s["name"] for s in upd]
+        n_pos = min(len(plan[n]) for n in names)
+        used = {c for chunks in plan.values() for c in chunks}
+        pools: Dict[int, List[int]] = {}
+        for c in available:
+            if c not in used:
+                pools.setdefault(labels[c], []).append(c)
+        positions = []
+        for k in range(n_pos):
+            labs = {labels[plan[n][k]] for n in names}
+            lab = labs.pop() if len(labs) == 1 else None
+            positions.append(lab)
+            if lab is not None:
+                pools.setdefault(lab, []).extend(plan[n][k] for n in names)
+        for lab in pools:
+            pools[lab].sort()
+        g_spec = reads[0]
+        g_size = torch.empty((), dtype=g_spec["dtype"]).element_size()
+        E = (cb - 65536) // 4
+        va = self._reserve(len(self.handles) * cb)
+        for c in available:
+            self._map(va + c * cb, c)
+        cfg = _B.make_config(K=2, lr=1e-9, weight_decay=0.0, delta=0.0, grad_dtype="f32" if g_size == 4 else "bf16")
+        cache = {}
+
+        def gradient(k):
+            if cache.get("k") != k:
+                at = k * (cb // 4) * g_size                                      # where position k starts in the gradient buffer
+                chunk = plan[g_spec["name"]][min(at // cb, len(plan[g_spec["name"]]) - 1)]
+                off = min(at % cb, cb - E * g_size)
+                g = self._tensor(va + chunk * cb + off, E, g_spec["dtype"])
+                g.normal_(std=0.05)
+                cache.update(k=k, g=g)
+            return cache["g"]
+
+        def measure(k, tup):
+            th, m, v = (self._tensor(va + c * cb + s.get("phase_bytes", 0), E, torch.float32) for c, s in zip(tup, upd))
+            th.normal_(std=0.02)
+            m.zero_()
+            v.fill_(1e-4)
+            g = gradient(k)
+            ctx = _B.gxpo_init(cfg, [dict(theta=th, m=m, v=v)])
+            st = _B.gxpo_get_state(ctx)
+            st.s_star = 0
+            _B.gxpo_set_state(ctx, st)
+            _B.gxpo_fallback_step(ctx, [g])
+            best = 0.0
+            for _ in range(2):                                                   # disturbances only slow a measurement down
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for _ in range(3):
+                    _B.gxpo_fallback_step(ctx, [g])
+                b.record()
+                b.synchronize()
+                best = max(best, 3 * (24.0 + g_size) * E / a.elapsed_time(b) / 1e6)
+            _B.gxpo_destroy(ctx)
+            return best
+
+        try:
+            tuples, seen = choose_tuples(pools, positions, len(names), candidates, measure)
+        finally:
+            cache.clear()
+            torch.cuda.synchronize(self.device)
+            self._unmap_all()
+        for k, tup in enumerate(tuples):
+            if tup is not None:
+                for n, c in zip(names, tup):
+                    plan[n][k] = c
+        rated = [r for r in seen if r]
+        if rated:
+            self.tuned = {"positions": len(rated), "candidates": candidates,
+                          "mean_gbps": round(sum(sum(r) for r in rated) / sum(len(r) for r in rated)),
+                          "chosen_gbps": round(sum(max(r) for r in rated) / len(rated))}
+            if verbose:
+                print(f"[hbm_arena] theta, m, v chosen by measurement at {len(rated)} chunk positions: candidates average "
+                      f"{self.tuned['mean_gbps']} GB/s on the fallback step, chosen ones {self.tuned['chosen_gbps']} GB/s", file=sys.stderr, flush=True)
 
     def close(self):
         if self._closed:

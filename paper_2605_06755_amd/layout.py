@@ -43,6 +43,7 @@ def alloc_phased(numel: int, dtype, device, phase_bytes: int = 0, fill=None) -> 
 
 
 RANKED_MIN_BYTES = 8 << 30          # below this everything lands in one rank anyway
+TUNE_CANDIDATES = 16                # candidate (theta, m, v) chunk triples timed per chunk position
 _last_placement = {"kind": None, "detail": None}
 
 
@@ -58,8 +59,9 @@ def alloc_engine_state(numel: int, device, *, adam: bool = True, model_copy: boo
     theta, theta_probe, (m, v), (model_copy) and a list of gradient buffers.
 
     placement: "ranked" = rank-aware placement through HIP's virtual-memory API
-    (hbm_arena.py; "ranked-adjacent" = the same with the chunks of a rank handed
-    out in index order instead of scattered, for comparison); "phased" = one plain allocation per buffer with the 64 KiB
+    (hbm_arena.py: chunks of a rank handed out in scattered order, the chunks of
+    theta, m, v then chosen by measurement; "ranked-scatter" = without that
+    choice, "ranked-adjacent" = chunks in index order, both for comparison); "phased" = one plain allocation per buffer with the 64 KiB
     phase rule only; "auto" = ranked for workloads of 8 GiB and more where the
     API is available, phased otherwise.  `last_placement()` tells which one
     the most recent call used.
@@ -72,7 +74,7 @@ def alloc_engine_state(numel: int, device, *, adam: bool = True, model_copy: boo
         _last_placement.update(kind="arena", detail=None)
         return _alloc_arena(numel, device, adam, model_copy, grad_dtype, n_grad_buffers)
     _last_placement.update(kind="phased", detail=None)
-    if placement not in ("auto", "ranked", "ranked-adjacent", "phased"):
+    if placement not in ("auto", "ranked", "ranked-scatter", "ranked-adjacent", "phased"):
         raise ValueError(placement)
     if placement != "phased":
         gs = torch.empty((), dtype=grad_dtype).element_size()
@@ -80,7 +82,8 @@ def alloc_engine_state(numel: int, device, *, adam: bool = True, model_copy: boo
         if placement.startswith("ranked") or total >= RANKED_MIN_BYTES:
             try:
                 return _alloc_ranked(numel, device, adam, model_copy, grad_dtype, n_grad_buffers, phases_kib, with_probe,
-                                     probe_is_read, verbose, scatter=placement != "ranked-adjacent")
+                                     probe_is_read, verbose, scatter=placement != "ranked-adjacent",
+                                     tune=TUNE_CANDIDATES if placement in ("auto", "ranked") else 0)
             except Exception as e:          # the virtual-memory API refused, or the placement probe failed
                 if placement.startswith("ranked"):
                     raise
@@ -112,14 +115,14 @@ def _default_phases_kib(grad_dtype) -> dict:
 
 
 def _alloc_ranked(numel, device, adam, model_copy, grad_dtype, n_grad_buffers, phases_kib, with_probe, probe_is_read, verbose,
-                  scatter=True):
+                  scatter=True, tune=0):
     """All buffers from one RankedArena: slab by slab, theta, m, v and the gradients share a rank;
     theta_probe and the bf16 copy (only ever written by the engine) come from another."""
     ph = _default_phases_kib(grad_dtype)
     ph.update(phases_kib or {})
-    specs = [dict(name="theta", numel=numel, dtype=torch.float32, group="read", phase_bytes=int(ph["theta"] * 1024))]
+    specs = [dict(name="theta", numel=numel, dtype=torch.float32, group="update", phase_bytes=int(ph["theta"] * 1024))]
     if adam:
-        specs += [dict(name=k, numel=numel, dtype=torch.float32, group="read", phase_bytes=int(ph[k] * 1024)) for k in ("m", "v")]
+        specs += [dict(name=k, numel=numel, dtype=torch.float32, group="update", phase_bytes=int(ph[k] * 1024)) for k in ("m", "v")]
     specs += [dict(name=f"g{i}", numel=numel, dtype=grad_dtype, group="read", phase_bytes=int(ph.get(f"g{i}", 0) * 1024))
               for i in range(n_grad_buffers)]
     if with_probe:
@@ -139,7 +142,7 @@ def _alloc_ranked(numel, device, adam, model_copy, grad_dtype, n_grad_buffers, p
     ar = RankedArena(device, n_chunks)
     try:
         labels = ar.classify(verbose=verbose)
-        bufs = ar.build(specs, scatter=scatter)
+        bufs = ar.build(specs, scatter=scatter, tune=tune, verbose=verbose)
     except Exception:
         ar.close()
         raise
@@ -147,7 +150,8 @@ def _alloc_ranked(numel, device, adam, model_copy, grad_dtype, n_grad_buffers, p
         counts = {lab: labels.count(lab) for lab in sorted(set(labels))}
         print(f"[layout] {n_chunks} chunks of {cb >> 20} MiB in ranks {counts}; read streams per slab in ranks {ar.slab_rank}", file=sys.stderr)
     counts = {lab: labels.count(lab) for lab in sorted(set(labels))}
-    _last_placement.update(kind="ranked", detail={"chunk_mib": cb >> 20, "chunks_per_rank": counts, "slab_rank": list(ar.slab_rank)})
+    _last_placement.update(kind="ranked", detail={"chunk_mib": cb >> 20, "chunks_per_rank": counts, "slab_rank": list(ar.slab_rank),
+                                                   "order": "scattered" if scatter else "index", "tuned": ar.tuned})
     out = {k: bufs[k] for k in ("theta", "theta_probe", "m", "v", "model_copy") if k in bufs}
     if adam:
         out["m"].zero_()

@@ -383,3 +383,40 @@ def test_chunk_plan_spills_and_refuses():
     # only the listed chunks may be used
     plan, _ = A.plan_chunks([0] * 40, specs, cb, available=list(range(20, 40)))
     assert min(c for v in plan.values() for c in v) >= 20
+
+
+def test_choose_tuples_keeps_the_best_rated_candidate_and_never_reuses_a_chunk():
+    from paper_2605_06755_amd import hbm_arena as A
+    pools = {0: list(range(0, 40)), 1: list(range(100, 112))}
+    positions = [0, 0, None, 1, 0, 1, 0]
+    calls = []
+
+    def rating(tup):
+        return -float(sum((c % 7 - 3) ** 2 for c in tup))          # best: chunks with c % 7 == 3
+
+    def measure(k, tup):
+        calls.append((k, tup))
+        assert len(set(tup)) == 3
+        return rating(tup)
+
+    tuples, seen = A.choose_tuples(pools, positions, 3, 8, measure, seed=3)
+    assert tuples[2] is None and seen[2] == []
+    flat = [c for t in tuples if t for c in t]
+    assert len(flat) == len(set(flat)) == 18                       # no chunk twice
+    for k, lab in enumerate(positions):
+        if lab is not None:
+            assert all(c in pools[lab] for c in tuples[k])
+            rated = [rating(t) for kk, t in calls if kk == k]
+            assert rating(tuples[k]) == max(rated) and 1 <= len(seen[k]) <= 8
+    # a chunk chosen for one position is not offered to a later one
+    for k, tup in list(calls):
+        earlier = [c for kk in range(k) if tuples[kk] for c in tuples[kk]]
+        assert not set(tup) & set(earlier)
+    # same seed, same choice; pools are not modified
+    again, _ = A.choose_tuples(pools, positions, 3, 8, measure, seed=3)
+    assert again == tuples and pools[0] == list(range(0, 40))
+    # the last position of a class can still be served when only its own chunks remain
+    tuples, _ = A.choose_tuples({0: [5, 6, 7, 8, 9, 10]}, [0, 0], 3, 8, measure)
+    assert sorted(c for t in tuples for c in t) == [5, 6, 7, 8, 9, 10]
+    with pytest.raises(A.ArenaUnavailable):
+        A.choose_tuples({0: [1, 2, 3, 4, 5]}, [0, 0], 3, 4, measure)
