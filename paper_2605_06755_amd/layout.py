@@ -43,6 +43,7 @@ def alloc_phased(numel: int, dtype, device, phase_bytes: int = 0, fill=None) -> 
 
 
 RANKED_MIN_BYTES = 8 << 30          # below this everything lands in one rank anyway
+SPARE_CHUNKS_MIN = 96                # chunks taken beyond the need (at least; a third of the need if that is more): choice for the placement
 TUNE_CANDIDATES = 16                # candidate (theta, m, v) chunk triples timed per chunk position
 _last_placement = {"kind": None, "detail": None}
 
@@ -138,7 +139,7 @@ def _alloc_ranked(numel, device, adam, model_copy, grad_dtype, n_grad_buffers, p
     budget = (free - (12 << 30)) // cb
     if budget < need:
         raise ArenaUnavailable(f"{need} chunks needed, room for {budget}")
-    n_chunks = int(min(budget, need + max(24, need // 3)))
+    n_chunks = int(min(budget, need + max(SPARE_CHUNKS_MIN, need // 3)))
     ar = RankedArena(device, n_chunks)
     try:
         labels = ar.classify(verbose=verbose)

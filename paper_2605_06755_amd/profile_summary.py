@@ -102,7 +102,7 @@ def main(argv):
         out.append(f"| `{short(r['Name'])}` | {r['Calls']} | {float(r['AverageNs']) / 1e6:.4f} | {float(r['MinNs']) / 1e6:.4f} | "
                    f"{float(r['MaxNs']) / 1e6:.4f} | {r['Percentage']} |")
     out.append("\n`k_optim_step` serves several calls (probe pass, slow step, fallback step) and, in runs with the rank-aware "
-               "allocator, the placement probe's thousands of launches on 128 MiB windows, which dominate its call count above. "
+               "allocator, the placement probe's thousands of launches on windows inside one 512 MiB chunk, which dominate its call count above. "
                "The same trace, launches on the full grid only, split by the call they belong to (nearest event-timed duration):\n")
     out.append("| call | kernel | launches | avg ms (rocprofv3 trace) | min | max | ms in bench.py (HIP events, median) | bytes/param | GB/s (trace avg) | % of 8 TB/s |")
     out.append("|---|---|---|---|---|---|---|---|---|---|")
