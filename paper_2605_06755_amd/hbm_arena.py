@@ -18,6 +18,11 @@ is the probe: parameters and moments in a reference chunk, the gradient in the
 candidate), and then maps the chunks into one contiguous address range per
 buffer so that, slab by slab, the streams a pass reads together sit in the same
 rank and the write-only streams (theta_probe, the bf16 model copy) in another.
+Inside a rank the chunks are handed out in a scattered order, and the chunks
+of the three streams that are read and written -- theta, m, v -- are chosen
+per 512 MiB position by timing candidate triples with the same probe: which
+chunks meet there moves the pass by several percent, with no pattern in the
+chunk numbers to plan by.
 Every buffer stays an ordinary contiguous device array; the engine sees plain
 pointers and knows nothing of this.
 """
