@@ -8,6 +8,7 @@
 //     hbm_probe phase      base addresses of the streams modulo 64 KiB
 //     hbm_probe ranks      one read stream moved across a 200 GiB allocation (DRAM rank regions)
 //     hbm_probe bf16       the fused pass with two bf16 gradient streams: 64-bit vs 128-bit accesses
+//     hbm_probe chunks     512 MiB physical chunks (virtual-memory API): which pairs and triples of chunks slow each other down
 //
 // The pass modelled is the AdamW-shaped step: read theta, m, v, g; write theta', m, v (28 B per
 // element with fp32 gradients), arithmetic reduced to a few multiply-adds (the real arithmetic
@@ -15,6 +16,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -127,6 +129,17 @@ __global__ __launch_bounds__(64) void k_copy(const float *src, float *dst, size_
     if (e0 >= n) return;
     const unsigned bytes = span_bytes(n, e0, 256);
     st<18>(rsrc(dst + e0, bytes), threadIdx.x * 16, ld<18>(rsrc(src + e0, bytes), threadIdx.x * 16));
+}
+
+// two streams read and written in place at the same element offset
+__global__ __launch_bounds__(64) void k_rmw2(float *a, float *b, size_t n) {
+    const size_t e0 = (size_t)blockIdx.x * 256;
+    if (e0 >= n) return;
+    const unsigned bytes = span_bytes(n, e0, 256);
+    const int off = threadIdx.x * 16;
+    const auto ra = rsrc(a + e0, bytes), rb = rsrc(b + e0, bytes);
+    const f4 A = ld<18>(ra, off), B = ld<18>(rb, off);
+    st<18>(ra, off, A * 0.999f + B * 1e-6f), st<18>(rb, off, B * 0.999f + A * 1e-6f);
 }
 
 __device__ __forceinline__ f4 widen(unsigned a, unsigned b) {
@@ -317,6 +330,104 @@ static int run_bf16() {
     return 0;
 }
 
+static void percentiles(std::vector<double> v, const char *what) {
+    std::sort(v.begin(), v.end());
+    auto q = [&](double f) { return v[(size_t)(f * (v.size() - 1))]; };
+    printf("  %-52s min %5.0f  5%% %5.0f  25%% %5.0f  median %5.0f  75%% %5.0f  95%% %5.0f  max %5.0f GB/s\n", what, v.front(), q(0.05), q(0.25), q(0.5),
+           q(0.75), q(0.95), v.back());
+    fflush(stdout);
+}
+
+static int run_chunks() {
+    const size_t H = 512 * MiB;
+    const int slots = 192;                                          // 96 GiB
+    const size_t n = (H - 64 * 1024) / 4;                           // windows start at a chunk's first byte (+ phase) and end inside it
+    const unsigned nb = (unsigned)((n + 255) / 256);
+    hipMemAllocationProp prop = {};
+    prop.type = hipMemAllocationTypePinned, prop.location.type = hipMemLocationTypeDevice, prop.location.id = 0;
+    hipMemAccessDesc acc = {};
+    acc.location = prop.location, acc.flags = hipMemAccessFlagsProtReadWrite;
+    static hipMemGenericAllocationHandle_t h[slots];
+    for (int i = 0; i < slots; ++i) CK(hipMemCreate(&h[i], H, &prop, 0));
+    void *va;
+    CK(hipMemAddressReserve(&va, slots * H, 2 * MiB, nullptr, 0));
+    for (int i = 0; i < slots; ++i) CK(hipMemMap((char *)va + i * H, H, 0, h[i], 0));
+    CK(hipMemSetAccess(va, slots * H, &acc, 1));
+    char *base = (char *)va;
+    k_fill<<<16384, 256>>>((float *)base, slots * H / 4, 7);
+    CK(hipDeviceSynchronize());
+    auto P = [&](int chunk, size_t phase = 0) { return (float *)(base + (size_t)chunk * H + phase); };   // phase <= 32 KiB: inside the chunk
+    printf("%d chunks of 512 MiB from hipMemCreate, mapped in creation order; windows of %zu elements at the start of a chunk\n", slots, n);
+
+    // chunks that share chunk 0's DRAM rank: gradient window in the candidate against theta, m, v in chunks 0, 1, 2
+    std::vector<int> pool;
+    {
+        std::vector<double> r(slots, 0.0);
+        for (int c = 3; c < slots; ++c) r[c] = gbps([&] { k_slow<<<nb, 64>>>(P(0), P(1, 32768), P(2, 32768), P(c), n); }, 28.0 * n, 3);
+        std::vector<double> s(r.begin() + 3, r.end());
+        std::sort(s.begin(), s.end());
+        const double top = s[s.size() * 3 / 4];
+        for (int c = 3; c < slots; ++c)
+            if (r[c] > 0.975 * top) pool.push_back(c);
+        printf("%zu of the chunks 3..%d share the rank of chunks 0-2 (gradient window there within 2.5 %% of the fast level)\n", pool.size(), slots - 1);
+    }
+    if (pool.size() < 48) {
+        printf("too few chunks in one rank for the rest of this probe\n");
+        return 1;
+    }
+
+    printf("pairs: two streams, both read and written in place, same phase; reference chunk against every chunk of the pool\n");
+    for (int ref : {pool[0], pool[1], pool[40]}) {
+        std::vector<double> r;
+        std::vector<int> who, slow;
+        for (int c : pool)
+            if (c != ref) who.push_back(c), r.push_back(gbps([&] { k_rmw2<<<nb, 64>>>(P(ref), P(c), n); }, 16.0 * n, 3));
+        char t[96];
+        snprintf(t, sizeof t, "reference chunk %d", ref);
+        percentiles(r, t);
+        std::vector<double> s = r;
+        std::sort(s.begin(), s.end());
+        const double med = s[s.size() / 2];
+        printf("    partners below 96 %% of the median:");
+        for (size_t i = 0; i < r.size(); ++i)
+            if (r[i] < 0.96 * med) printf(" %d", who[i]), slow.push_back(who[i]);
+        printf("   (%zu of %zu)\n", slow.size(), r.size());
+        // the same partners with the partner 32 KiB out of phase, and as a plain copy reference -> partner
+        std::vector<double> ph, cp;
+        for (int c : slow) ph.push_back(gbps([&] { k_rmw2<<<nb, 64>>>(P(ref), P(c, 32768), n); }, 16.0 * n, 3)),
+            cp.push_back(gbps([&] { k_copy<<<nb, 64>>>(P(ref), P(c), n); }, 8.0 * n, 3));
+        if (!slow.empty()) percentiles(ph, "    those partners, 32 KiB out of phase"), percentiles(cp, "    those partners, copy reference -> partner");
+    }
+
+    printf("triples: slow-step shape, theta, m, v (moments +32 KiB) and the gradient in four chunks drawn at random from the pool\n");
+    {
+        unsigned x = 12345;
+        auto rnd = [&](int m) { x = x * 1664525u + 1013904223u; return (int)((x >> 8) % (unsigned)m); };
+        std::vector<double> r, again;
+        for (int t = 0; t < 600; ++t) {
+            int c[4];
+            for (int k = 0; k < 4; ++k) {
+                bool fresh;
+                do {
+                    c[k] = pool[rnd((int)pool.size())], fresh = true;
+                    for (int j = 0; j < k; ++j) fresh = fresh && c[j] != c[k];
+                } while (!fresh);
+            }
+            r.push_back(gbps([&] { k_slow<<<nb, 64>>>(P(c[0]), P(c[1], 32768), P(c[2], 32768), P(c[3]), n); }, 28.0 * n, 3));
+            if (t % 20 == 0) again.push_back(gbps([&] { k_slow<<<nb, 64>>>(P(c[0]), P(c[1], 32768), P(c[2], 32768), P(c[3]), n); }, 28.0 * n, 3) - r.back());
+        }
+        percentiles(r, "600 random quadruples");
+        double s2 = 0;
+        for (double d : again) s2 += d * d;
+        printf("  the same quadruple measured twice differs by %.0f GB/s (rms over %zu)\n", std::sqrt(s2 / again.size()), again.size());
+    }
+    CK(hipDeviceSynchronize());
+    CK(hipMemUnmap(va, slots * H));
+    for (int i = 0; i < slots; ++i) CK(hipMemRelease(h[i]));
+    CK(hipMemAddressFree(va, slots * H));
+    return 0;
+}
+
 int main(int argc, char **argv) {
     const char *what = argc > 1 ? argv[1] : "";
     if (!strcmp(what, "shape")) return run_shape();
@@ -324,6 +435,7 @@ int main(int argc, char **argv) {
     if (!strcmp(what, "phase")) return run_phase();
     if (!strcmp(what, "ranks")) return run_ranks();
     if (!strcmp(what, "bf16")) return run_bf16();
-    printf("usage: hbm_probe shape | policy | phase | ranks | bf16\n");
+    if (!strcmp(what, "chunks")) return run_chunks();
+    printf("usage: hbm_probe shape | policy | phase | ranks | bf16 | chunks\n");
     return 2;
 }

@@ -587,6 +587,10 @@ def test_rank_aware_placement_changes_no_result():
         except hbm_arena.ArenaUnavailable as e:
             pytest.skip(f"virtual-memory API not available: {e}")
         assert layout_mod.last_placement()["kind"] == placement
+        if placement == "ranked":                         # scattered order, and theta, m, v of every chunk position chosen by measurement
+            detail = layout_mod.last_placement()["detail"]
+            assert detail["order"] == "scattered" and detail["tuned"]["positions"] == 3 and detail["tuned"]["candidates"] > 1
+            assert detail["tuned"]["chosen_gbps"] >= detail["tuned"]["mean_gbps"]
         for k, t in list(flat.items()) + [(f"g{i}", g) for i, g in enumerate(gflat)]:
             assert t.is_contiguous() and t.numel() == numel and t.device.type == "cuda", k
             assert t.data_ptr() % 65536 == {"m": 32768, "v": 32768, "g1": 1024}.get(k, 0), k
