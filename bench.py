@@ -273,6 +273,8 @@ def measure(name: str, args, want_cpu_inputs: bool = False):
     b.record()
     torch.cuda.synchronize()
     copy_gbps = 8.0 * n_copy * 10 / a.elapsed_time(b) / 1e6
+    for k in kernels.values():
+        k["frac_of_copy"] = round(k["gbps"] / copy_gbps, 4)
 
     # ---- fallback-phase throughput (reported for the gate-transition workload) ---------------------------
     fallback = None
@@ -313,7 +315,8 @@ def measure(name: str, args, want_cpu_inputs: bool = False):
         "gparams_per_s": round(P / ms_per_step / 1e6, 3),
         "hbm_gbps_step": round(step_bpp * P / ms_per_step / 1e6, 1),
         "hbm_frac_of_peak_step": round(step_bpp * P / ms_per_step / 1e6 / HBM_PEAK_GBPS, 4),
-        "copy_kernel_gbps": round(copy_gbps, 1), "kernels": kernels, "dominant_kernel": dominant,
+        "copy_kernel_gbps": round(copy_gbps, 1), "hbm_frac_of_copy_step": round(step_bpp * P / ms_per_step / 1e6 / copy_gbps, 4),
+        "kernels": kernels, "dominant_kernel": dominant,
         "gate": {"norm": info.norm, "z": None if math.isnan(info.z) else info.z, "tripped": bool(info.tripped),
                  "live_step_norm": live_info.norm},
     }
@@ -412,6 +415,7 @@ def main():
         "hbm_gbps_step": head["hbm_gbps_step"],
         "hbm_frac_of_peak_step": head["hbm_frac_of_peak_step"],
         "copy_kernel_gbps": head["copy_kernel_gbps"],
+        "hbm_frac_of_copy_step": head["hbm_frac_of_copy_step"],
         "kernels": head["kernels"],
         "gate": head["gate"],
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": dk["gbps"], "peak": HBM_PEAK_GBPS,
