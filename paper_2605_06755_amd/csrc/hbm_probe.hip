@@ -77,6 +77,18 @@ __global__ __launch_bounds__(64 * WPB) void k_step(const float *th_in, float *th
     }
 }
 
+// the same step with the two moments in ONE array, interleaved per block: 1 KiB of m, then 1 KiB of v (one stream fewer)
+__global__ __launch_bounds__(64) void k_step_mv(const float *th_in, float *th_out, float *mv, const float *g, size_t n) {
+    const size_t e0 = (size_t)blockIdx.x * 256;
+    if (e0 >= n) return;
+    const unsigned bytes = span_bytes(n, e0, 256);
+    const int off = threadIdx.x * 16;
+    const auto rm = rsrc(mv + 2 * e0, bytes), rv = rsrc(mv + 2 * e0 + 256, bytes);
+    f4 T = ld<18>(rsrc(th_in + e0, bytes), off), M = ld<18>(rm, off), V = ld<18>(rv, off), G = ld<18>(rsrc(g + e0, bytes), off);
+    math(T, M, V, G);
+    st<18>(rsrc(th_out + e0, bytes), off, T), st<18>(rm, off, M), st<18>(rv, off, V);
+}
+
 // persistent blocks that walk the arrays with a grid stride
 template <int WPB>
 __global__ __launch_bounds__(64 * WPB) void k_step_stride(const float *th_in, float *th_out, float *m, float *v, const float *g, size_t n) {
@@ -252,6 +264,8 @@ static int run_shape() {
             line(what, gbps([&] { k_step_stride<1><<<256 * per_cu, 64>>>(f.a[0], f.a[1], f.a[2], f.a[3], f.a[4], n); }, 28.0 * n));
         }
     line("grid-stride loop, 4-wavefront blocks, 8 blocks per CU", gbps([&] { k_step_stride<4><<<256 * 8, 256>>>(f.a[0], f.a[1], f.a[2], f.a[3], f.a[4], n); }, 28.0 * n));
+    // the interleaved array takes the place of m and v: 8n bytes from m's start end before the gradient array begins
+    line("1 wavefront, 4 elements per lane, m and v interleaved per block in one array", gbps([&] { k_step_mv<<<nb(256), 64>>>(f.a[0], f.a[1], f.a[2], f.a[4], n); }, 28.0 * n));
     line("plain copy, same shape (8 B/element)", gbps([&] { k_copy<<<nb(256), 64>>>(f.a[0], f.a[1], n); }, 8.0 * n));
     return 0;
 }
