@@ -42,7 +42,7 @@ def alloc_phased(numel: int, dtype, device, phase_bytes: int = 0, fill=None) -> 
     return out
 
 
-RANKED_MIN_BYTES = 8 << 30          # below this everything lands in one rank anyway
+RANKED_MIN_BYTES = 3 << 30          # below this a buffer is a single chunk: nothing to place
 SPARE_CHUNKS_MIN = 96                # chunks taken beyond the need (at least; a third of the need if that is more): choice for the placement
 TUNE_CANDIDATES = 16                # candidate (theta, m, v) chunk triples timed per chunk position
 _last_placement = {"kind": None, "detail": None}
@@ -63,7 +63,7 @@ def alloc_engine_state(numel: int, device, *, adam: bool = True, model_copy: boo
     (hbm_arena.py: chunks of a rank handed out in scattered order, the chunks of
     theta, m, v then chosen by measurement; "ranked-scatter" = without that
     choice, "ranked-adjacent" = chunks in index order, both for comparison); "phased" = one plain allocation per buffer with the 64 KiB
-    phase rule only; "auto" = ranked for workloads of 8 GiB and more where the
+    phase rule only; "auto" = ranked for workloads of 3 GiB and more where the
     API is available, phased otherwise.  `last_placement()` tells which one
     the most recent call used.
     `probe_is_read`: the schedule reads theta_probe back (unfused second fast
