@@ -44,6 +44,8 @@ def alloc_phased(numel: int, dtype, device, phase_bytes: int = 0, fill=None) -> 
 
 RANKED_MIN_BYTES = 3 << 30          # below this a buffer is a single chunk: nothing to place
 SPARE_CHUNKS_MIN = 96                # chunks taken beyond the need (at least; a third of the need if that is more): choice for the placement
+CHUNKS_MIN = 240                     # ... and at least this many in all (120 GiB, more than one rank holds): the first 96 GiB a
+                                     # process is given tend to lie in one rank, and theta_probe wants a rank of its own
 TUNE_CANDIDATES = 16                # candidate (theta, m, v) chunk triples timed per chunk position
 _last_placement = {"kind": None, "detail": None}
 
@@ -139,7 +141,7 @@ def _alloc_ranked(numel, device, adam, model_copy, grad_dtype, n_grad_buffers, p
     budget = (free - (12 << 30)) // cb
     if budget < need:
         raise ArenaUnavailable(f"{need} chunks needed, room for {budget}")
-    n_chunks = int(min(budget, need + max(SPARE_CHUNKS_MIN, need // 3)))
+    n_chunks = int(min(budget, max(CHUNKS_MIN, need + max(SPARE_CHUNKS_MIN, need // 3))))
     ar = RankedArena(device, n_chunks)
     try:
         labels = ar.classify(verbose=verbose)
