@@ -3,11 +3,11 @@
 
 Three runs of the same command feed one summary (rocprofv3 collects counters in runs of their own):
 
-    rocprofv3 --kernel-trace --stats --output-format csv -d gpurun_out/prof_X      -- python3 bench.py --workload X --no-cpu-baseline --steps 10
-    rocprofv3 --pmc FETCH_SIZE       --output-format csv -d gpurun_out/pmc_fetch_X -- python3 bench.py --workload X --no-cpu-baseline --steps 3 --warmup 1
-    rocprofv3 --pmc WRITE_SIZE       --output-format csv -d gpurun_out/pmc_write_X -- python3 bench.py --workload X --no-cpu-baseline --steps 3 --warmup 1
+    rocprofv3 --kernel-trace --stats --output-format csv -d /tmp/gxpo_prof/prof_X      -- python3 /root/repo/bench.py --workload X --no-cpu-baseline --steps 10
+    rocprofv3 --pmc FETCH_SIZE       --output-format csv -d /tmp/gxpo_prof/pmc_fetch_X -- python3 /root/repo/bench.py --workload X --no-cpu-baseline --steps 3 --warmup 1
+    rocprofv3 --pmc WRITE_SIZE       --output-format csv -d /tmp/gxpo_prof/pmc_write_X -- python3 /root/repo/bench.py --workload X --no-cpu-baseline --steps 3 --warmup 1
 
-    python3 -m paper_2605_06755_amd.profile_summary X gpurun_out/prof_X gpurun_out/pmc_fetch_X gpurun_out/pmc_write_X gpurun_out/prof_X.log
+    python3 -m paper_2605_06755_amd.profile_summary X /tmp/gxpo_prof/prof_X /tmp/gxpo_prof/pmc_fetch_X /tmp/gxpo_prof/pmc_write_X /tmp/gxpo_prof/prof_X.log
 
 The last argument is the stdout of the kernel-trace run (bench.py's JSON line).  Writes
 profiles/gxpo_kernels_<X>.md and profiles/traffic_<kernel>_<X>.json; the latter carries a hash of the
@@ -94,8 +94,8 @@ def main(argv):
            f"Workload: {bench['config']['workload']}; {P} parameters in {bench['config']['tensors']} tensor(s), "
            f"{bench['config']['grad_dtype']} gradients, HBM layout: {bench['config']['hbm_layout']}.\n",
            "## kernel trace (`--kernel-trace --stats`)\n",
-           f"Command: `cd /tmp && TMPDIR=/tmp rocprofv3 --kernel-trace --stats --output-format csv -d gpurun_out/prof_{tag} -- "
-           f"python3 bench.py --workload {tag} --no-cpu-baseline --steps {bench['steps']}`\n",
+           f"Command: `cd /tmp && TMPDIR=/tmp rocprofv3 --kernel-trace --stats --output-format csv -d /tmp/gxpo_prof/prof_{tag} -- "
+           f"python3 /root/repo/bench.py --workload {tag} --no-cpu-baseline --steps {bench['steps']}`\n",
            "rocprofv3's own statistics, all launches of a kernel name together:\n",
            "| kernel | calls | avg ms | min ms | max ms | % of GPU time |", "|---|---|---|---|---|---|"]
     for r in kernel_stats(d_stats):
@@ -132,10 +132,10 @@ def main(argv):
     cf, cw = max(fetch["gxpo::k_stream_copy"]), max(write["gxpo::k_stream_copy"])
     f_scale, w_scale = copy_kib / cf, copy_kib / cw
     out.append("## HBM traffic (`--pmc FETCH_SIZE`, then `--pmc WRITE_SIZE`, one run each)\n")
-    out.append(f"Commands: `rocprofv3 --pmc FETCH_SIZE --output-format csv -d gpurun_out/pmc_fetch_{tag} -- python3 bench.py --workload {tag} "
-               f"--no-cpu-baseline --steps 3 --warmup 1`, the same with `WRITE_SIZE` into `gpurun_out/pmc_write_{tag}`, then "
-               f"`python3 -m paper_2605_06755_amd.profile_summary {tag} gpurun_out/prof_{tag} gpurun_out/pmc_fetch_{tag} gpurun_out/pmc_write_{tag} "
-               f"gpurun_out/prof_{tag}.log`.\n")
+    out.append(f"Commands: `cd /tmp && rocprofv3 --pmc FETCH_SIZE --output-format csv -d /tmp/gxpo_prof/pmc_fetch_{tag} -- python3 /root/repo/bench.py --workload {tag} "
+               f"--no-cpu-baseline --steps 3 --warmup 1`, the same with `WRITE_SIZE` into `/tmp/gxpo_prof/pmc_write_{tag}`, then "
+               f"`cd /root/repo && python3 -m paper_2605_06755_amd.profile_summary {tag} /tmp/gxpo_prof/prof_{tag} /tmp/gxpo_prof/pmc_fetch_{tag} /tmp/gxpo_prof/pmc_write_{tag} "
+               f"/tmp/gxpo_prof/prof_{tag}.log`.\n")
     out.append(f"Calibration: `gxpo::k_stream_copy` moves {n_copy} fp32 = {copy_kib:.0f} KiB each way per launch; the counters read "
                f"FETCH_SIZE = {cf:.0f} and WRITE_SIZE = {cw:.0f} for it, so FETCH_SIZE is scaled by {f_scale:.4f} and WRITE_SIZE by {w_scale:.4f}. "
                "Launches on the full grid only; a launch is attributed to the call whose read (write) bytes per parameter it is nearest to.\n")
