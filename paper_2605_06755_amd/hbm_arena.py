@@ -398,7 +398,8 @@ class RankedArena:
         fallback step (standard deviation one point), and no rule in the chunk numbers predicts it.  So they are
         chosen by measurement: per position, `candidates` random triples from the rank's pool (the chunks planned
         for theta, m, v there plus the spare ones) are timed with the engine's fallback step on windows at the
-        start of the chunks, against the gradient chunk planned for that position, and the best triple is kept.
+        start of the chunks, against the chunks planned there for the first and the last gradient stream (what the
+        fused pass and the fallback step read, and what the slow step reads), and the best triple is kept.
         Edits `plan` in place; leaves it alone when the buffers are not the AdamW set."""
         upd = [s for s in specs if s["group"] == "update"]
         reads = [s for s in specs if s["group"] == "read"]
@@ -422,8 +423,9 @@ class RankedArena:
                 pools.setdefault(lab, []).extend(plan[n][k] for n in names)
         for lab in pools:
             pools[lab].sort()
-        g_spec = reads[0]
-        g_size = torch.empty((), dtype=g_spec["dtype"]).element_size()
+        # the gradient streams the written passes read: the first (fused pass, fallback step) and the last (slow step)
+        g_specs = [reads[0]] + ([reads[-1]] if len(reads) > 1 and reads[-1]["dtype"] == reads[0]["dtype"] else [])
+        g_size = torch.empty((), dtype=g_specs[0]["dtype"]).element_size()
         E = (cb - 65536) // 4
         va = self._reserve(len(self.handles) * cb)
         for c in available:
@@ -431,38 +433,43 @@ class RankedArena:
         cfg = _B.make_config(K=2, lr=1e-9, weight_decay=0.0, delta=0.0, grad_dtype="f32" if g_size == 4 else "bf16")
         cache = {}
 
-        def gradient(k):
+        def gradients(k):
             if cache.get("k") != k:
-                at = k * (cb // 4) * g_size                                      # where position k starts in the gradient buffer
-                chunk = plan[g_spec["name"]][min(at // cb, len(plan[g_spec["name"]]) - 1)]
-                off = min(at % cb, cb - E * g_size)
-                g = self._tensor(va + chunk * cb + off, E, g_spec["dtype"])
-                g.normal_(std=0.05)
-                cache.update(k=k, g=g)
-            return cache["g"]
+                gs = []
+                for g_spec in g_specs:
+                    at = k * (cb // 4) * g_size                                  # where position k starts in the gradient buffer
+                    chunk = plan[g_spec["name"]][min(at // cb, len(plan[g_spec["name"]]) - 1)]
+                    off = min(at % cb, cb - E * g_size)
+                    g = self._tensor(va + chunk * cb + off, E, g_spec["dtype"])
+                    g.normal_(std=0.05)
+                    gs.append(g)
+                cache.update(k=k, gs=gs)
+            return cache["gs"]
 
         def measure(k, tup):
             th, m, v = (self._tensor(va + c * cb + s.get("phase_bytes", 0), E, torch.float32) for c, s in zip(tup, upd))
             th.normal_(std=0.02)
             m.zero_()
             v.fill_(1e-4)
-            g = gradient(k)
             ctx = _B.gxpo_init(cfg, [dict(theta=th, m=m, v=v)])
             st = _B.gxpo_get_state(ctx)
             st.s_star = 0
             _B.gxpo_set_state(ctx, st)
-            _B.gxpo_fallback_step(ctx, [g])
-            best = 0.0
-            for _ in range(2):                                                   # disturbances only slow a measurement down
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record()
-                for _ in range(3):
-                    _B.gxpo_fallback_step(ctx, [g])
-                b.record()
-                b.synchronize()
-                best = max(best, 3 * (24.0 + g_size) * E / a.elapsed_time(b) / 1e6)
+            total_ms = 0.0
+            for g in gradients(k):
+                _B.gxpo_fallback_step(ctx, [g])
+                best = float("inf")
+                for _ in range(2):                                               # disturbances only slow a measurement down
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record()
+                    for _ in range(3):
+                        _B.gxpo_fallback_step(ctx, [g])
+                    b.record()
+                    b.synchronize()
+                    best = min(best, a.elapsed_time(b) / 3)
+                total_ms += best
             _B.gxpo_destroy(ctx)
-            return best
+            return len(g_specs) * (24.0 + g_size) * E / total_ms / 1e6
 
         try:
             tuples, seen = choose_tuples(pools, positions, len(names), candidates, measure)
