@@ -346,7 +346,12 @@ int gxpo_plan_blocks(const uint64_t *numel, uint32_t n_tensors, uint32_t *block_
  * are only written (theta_probe and model_copy under fuse_step2) are best kept in
  * another.  Allocating each tensor's buffers next to each other achieves that for
  * tensors up to a few GiB; for larger ones the Python package's hbm_arena module
- * maps each buffer from physical chunks chosen by region. */
+ * maps each buffer from physical chunks chosen by region.  Inside a region a
+ * third effect remains, also beyond a phase: which physical blocks theta, m and v
+ * (the three streams a pass writes) occupy at the same element offset moves a
+ * pass by up to several percent with no usable pattern in the addresses; that
+ * module therefore times candidate blocks with gxpo_fallback_step and keeps the
+ * fastest, which any caller can do the same way. */
 enum { GXPO_BUF_THETA = 0, GXPO_BUF_THETA_PROBE = 1, GXPO_BUF_M = 2, GXPO_BUF_V = 3,
        GXPO_BUF_MODEL_COPY = 4, GXPO_BUF_GRAD = 5 };
 int gxpo_layout_hint(int buffer_kind, uint64_t *phase_bytes, uint64_t *period_bytes);
