@@ -111,6 +111,26 @@ typedef struct gxpo_tensor {
                             fuse_step2 both fast steps' moment updates are applied together by
                             gxpo_extrapolate (the first fast step is previewed, then replayed). */
     void  *model_copy;   /* optional bf16 [numel] copy the trainer's forward/backward reads; NULL = none */
+    float *m_alt, *v_alt; /* optional second buffers for the moments, fp32 [numel] each: ALTERNATING STATE.  Given
+                            for every tensor (together with theta_probe), or for none.  The engine then owns two
+                            sets of buffers, {theta, m, v} and {theta_probe, m_alt, v_alt}, and every pass that
+                            advances the state reads one set and writes the other instead of updating in place:
+                            on MI355X a pass whose written streams lie in other physical memory than the streams
+                            it reads runs 2-4 % faster (no read and write of the same DRAM pages side by side).
+                            gxpo_state.current_set (gxpo_get_state) says which set holds the state; with c its
+                            value when a training step starts:
+                              gxpo_fast_steps(0)   reads set c, writes theta^{t,1} into the parameter buffer of
+                                                   set 1-c (theta_probe if c == 0, theta if c == 1);
+                              gxpo_extrapolate     reads set c, writes theta~^t, m, v to set 1-c; current_set
+                                                   becomes 1-c: the trainer differentiates there;
+                              gxpo_slow_step       reads set 1-c, writes theta^{t+1}, m, v to set c;
+                                                   current_set is c again;
+                              gxpo_fallback_step   reads the current set, writes the other, flips current_set
+                                                   (so fallback steps alternate between the two sets).
+                            The values are bit for bit those of the in-place schedule; model_copy always receives
+                            the newest iterate, so a trainer that differentiates through it need not follow the
+                            alternation.  Needs GXPO_OPT_ADAMW, fuse_step2 = 1 and explicit_steps = 0
+                            (GXPO_ERR_UNSUPPORTED otherwise).  Costs 8 bytes per parameter of HBM. */
 } gxpo_tensor;
 
 /* Hyper-parameters.  All reals travel as double; the library derives the
@@ -192,7 +212,8 @@ typedef struct gxpo_state {
     int64_t  s_star;             /* -1 = +infinity */
     int64_t  backward_passes;    /* gradient hand-offs so far: 3 s* + (T - s*) after T steps */
     uint32_t window_len;         /* norms currently in the rolling buffer */
-    uint32_t reserved;
+    uint32_t current_set;        /* alternating state (gxpo_tensor.m_alt): 0 = theta, m, v hold the state,
+                                    1 = theta_probe, m_alt, v_alt do.  Always 0 otherwise. */
     double   window[GXPO_MAX_WINDOW];   /* oldest first */
 } gxpo_state;
 

@@ -52,7 +52,8 @@ EXPORTED_SYMBOLS = [
 # ---- structs (mirror include/gxpo.h) ----------------------------------------------------------
 class gxpo_tensor(ctypes.Structure):
     _fields_ = [("numel", ctypes.c_uint64), ("theta", ctypes.c_void_p), ("theta_probe", ctypes.c_void_p),
-                ("m", ctypes.c_void_p), ("v", ctypes.c_void_p), ("model_copy", ctypes.c_void_p)]
+                ("m", ctypes.c_void_p), ("v", ctypes.c_void_p), ("model_copy", ctypes.c_void_p),
+                ("m_alt", ctypes.c_void_p), ("v_alt", ctypes.c_void_p)]
 
 
 class gxpo_config(ctypes.Structure):
@@ -86,7 +87,7 @@ class gxpo_diagnostics(ctypes.Structure):
 class gxpo_state(ctypes.Structure):
     _fields_ = [("struct_size", ctypes.c_uint32), ("phase", ctypes.c_uint32), ("t", ctypes.c_int64),
                 ("optim_steps", ctypes.c_int64), ("s_star", ctypes.c_int64), ("backward_passes", ctypes.c_int64),
-                ("window_len", ctypes.c_uint32), ("reserved", ctypes.c_uint32),
+                ("window_len", ctypes.c_uint32), ("current_set", ctypes.c_uint32),
                 ("window", ctypes.c_double * GXPO_MAX_WINDOW)]
 
 
@@ -232,7 +233,7 @@ class GradList:
 
 def gxpo_init(cfg: gxpo_config, tensors: Sequence[dict]) -> Context:
     """tensors: one dict per parameter tensor with torch tensors under the keys
-    theta, theta_probe, and optionally m, v, model_copy."""
+    theta, theta_probe, and optionally m, v, model_copy, m_alt, v_alt."""
     n = len(tensors)
     arr = (gxpo_tensor * max(n, 1))()
     for i, t in enumerate(tensors):
@@ -243,6 +244,8 @@ def gxpo_init(cfg: gxpo_config, tensors: Sequence[dict]) -> Context:
         arr[i].m = _dev_ptr(t.get("m"), torch.float32, numel)
         arr[i].v = _dev_ptr(t.get("v"), torch.float32, numel)
         arr[i].model_copy = _dev_ptr(t.get("model_copy"), torch.bfloat16, numel)
+        arr[i].m_alt = _dev_ptr(t.get("m_alt"), torch.float32, numel)
+        arr[i].v_alt = _dev_ptr(t.get("v_alt"), torch.float32, numel)
     handle = _ctx_p(None)
     rc = _lib.gxpo_init(ctypes.byref(handle), ctypes.byref(cfg), arr, n)
     if rc != GXPO_OK:

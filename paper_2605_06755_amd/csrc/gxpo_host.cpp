@@ -61,6 +61,7 @@ struct gxpo_ctx {
     bool have_diag = false, cos_valid = false;
     int64_t diag_t = -1;
     uint32_t n_acc = 1;                      // accumulators the workspace holds (1, or kNumAcc with diagnostics)
+    bool alternating = false;                // every tensor brought m_alt, v_alt: passes read one set and write the other
 
     // gradient pointer staging
     const void **h_stage = nullptr;          // pinned, [kStageSlots][n]
@@ -80,10 +81,14 @@ struct gxpo_ctx {
     TensorRec record(uint32_t t) const {
         const gxpo_tensor &x = tensors[t];
         const gxpo_tensor_options &o = options[t];
-        return TensorRec{x.theta, x.theta_probe, x.m, x.v, x.model_copy, x.numel, (float)o.lr_scale,
+        return TensorRec{x.theta, x.theta_probe, x.m, x.v, x.model_copy, x.m_alt, x.v_alt, x.numel, (float)o.lr_scale,
                          (float)(o.lr_scale * o.weight_decay_scale)};
     }
     Layout layout() const { return Layout{d_tab, d_blk_start, d_coarse, n, n_blocks, record(0)}; }
+    // the set that holds the state, and the set a state-advancing pass writes
+    int cur_set() const { return st.current_set ? kSetAlt : kSetMain; }
+    int next_set() const { return alternating ? (st.current_set ? kSetMain : kSetAlt) : kSetMain; }
+    void advance_set() { if (alternating) st.current_set ^= 1u; }
 };
 
 namespace {
@@ -390,7 +395,13 @@ int gxpo_init(gxpo_ctx **out, const gxpo_config *cfg, const gxpo_tensor *tensors
         if (!x.theta) return fail(nullptr, GXPO_ERR_INVALID_ARG, "tensor %u: theta is NULL", t);
         if (adam && (!x.m || !x.v)) return fail(nullptr, GXPO_ERR_INVALID_ARG, "tensor %u: AdamW needs m and v", t);
         if (!adam && (x.m || x.v)) return fail(nullptr, GXPO_ERR_INVALID_ARG, "tensor %u: m and v must be NULL for plain GD", t);
-        const void *f32[] = {x.theta, x.theta_probe, x.m, x.v};
+        if ((x.m_alt == nullptr) != (x.v_alt == nullptr) || (x.m_alt != nullptr) != (tensors[0].m_alt != nullptr))
+            return fail(nullptr, GXPO_ERR_INVALID_ARG, "tensor %u: m_alt and v_alt come together, for every tensor or for none", t);
+        if (x.m_alt && !x.theta_probe)
+            return fail(nullptr, GXPO_ERR_INVALID_ARG, "tensor %u: alternating state (m_alt, v_alt) needs theta_probe as the second parameter buffer", t);
+        if (x.m_alt && (!adam || !cfg->fuse_step2 || cfg->explicit_steps))
+            return fail(nullptr, GXPO_ERR_UNSUPPORTED, "alternating state (m_alt, v_alt) needs AdamW, fuse_step2 = 1 and explicit_steps = 0");
+        const void *f32[] = {x.theta, x.theta_probe, x.m, x.v, x.m_alt, x.v_alt};
         for (const void *p : f32)
             if (p && (uintptr_t)p % 16) return fail(nullptr, GXPO_ERR_ALIGNMENT, "tensor %u: an fp32 buffer is not 16-byte aligned", t);
         if (x.model_copy && (uintptr_t)x.model_copy % 8)
@@ -411,6 +422,8 @@ int gxpo_init(gxpo_ctx **out, const gxpo_config *cfg, const gxpo_tensor *tensors
         add(x.theta_probe, x.numel * 4, "theta_probe");
         add(x.m, x.numel * 4, "m");
         add(x.v, x.numel * 4, "v");
+        add(x.m_alt, x.numel * 4, "m_alt");
+        add(x.v_alt, x.numel * 4, "v_alt");
         add(x.model_copy, x.numel * 2, "model_copy");
     }
     std::sort(iv.begin(), iv.end(), [](const Interval &a, const Interval &b) { return a.lo < b.lo; });
@@ -434,6 +447,7 @@ int gxpo_init(gxpo_ctx **out, const gxpo_config *cfg, const gxpo_tensor *tensors
     ctx->n = n_tensors;
     ctx->n_acc = (cfg->diagnostics || cfg->clip_norm > 0.0) ? (uint32_t)kNumAcc : 1u;
     ctx->device = device;
+    ctx->alternating = tensors[0].m_alt != nullptr;
     ctx->tensors.assign(tensors, tensors + n_tensors);
     ctx->options.assign(n_tensors, gxpo_tensor_options{1.0, 1.0});
     ctx->blk_start = blk_start;
@@ -538,12 +552,15 @@ int gxpo_fast_steps(gxpo_ctx *ctx, int which, const void *const *grads, void *st
         ctx->pending_step2 = step_no;
     } else {
         const StepParams p = make_step_params(ctx->cfg, step_no);
-        const int src = which == 0 ? kSrcTheta : kSrcProbe;
+        // the first fast step reads the current set and writes theta^{t,1} into the other set's parameter buffer
+        // (alternating state: whichever of theta / theta_probe is not current); the unfused second step works on theta_probe
+        const int src = which == 0 ? ctx->cur_set() : kSrcProbe;
+        const int dst = (which == 0 && ctx->st.current_set) ? kSrcTheta : kSrcProbe;
         // the trainer differentiates at theta^{t,1}; with explicit lookahead at every probe iterate
         const int wc = ((which == 0 || ctx->cfg.explicit_steps) && copy_at_probe) ? 1 : 0;
         // fused schedule: the probe pass only previews the step, the moments are advanced by gxpo_extrapolate
         const int write_moments = fused ? 0 : 1;
-        GXPO_HIP(ctx, launch_step(ctx->layout(), (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, src, kSrcProbe,
+        GXPO_HIP(ctx, launch_step(ctx->layout(), (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, src, dst,
                                   write_moments, wc, nullptr, GradArg{}, ctx->d_clip, which == 0 ? kClipG0 : kClipG1, s));
         if (fused) {
             ctx->pending_g0.assign(grads, grads + ctx->n);
@@ -594,7 +611,8 @@ int gxpo_extrapolate(gxpo_ctx *ctx, const void *const *g0, const void *const *g1
         const StepParams p1 = make_step_params(ctx->cfg, ctx->pending_step1);
         const StepParams p2 = make_step_params(ctx->cfg, ctx->pending_step2);
         GXPO_HIP(ctx, launch_fused_steps_extrapolate(ctx->layout(), (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g0, d_g1,
-                                                     p1, p2, e, wc, diag, ctx->d_clip, s));
+                                                     p1, p2, e, ctx->cur_set(), ctx->next_set(), wc, diag, ctx->d_clip, s));
+        ctx->advance_set();
     } else {
         GXPO_HIP(ctx, launch_extrapolate(ctx->layout(), (int)ctx->cfg.grad_dtype, d_g0, d_g1, e, wc, diag, ctx->d_clip, s));
     }
@@ -630,8 +648,9 @@ int gxpo_slow_step(gxpo_ctx *ctx, const void *const *g_slow, void *stream) {
     rc = clip_prepass(ctx, d_g, kAccSlowSq, kClipSlow, s);
     if (rc != GXPO_OK) return rc;
     double *partial = (ctx->d_clip && !cos_valid) ? nullptr : ctx->d_partial;
-    GXPO_HIP(ctx, launch_step(ctx->layout(), (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, kSrcTheta, kSrcTheta, 1, wc,
+    GXPO_HIP(ctx, launch_step(ctx->layout(), (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, ctx->cur_set(), ctx->next_set(), 1, wc,
                               partial, dot, ctx->d_clip, kClipSlow, s));
+    ctx->advance_set();
     if (partial)
         GXPO_HIP(ctx, launch_finalize(ctx->d_partial, ctx->n_blocks, ctx->d_seg, ctx->n_segs, ctx->d_tensor_seg_start, ctx->n,
                                       ctx->d_seg_sum, ctx->d_result, kAccSlowSq, cos_valid ? 2 : 1, s));
@@ -679,8 +698,9 @@ int gxpo_fallback_step(gxpo_ctx *ctx, const void *const *g0, void *stream) {
     const int wc = (ctx->cfg.copy_mask & GXPO_COPY_AT_FINAL) ? 1 : 0;
     rc = clip_prepass(ctx, d_g, kAccClipG0, kClipG0, s);
     if (rc != GXPO_OK) return rc;
-    GXPO_HIP(ctx, launch_step(ctx->layout(), (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, kSrcTheta, kSrcTheta, 1, wc,
+    GXPO_HIP(ctx, launch_step(ctx->layout(), (int)ctx->cfg.optimizer, (int)ctx->cfg.grad_dtype, d_g, p, ctx->cur_set(), ctx->next_set(), 1, wc,
                               nullptr, GradArg{}, ctx->d_clip, kClipG0, s));
+    ctx->advance_set();
     st.optim_steps = step_no;
     st.backward_passes += 1;
     st.t += 1;
@@ -747,6 +767,9 @@ int gxpo_set_state(gxpo_ctx *ctx, const gxpo_state *in) {
     if (in->t < 0 || in->optim_steps < 0 || in->backward_passes < 0 || in->s_star < -1)
         return fail(ctx, GXPO_ERR_INVALID_ARG, "gxpo_set_state: negative counter");
     if (in->window_len > ctx->cfg.window) return fail(ctx, GXPO_ERR_INVALID_ARG, "gxpo_set_state: window_len exceeds the configured window");
+    if (in->current_set > (ctx->alternating ? 1u : 0u))
+        return fail(ctx, GXPO_ERR_INVALID_ARG, "gxpo_set_state: current_set %u, but the tensors %s", in->current_set,
+                    ctx->alternating ? "have two buffer sets (0 or 1)" : "have no second buffer set (m_alt, v_alt)");
     ctx->st = *in;
     return GXPO_OK;
 }
@@ -848,7 +871,7 @@ int gxpo_slow_step_noalloc(const gxpo_config *cfg, const gxpo_tensor *tensor, in
     Layout L{};
     L.n_tensors = 1;
     L.n_blocks = (uint32_t)((x.numel + kWaveElems - 1) / kWaveElems);
-    L.single = TensorRec{x.theta, nullptr, x.m, x.v, wc ? x.model_copy : nullptr, x.numel, 1.0f, 1.0f};
+    L.single = TensorRec{x.theta, nullptr, x.m, x.v, wc ? x.model_copy : nullptr, nullptr, nullptr, x.numel, 1.0f, 1.0f};
     const StepParams p = make_step_params(*cfg, optim_step);
     hipError_t e = launch_slow_step_noalloc(L, (int)cfg->optimizer, (int)cfg->grad_dtype, GradArg{nullptr, g_slow}, p, wc ? 1 : 0,
                                             sum_sq_out_device, (hipStream_t)stream);

@@ -21,6 +21,8 @@ struct TensorRec {          // device copy of one gxpo_tensor
     float *m;
     float *v;
     void *copy;             // bf16 model copy or nullptr
+    float *m_alt;           // second buffers for the moments (alternating state) or nullptr
+    float *v_alt;
     uint64_t numel;
     float lr_scale;         // parameter group: multiplies the step size (1 = the context's lr)
     float lr_wd_scale;      // lr_scale * weight_decay_scale: multiplies lr * weight_decay
@@ -76,7 +78,10 @@ struct SegRec {             // a run of per-block partials inside one tensor
     uint32_t count;
 };
 
-enum { kSrcTheta = 0, kSrcProbe = 1 };
+// Which buffers a pass reads (src) and writes (dst): bit 0 picks the parameter buffer (theta or
+// theta_probe), bit 1 the moments (m, v or m_alt, v_alt).  With alternating state the two sets
+// {theta, m, v} and {theta_probe, m_alt, v_alt} are kSetMain and kSetAlt.
+enum { kSrcTheta = 0, kSrcProbe = 1, kMomentsAlt = 2, kSetMain = 0, kSetAlt = kSrcProbe | kMomentsAlt };
 
 // Reduction accumulators.  Each owns one XCD-major array of per-block partials,
 // `partial_pitch(n_blocks)` doubles apart.  Only kAccSlowSq exists unless the
@@ -129,11 +134,13 @@ hipError_t launch_extrapolate(const Layout &L, int grad_dtype,
 // theta <- theta + alpha (theta_probe - theta), nothing else (explicit lookahead).
 hipError_t launch_reposition(const Layout &L, float alpha, int write_copy, hipStream_t stream);
 
-// p1 / p2: constants of the first / second fast step (both are applied here).
+// p1 / p2: constants of the first / second fast step (both are applied here).  src / dst: the set (kSetMain or
+// kSetAlt) the pass reads theta^t, m, v from and the set it writes theta~, m, v to; equal = in place.
 hipError_t launch_fused_steps_extrapolate(const Layout &L, int optimizer, int grad_dtype,
                                           const GradArg &d_g0, const GradArg &d_g1,
                                           const StepParams &p1, const StepParams &p2, const ExtrapParams &e,
-                                          int write_copy, double *d_diag_partial, const float *d_clip, hipStream_t stream);
+                                          int src, int dst, int write_copy, double *d_diag_partial, const float *d_clip,
+                                          hipStream_t stream);
 
 // Reduces accumulators [first_acc, first_acc + n_acc).  For accumulator a:
 // result[a * (1 + n_tensors)] = sum over all tensors, result[a * (1 + n_tensors) + 1 + t] = tensor t.

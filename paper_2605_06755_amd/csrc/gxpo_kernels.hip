@@ -349,20 +349,18 @@ __global__ __launch_bounds__(64) void k_optim_step(Layout L, GradArg grads, Step
     const StepParams p = for_tensor(p_all, s.rec);
     const uint32_t elem = threadIdx.x * kLaneElems;
     const uint32_t bytes = s.cnt * 4u;
-    const float *src_ptr = (src == kSrcProbe ? s.rec.probe : s.rec.theta) + s.e0;
-    float *dst_base = dst == kSrcProbe ? s.rec.probe : s.rec.theta;      // a NULL probe: nobody wants fp32 theta^{t,1}
+    const float *src_ptr = ((src & kSrcProbe) ? s.rec.probe : s.rec.theta) + s.e0;
+    float *dst_base = (dst & kSrcProbe) ? s.rec.probe : s.rec.theta;     // a NULL probe: nobody wants fp32 theta^{t,1}
     const auto r_src = span_rsrc(src_ptr, bytes);
     const auto r_g = grad_rsrc<GDT>(grad_ptr(grads, L, s.tensor), s.e0, s.cnt);
 
     f32x4 th = load_f32(r_src, elem, s.full);
     f32x4 g = load_grad<GDT>(r_g, elem, s.full);
     f32x4 m = {0, 0, 0, 0}, v = {0, 0, 0, 0};
-    __amdgpu_buffer_rsrc_t r_m, r_v;
     if (OPT == 1) {
-        r_m = span_rsrc(s.rec.m + s.e0, bytes);
-        r_v = span_rsrc(s.rec.v + s.e0, bytes);
-        m = load_f32(r_m, elem, s.full);
-        v = load_f32(r_v, elem, s.full);
+        const bool alt = (src & kMomentsAlt) != 0;
+        m = load_f32(span_rsrc((alt ? s.rec.m_alt : s.rec.m) + s.e0, bytes), elem, s.full);
+        v = load_f32(span_rsrc((alt ? s.rec.v_alt : s.rec.v) + s.e0, bytes), elem, s.full);
     }
     const float coef = clip ? clip[clip_index] : 1.0f;          // global-norm clipping factor of this gradient
 #pragma unroll
@@ -374,8 +372,9 @@ __global__ __launch_bounds__(64) void k_optim_step(Layout L, GradArg grads, Step
     }
     if (dst_base) store_f32(span_rsrc(dst_base + s.e0, bytes), elem, s.full, th);
     if (OPT == 1 && write_moments) {
-        store_f32(r_m, elem, s.full, m);
-        store_f32(r_v, elem, s.full, v);
+        const bool alt = (dst & kMomentsAlt) != 0;
+        store_f32(span_rsrc((alt ? s.rec.m_alt : s.rec.m) + s.e0, bytes), elem, s.full, m);
+        store_f32(span_rsrc((alt ? s.rec.v_alt : s.rec.v) + s.e0, bytes), elem, s.full, v);
     }
     if (write_copy && s.rec.copy) {
         const auto r_c = span_rsrc((unsigned short *)s.rec.copy + s.e0, s.cnt * 2u);
@@ -475,25 +474,23 @@ __global__ __launch_bounds__(64) void k_reposition(Layout L, float alpha, int wr
 // ============================================================================
 template <int OPT, int GDT, bool DIAG>
 __global__ __launch_bounds__(64) void k_fused_steps_extrapolate(Layout L, GradArg g0s, GradArg g1s, StepParams p1_all,
-                                                                    StepParams p2_all, ExtrapParams e, int write_copy,
-                                                                    double *__restrict__ diag_partial,
+                                                                    StepParams p2_all, ExtrapParams e, int src, int dst,
+                                                                    int write_copy, double *__restrict__ diag_partial,
                                                                     const float *__restrict__ clip) {
     const Span s = locate(L, blockIdx.x);
     const StepParams p1 = for_tensor(p1_all, s.rec), p2 = for_tensor(p2_all, s.rec);
     const uint32_t elem = threadIdx.x * kLaneElems;
     const uint32_t bytes = s.cnt * 4u;
-    const auto r_th = span_rsrc(s.rec.theta + s.e0, bytes);
+    const auto r_th = span_rsrc(((src & kSrcProbe) ? s.rec.probe : s.rec.theta) + s.e0, bytes);
     const auto r_g0 = grad_rsrc<GDT>(grad_ptr(g0s, L, s.tensor), s.e0, s.cnt);
     const auto r_g1 = grad_rsrc<GDT>(grad_ptr(g1s, L, s.tensor), s.e0, s.cnt);
     f32x4 th0 = load_f32(r_th, elem, s.full);
     f32x4 g0 = load_grad<GDT>(r_g0, elem, s.full);
     f32x4 m = {0, 0, 0, 0}, v = {0, 0, 0, 0};
-    __amdgpu_buffer_rsrc_t r_m, r_v;
     if (OPT == 1) {
-        r_m = span_rsrc(s.rec.m + s.e0, bytes);
-        r_v = span_rsrc(s.rec.v + s.e0, bytes);
-        m = load_f32(r_m, elem, s.full);
-        v = load_f32(r_v, elem, s.full);
+        const bool alt = (src & kMomentsAlt) != 0;
+        m = load_f32(span_rsrc((alt ? s.rec.m_alt : s.rec.m) + s.e0, bytes), elem, s.full);
+        v = load_f32(span_rsrc((alt ? s.rec.v_alt : s.rec.v) + s.e0, bytes), elem, s.full);
     }
     f32x4 g1 = load_grad<GDT>(r_g1, elem, s.full);
     const float c0 = clip ? clip[kClipG0] : 1.0f, c1 = clip ? clip[kClipG1] : 1.0f;
@@ -511,10 +508,11 @@ __global__ __launch_bounds__(64) void k_fused_steps_extrapolate(Layout L, GradAr
         if (DIAG) add_extrap_diag(diag, g0[k], g1[k], si, disp2, elem + k < s.cnt);
         th0[k] = fmaf(e.alpha * si.scale, disp2, th0[k]);
     }
-    store_f32(r_th, elem, s.full, th0);
+    store_f32(span_rsrc(((dst & kSrcProbe) ? s.rec.probe : s.rec.theta) + s.e0, bytes), elem, s.full, th0);
     if (OPT == 1) {
-        store_f32(r_m, elem, s.full, m);
-        store_f32(r_v, elem, s.full, v);
+        const bool alt = (dst & kMomentsAlt) != 0;
+        store_f32(span_rsrc((alt ? s.rec.m_alt : s.rec.m) + s.e0, bytes), elem, s.full, m);
+        store_f32(span_rsrc((alt ? s.rec.v_alt : s.rec.v) + s.e0, bytes), elem, s.full, v);
     }
     if (write_copy && s.rec.copy) {
         const auto r_c = span_rsrc((unsigned short *)s.rec.copy + s.e0, s.cnt * 2u);
@@ -670,21 +668,22 @@ hipError_t launch_extrapolate(const Layout &L, int grad_dtype, const GradArg &g0
 namespace {
 template <bool DIAG>
 hipError_t fused_launch(const Layout &L, int optimizer, int grad_dtype, const GradArg &g0, const GradArg &g1, const StepParams &p1,
-                        const StepParams &p2, const ExtrapParams &e, int write_copy, double *diag, const float *clip, hipStream_t st) {
+                        const StepParams &p2, const ExtrapParams &e, int src, int dst, int write_copy, double *diag, const float *clip,
+                        hipStream_t st) {
     const dim3 grid(L.n_blocks), block(64);
-    if (optimizer == 0 && grad_dtype == 0) k_fused_steps_extrapolate<0, 0, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag, clip);
-    else if (optimizer == 0) k_fused_steps_extrapolate<0, 1, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag, clip);
-    else if (grad_dtype == 0) k_fused_steps_extrapolate<1, 0, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag, clip);
-    else k_fused_steps_extrapolate<1, 1, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, write_copy, diag, clip);
+    if (optimizer == 0 && grad_dtype == 0) k_fused_steps_extrapolate<0, 0, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, src, dst, write_copy, diag, clip);
+    else if (optimizer == 0) k_fused_steps_extrapolate<0, 1, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, src, dst, write_copy, diag, clip);
+    else if (grad_dtype == 0) k_fused_steps_extrapolate<1, 0, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, src, dst, write_copy, diag, clip);
+    else k_fused_steps_extrapolate<1, 1, DIAG><<<grid, block, 0, st>>>(L, g0, g1, p1, p2, e, src, dst, write_copy, diag, clip);
     return hipGetLastError();
 }
 }  // namespace
 
 hipError_t launch_fused_steps_extrapolate(const Layout &L, int optimizer, int grad_dtype, const GradArg &d_g0, const GradArg &d_g1,
-                                          const StepParams &p1, const StepParams &p2, const ExtrapParams &e, int write_copy,
-                                          double *d_diag_partial, const float *d_clip, hipStream_t stream) {
-    return d_diag_partial ? fused_launch<true>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, d_diag_partial, d_clip, stream)
-                          : fused_launch<false>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, write_copy, nullptr, d_clip, stream);
+                                          const StepParams &p1, const StepParams &p2, const ExtrapParams &e, int src, int dst,
+                                          int write_copy, double *d_diag_partial, const float *d_clip, hipStream_t stream) {
+    return d_diag_partial ? fused_launch<true>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, src, dst, write_copy, d_diag_partial, d_clip, stream)
+                          : fused_launch<false>(L, optimizer, grad_dtype, d_g0, d_g1, p1, p2, e, src, dst, write_copy, nullptr, d_clip, stream);
 }
 
 hipError_t launch_sumsq(const Layout &L, int grad_dtype, const GradArg &g, double *partial, int acc, hipStream_t st) {

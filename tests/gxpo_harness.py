@@ -75,7 +75,7 @@ class DeviceState:
 
     CANARY = 12345.0
 
-    def __init__(self, numels: Sequence[int], adam: bool, with_copy: bool, device="cuda"):
+    def __init__(self, numels: Sequence[int], adam: bool, with_copy: bool, device="cuda", alternating: bool = False):
         self.numels = list(numels)
         layout = [(str(i), n) for i, n in enumerate(self.numels)]
         self.layout = layout
@@ -85,6 +85,9 @@ class DeviceState:
         if adam:
             self.flat["m"] = mk(torch.float32)
             self.flat["v"] = mk(torch.float32)
+        if alternating:                          # second buffers for the moments: the engine alternates between two sets
+            self.flat["m_alt"] = mk(torch.float32)
+            self.flat["v_alt"] = mk(torch.float32)
         if with_copy:
             self.flat["model_copy"] = mk(torch.bfloat16)
         self.views = {k: synth.split_like(v, layout, 4) for k, v in self.flat.items()}
@@ -97,6 +100,11 @@ class DeviceState:
             if k in self.views:
                 for x in self.views[k]:
                     x.zero_()
+
+    @staticmethod
+    def set_keys(current_set: int):
+        """Names of the parameter, first-moment and second-moment buffers of one of the two sets."""
+        return ("theta_probe", "m_alt", "v_alt") if current_set else ("theta", "m", "v")
 
     def tensor_dicts(self) -> List[dict]:
         return [{k: self.views[k][i] for k in self.views} for i in range(len(self.numels))]
@@ -131,12 +139,13 @@ def oracle_config(cfg: B.gxpo_config) -> O.GXPOConfig:
                           min_count=(cfg.gate_min_count or None)))
 
 
-def sync_oracle_to_device(orc: O.GXPOOracle, dev: DeviceState, optim_steps: int):
-    """Make the oracle start a step from exactly the state the GPU holds."""
-    orc.theta = dev.host("theta")
+def sync_oracle_to_device(orc: O.GXPOOracle, dev: DeviceState, optim_steps: int, current_set: int = 0):
+    """Make the oracle start a step from exactly the state the GPU holds (in the buffer set that is current)."""
+    th, m, v = DeviceState.set_keys(current_set)
+    orc.theta = dev.host(th)
     if "m" in dev.views:
-        orc.m = dev.host("m")
-        orc.v = dev.host("v")
+        orc.m = dev.host(m)
+        orc.v = dev.host(v)
     orc.optim_steps = optim_steps
 
 
@@ -169,10 +178,18 @@ def lockstep_active_step(ctx: B.Context, dev: DeviceState, orc: O.GXPOOracle, gr
     """
     g0b, g1b, gsb = grads
     st = B.gxpo_get_state(ctx)
-    sync_oracle_to_device(orc, dev, st.optim_steps)
-    start = dev.host("theta")
+    # where things are: in place, theta / m / v hold the state throughout and theta_probe the first probe; with
+    # alternating state (the tensors brought m_alt, v_alt) the state moves between the two sets as the header says
+    alternating = "m_alt" in dev.views
+    c0 = st.current_set
+    assert alternating or c0 == 0
+    K_TH, K_M, K_V = DeviceState.set_keys(c0)                       # the set that holds theta^t
+    K_PROBE = DeviceState.set_keys(1 - c0)[0] if alternating else "theta_probe"
+    K_TH2, K_M2, K_V2 = DeviceState.set_keys(1 - c0) if alternating else (K_TH, K_M, K_V)       # where theta~ goes
+    sync_oracle_to_device(orc, dev, st.optim_steps, c0)
+    start = dev.host(K_TH)
     adam = "m" in dev.views
-    m_start, v_start = (dev.host("m"), dev.host("v")) if adam else (None, None)
+    m_start, v_start = (dev.host(K_M), dev.host(K_V)) if adam else (None, None)
 
     def compare(key_gpu: str, ref_list, label, disp_from=None, amplified=False):
         got = dev.host(key_gpu)
@@ -193,28 +210,28 @@ def lockstep_active_step(ctx: B.Context, dev: DeviceState, orc: O.GXPOOracle, gr
             assert num <= dtol * den + floor, (f"{what} {label}: displacement error {num:.3e} vs displacement {den:.3e} "
                                                f"(dtol {dtol}, fp32 storage floor {floor:.3e})")
 
-    def compare_moments(label):
+    def compare_moments(label, km=K_M, kv=K_V):
         if adam:
-            compare("m", orc.m, label + " m")
-            compare("v", orc.v, label + " v")
+            compare(km, orc.m, label + " m")
+            compare(kv, orc.v, label + " v")
 
     # fast step 1
-    grad_fn(dev.views["theta"], g0b)
+    grad_fn(dev.views[K_TH], g0b)
     B.gxpo_fast_steps(ctx, 0, g0b)
     ref1 = orc.fast_step_1([f64(g) for g in g0b])
-    compare("theta_probe", ref1, "theta^{t,1}", start)
+    compare(K_PROBE, ref1, "theta^{t,1}", start)
     if fused:
         # the probe pass only previews the step: the stored moments are advanced by gxpo_extrapolate
         if adam:
-            for k, before in (("m", m_start), ("v", v_start)):
+            for k, before in ((K_M, m_start), (K_V, v_start)):
                 for g, b in zip(dev.host(k), before):
                     np.testing.assert_array_equal(g, b, err_msg=f"{what}: {k} changed by the probe pass of the fused schedule")
     else:
         compare_moments("after fast step 1")
-    for g, s in zip(dev.host("theta"), start):
+    for g, s in zip(dev.host(K_TH), start):
         np.testing.assert_array_equal(g, s, err_msg=f"{what}: theta^t modified by the first fast step")
     # fast step 2
-    grad_fn(dev.views["theta_probe"], g1b)
+    grad_fn(dev.views[K_PROBE], g1b)
     B.gxpo_fast_steps(ctx, 1, g1b)
     ref2 = orc.fast_step_2([f64(g) for g in g1b])
     if not fused:
@@ -222,20 +239,26 @@ def lockstep_active_step(ctx: B.Context, dev: DeviceState, orc: O.GXPOOracle, gr
         compare_moments("after fast step 2")
     # extrapolate + reposition
     B.gxpo_extrapolate(ctx, g0b, g1b)
+    assert B.gxpo_get_state(ctx).current_set == (1 - c0 if alternating else 0)
     ref_t = orc.extrapolate([f64(g) for g in g0b], [f64(g) for g in g1b])
-    compare("theta", ref_t, "theta~", start, amplified=True)
-    compare_moments("after extrapolate")
+    compare(K_TH2, ref_t, "theta~", start, amplified=True)
+    compare_moments("after extrapolate", K_M2, K_V2)
+    if alternating:                                                 # the set that was read still holds the step's start
+        for k, before in ((K_TH, start), (K_M, m_start), (K_V, v_start)):
+            for g, b in zip(dev.host(k), before):
+                np.testing.assert_array_equal(g, b, err_msg=f"{what}: {k} (the set gxpo_extrapolate reads) changed")
     if check_copy and (ctx.cfg.copy_mask & B.GXPO_COPY_AT_TILDE):
-        check_bf16_copy(dev, ref_t, what + " theta~")
+        check_bf16_copy_of(dev, K_TH2, ref_t, what + " theta~")
     # slow step
-    grad_fn(dev.views["theta"], gsb)
+    grad_fn(dev.views[K_TH2], gsb)
     gs_host = [f64(g) for g in gsb]
     B.gxpo_slow_step(ctx, gsb)
+    assert B.gxpo_get_state(ctx).current_set == c0
     ref_n = orc.slow_step(gs_host)
-    compare("theta", ref_n, "theta^{t+1}", start, amplified=True)
+    compare(K_TH, ref_n, "theta^{t+1}", start, amplified=True)
     compare_moments("after slow step")
     if check_copy and (ctx.cfg.copy_mask & B.GXPO_COPY_AT_FINAL):
-        check_bf16_copy(dev, ref_n, what + " theta^{t+1}")
+        check_bf16_copy_of(dev, K_TH, ref_n, what + " theta^{t+1}")
     # gate
     info = B.gxpo_gate(ctx)
     ref_info = orc.gate_step()

@@ -26,7 +26,7 @@ hipError_t launch_extrapolate(const Layout &, int, const GradArg &, const GradAr
                               hipStream_t) { return never(); }
 hipError_t launch_reposition(const Layout &, float, int, hipStream_t) { return never(); }
 hipError_t launch_fused_steps_extrapolate(const Layout &, int, int, const GradArg &, const GradArg &, const StepParams &, const StepParams &,
-                                          const ExtrapParams &, int, double *, const float *, hipStream_t) { return never(); }
+                                          const ExtrapParams &, int, int, int, double *, const float *, hipStream_t) { return never(); }
 hipError_t launch_finalize(const double *, uint32_t, const SegRec *, uint32_t, const uint32_t *, uint32_t, double *, double *, int, int,
                            hipStream_t) { return never(); }
 hipError_t launch_stream_copy(void *, const void *, uint64_t, hipStream_t) { return never(); }

@@ -32,9 +32,9 @@ def quad_trainer(problem, numels, sigma=None, step_noise=None):
     return grad_fn
 
 
-def build(numels, cfg, problem, with_copy=False):
+def build(numels, cfg, problem, with_copy=False, alternating=False):
     adam = cfg.optimizer == B.GXPO_OPT_ADAMW
-    dev = H.DeviceState(numels, adam, with_copy)
+    dev = H.DeviceState(numels, adam, with_copy, alternating=alternating)
     offs = np.concatenate([[0], np.cumsum(numels)])
     dev.set_theta([problem.theta_0[offs[i]:offs[i + 1]] for i in range(len(numels))])
     ctx = B.gxpo_init(cfg, dev.tensor_dicts())
@@ -75,25 +75,26 @@ def test_surrogate_config1_lockstep_and_closed_form(fused, alpha):
 # ---------------------------------------------------------------------------------------------
 # config 2 shape at reduced size: AdamW, noisy quadratic, K = 8, ragged multi-tensor
 # ---------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("fused", [True, False])
+@pytest.mark.parametrize("fused,alternating", [(True, False), (False, False), (True, True)])
 @pytest.mark.parametrize("grad_dtype", ["f32", "bf16"])
-def test_adamw_ragged_lockstep(fused, grad_dtype):
+def test_adamw_ragged_lockstep(fused, alternating, grad_dtype):
     numels = RAGGED
     P = sum(numels)
     problem = synth.policy_problem(P, seed=1, sigma=0.05, device="cuda")
     cfg = B.make_config(optimizer="adamw", grad_dtype=grad_dtype, K=8, alpha=0.5, delta=1.75e-3, lr=1e-6,
                         weight_decay=0.01, fuse_step2=fused, tau=3.0, window=10, gate_min_count=2,
                         copy_mask=7)
-    dev, ctx, orc, grads = build(numels, cfg, problem, with_copy=True)
+    dev, ctx, orc, grads = build(numels, cfg, problem, with_copy=True, alternating=alternating)
     step_id = [0]
     noise = lambda: synth.step_noise(problem, step_id[0])
     grad_fn = quad_trainer(problem, numels, step_noise=noise)
     for step in range(4):
         step_id[0] = step
         H.lockstep_active_step(ctx, dev, orc, grad_fn, grads, dtol=1e-4, fused=fused, check_copy=True,
-                               what=f"{grad_dtype} fused={fused} step {step}")
+                               what=f"{grad_dtype} fused={fused} alternating={alternating} step {step}")
     st = B.gxpo_get_state(ctx)
     assert (st.t, st.optim_steps, st.backward_passes) == (4, 12, 12)
+    dev.check_canaries()
 
 
 @pytest.mark.parametrize("grad_dtype", ["f32", "bf16"])
@@ -1119,6 +1120,163 @@ def test_fused_replay_is_bit_identical_to_the_unfused_passes(optimizer, grad_dty
             B.gxpo_gate(ctx)
     for fused in (True, False):
         B.gxpo_destroy(runs[fused][1])
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("grad_dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("clip_norm,diagnostics", [(0.0, False), (0.5, False), (0.0, True)])
+def test_alternating_state_is_bit_identical_to_the_in_place_schedule(grad_dtype, clip_norm, diagnostics):
+    """Two buffer sets ({theta, m, v} and {theta_probe, m_alt, v_alt}): every state-advancing pass reads one and
+    writes the other.  Same inputs through the in-place schedule (checked against the oracle by the other tests)
+    and the alternating one: after every call the iterate the call produces, the moments, the bf16 copy, the
+    norm and the gate's decision are bit-identical, they are where gxpo_state.current_set says, and the set
+    that was read is untouched.  Active steps, then fallback steps (which alternate), then a resume from a
+    checkpoint taken while set 1 was current.  (The alternating schedule is also compared with the oracle
+    directly, call by call, in test_adamw_ragged_lockstep.)"""
+    numels = RAGGED
+    P = sum(numels)
+    problem = synth.policy_problem(P, seed=41, sigma=0.05, device="cuda")
+    cfg = B.make_config(optimizer="adamw", grad_dtype=grad_dtype, K=6, alpha=0.5, delta=1.75e-3, lr=1e-4, weight_decay=0.01,
+                        clip_norm=clip_norm, diagnostics=diagnostics, copy_mask=7, r_max=4.0, tau=1e9)
+    ref_dev, ref_ctx, orc, (g0, g1, gs) = build(numels, cfg, problem, with_copy=True)
+    alt_dev, alt_ctx, _, _ = build(numels, cfg, problem, with_copy=True, alternating=True)
+    step_id = [0]
+    grad_fn = quad_trainer(problem, numels, step_noise=lambda: synth.step_noise(problem, step_id[0]))
+    raw = lambda x: x.view(torch.int32) if x.element_size() == 4 else x.view(torch.int16)
+
+    def same(key_ref, key_alt, what):
+        for i, (a, b) in enumerate(zip(ref_dev.views[key_ref], alt_dev.views[key_alt])):
+            assert torch.equal(raw(a), raw(b)), f"{what}: tensor {i}, {key_ref} (in place) differs from {key_alt} (alternating)"
+
+    def same_state(what):
+        cur = B.gxpo_get_state(alt_ctx).current_set
+        th, m, v = H.DeviceState.set_keys(cur)
+        same("theta", th, what), same("m", m, what), same("v", v, what), same("model_copy", "model_copy", what)
+        return cur
+
+    def snapshot(cur):
+        return [x.clone() for k in H.DeviceState.set_keys(cur) for x in alt_dev.views[k]]
+
+    def untouched(cur, before, what):
+        now = [x for k in H.DeviceState.set_keys(cur) for x in alt_dev.views[k]]
+        assert all(torch.equal(raw(a), raw(b)) for a, b in zip(before, now)), f"{what}: the set that was read has changed"
+
+    def both(fn):
+        return fn(ref_ctx), fn(alt_ctx)
+
+    assert B.gxpo_get_state(alt_ctx).current_set == 0 and B.gxpo_get_state(ref_ctx).current_set == 0
+    for step in range(3):
+        step_id[0] = step
+        c = B.gxpo_get_state(alt_ctx).current_set
+        assert c == 0                                               # an active step ends in the set it started in
+        th_c, _, _ = H.DeviceState.set_keys(c)
+        th_o, _, _ = H.DeviceState.set_keys(1 - c)
+        grad_fn(ref_dev.views["theta"], g0)
+        before = snapshot(c)
+        both(lambda ctx: B.gxpo_fast_steps(ctx, 0, g0))
+        same("theta_probe", th_o, f"step {step}, theta^(t,1)")
+        untouched(c, before, f"step {step}, first fast step")
+        grad_fn(ref_dev.views["theta_probe"], g1)
+        both(lambda ctx: B.gxpo_fast_steps(ctx, 1, g1))
+        both(lambda ctx: B.gxpo_extrapolate(ctx, g0, g1))
+        assert B.gxpo_get_state(alt_ctx).current_set == 1 - c and B.gxpo_get_state(ref_ctx).current_set == 0
+        same_state(f"step {step}, after gxpo_extrapolate")
+        untouched(c, before, f"step {step}, gxpo_extrapolate")      # theta^t, m, v of the step's start are still there
+        grad_fn(ref_dev.views["theta"], gs)
+        before = snapshot(1 - c)
+        both(lambda ctx: B.gxpo_slow_step(ctx, gs))
+        assert B.gxpo_get_state(alt_ctx).current_set == c
+        same_state(f"step {step}, after gxpo_slow_step")
+        untouched(1 - c, before, f"step {step}, gxpo_slow_step")
+        assert B.gxpo_tensor_norms(ref_ctx) == B.gxpo_tensor_norms(alt_ctx)
+        if diagnostics:
+            da, db = both(B.gxpo_get_diagnostics)
+            assert all(getattr(da, k) == getattr(db, k) or (getattr(da, k) != getattr(da, k) and getattr(db, k) != getattr(db, k))
+                       for k, _ in da._fields_)
+        ia, ib = both(B.gxpo_gate)
+        assert (ia.norm, ia.tripped, ia.s_star) == (ib.norm, ib.tripped, ib.s_star)
+    alt_dev.check_canaries()
+
+    # fallback steps alternate between the sets
+    for ctx in (ref_ctx, alt_ctx):
+        st = B.gxpo_get_state(ctx)
+        st.s_star = st.t
+        B.gxpo_set_state(ctx, st)
+    checkpoint = None
+    for k in range(3):
+        step_id[0] = 10 + k
+        c = B.gxpo_get_state(alt_ctx).current_set
+        assert c == k % 2
+        grad_fn(ref_dev.views["theta"], g0)
+        before = snapshot(c)
+        both(lambda ctx: B.gxpo_fallback_step(ctx, g0))
+        assert same_state(f"fallback step {k}") == 1 - c
+        untouched(c, before, f"fallback step {k}")
+        if k == 0:
+            checkpoint = B.gxpo_get_state(alt_ctx)                  # set 1 is current here
+            saved = {key: [x.clone() for x in alt_dev.views[key]] for key in alt_dev.views}
+    assert checkpoint.current_set == 1
+    final = {key: [x.clone() for x in alt_dev.views[key]] for key in ("theta", "theta_probe", "m", "v", "m_alt", "v_alt", "model_copy")}
+
+    # resume from the checkpoint in a new context: the same two fallback steps give the same bits
+    B.gxpo_destroy(alt_ctx)
+    for key, views in saved.items():
+        for dst, src in zip(alt_dev.views[key], views):
+            dst.copy_(src)
+    alt_ctx = B.gxpo_init(cfg, alt_dev.tensor_dicts())
+    B.gxpo_set_state(alt_ctx, checkpoint)
+    for k in (1, 2):
+        step_id[0] = 10 + k
+        cur = H.DeviceState.set_keys(B.gxpo_get_state(alt_ctx).current_set)[0]
+        grad_fn(alt_dev.views[cur], g0)
+        B.gxpo_fallback_step(alt_ctx, g0)
+    for key, views in final.items():
+        if key in H.DeviceState.set_keys(B.gxpo_get_state(alt_ctx).current_set) or key == "model_copy":
+            assert all(torch.equal(raw(a), raw(b)) for a, b in zip(views, alt_dev.views[key])), f"resume: {key} differs"
+    alt_dev.check_canaries()
+
+    # an in-place context has no second set to point at
+    st = B.gxpo_get_state(ref_ctx)
+    st.current_set = 1
+    with pytest.raises(B.GxpoError) as e:
+        B.gxpo_set_state(ref_ctx, st)
+    assert e.value.code == B.GXPO_ERR_INVALID_ARG
+    B.gxpo_destroy(ref_ctx)
+    B.gxpo_destroy(alt_ctx)
+
+
+@pytest.mark.gpu
+def test_alternating_state_is_refused_where_it_cannot_work():
+    numels = [1000, 4099]
+    dev = H.DeviceState(numels, True, False, alternating=True)
+    ok = B.make_config(optimizer="adamw")
+    for bad in (dict(fuse_step2=False), dict(explicit_steps=3)):
+        with pytest.raises(B.GxpoError) as e:
+            B.gxpo_init(B.make_config(optimizer="adamw", **bad), dev.tensor_dicts())
+        assert e.value.code == B.GXPO_ERR_UNSUPPORTED
+    dicts = dev.tensor_dicts()
+    del dicts[1]["v_alt"]                                           # half a pair
+    with pytest.raises(B.GxpoError) as e:
+        B.gxpo_init(ok, dicts)
+    assert e.value.code == B.GXPO_ERR_INVALID_ARG
+    dicts = dev.tensor_dicts()
+    del dicts[1]["m_alt"], dicts[1]["v_alt"]                        # one tensor with, one without
+    with pytest.raises(B.GxpoError) as e:
+        B.gxpo_init(ok, dicts)
+    assert e.value.code == B.GXPO_ERR_INVALID_ARG
+    dicts = dev.tensor_dicts()
+    for d in dicts:
+        del d["theta_probe"]                                        # no second parameter buffer
+    with pytest.raises(B.GxpoError) as e:
+        B.gxpo_init(ok, dicts)
+    assert e.value.code == B.GXPO_ERR_INVALID_ARG
+    dicts = dev.tensor_dicts()
+    dicts[0]["m_alt"] = dicts[0]["m"]                               # aliasing the first set
+    with pytest.raises(B.GxpoError) as e:
+        B.gxpo_init(ok, dicts)
+    assert e.value.code == B.GXPO_ERR_INVALID_ARG
+    ctx = B.gxpo_init(ok, dev.tensor_dicts())                       # and the plain case works
+    B.gxpo_destroy(ctx)
 
 
 # ---------------------------------------------------------------------------------------------

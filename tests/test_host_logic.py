@@ -55,7 +55,7 @@ def test_plain_c_driver_links_against_the_library():
 
 def test_struct_sizes_match_the_header_layout():
     # natural C layout of the header's structs on x86-64
-    assert ctypes.sizeof(B.gxpo_tensor) == 8 + 5 * 8
+    assert ctypes.sizeof(B.gxpo_tensor) == 8 + 7 * 8
     assert ctypes.sizeof(B.gxpo_config) == 12 * 4 + 11 * 8
     assert ctypes.sizeof(B.gxpo_tensor_options) == 2 * 8
     assert ctypes.sizeof(B.gxpo_diagnostics) == 9 * 8 + 8
