@@ -48,6 +48,9 @@ def parse_args():
     ap.add_argument("--placement", default="auto", choices=["auto", "ranked", "ranked-scatter", "ranked-adjacent", "phased"],
                     help="ranked: rank-aware placement through HIP's virtual-memory API; phased: one plain allocation per buffer")
     ap.add_argument("--phases", default="", help="experiment: KiB phases (mod 64) of theta,theta_probe,m,v,g0,g1,g2[,model_copy]")
+    ap.add_argument("--alternating", action="store_true",
+                    help="two buffer sets (theta_probe, m_alt, v_alt next to theta, m, v; 8 B/param more) that every pass alternates "
+                         "between instead of updating in place")
     ap.add_argument("--no-probe", action="store_true",
                     help="workloads with a bf16 model copy: deliver theta^{t,1} through the copy only (no fp32 theta_probe)")
     ap.add_argument("--explicit-steps", type=int, default=0, help="explicit lookahead with this many real fast steps instead of GXPO")
@@ -154,9 +157,19 @@ def measure(name: str, args, want_cpu_inputs: bool = False):
         gflat = [torch.empty(padded, dtype=gdt, device=dev) for _ in range(3)]
         placement = {"kind": "same-phase", "detail": None}
     else:
-        flat, gflat = layout_mod.alloc_engine_state(padded, dev, adam=adam, model_copy=spec["copy"], grad_dtype=gdt,
-                                                    arena=args.arena, phases_kib=phases, placement=args.placement,
-                                                    probe_is_read=not fused, verbose=True)
+        # on request: two buffer sets the passes alternate between (8 B/param more HBM), where the schedule allows and they fit
+        alternating = args.alternating and adam and fused and not spec.get("no_probe") and not args.arena
+        kw = dict(adam=adam, model_copy=spec["copy"], grad_dtype=gdt, arena=args.arena, phases_kib=phases, placement=args.placement,
+                  probe_is_read=not fused, verbose=True)
+        try:
+            flat, gflat = layout_mod.alloc_engine_state(padded, dev, alternating=alternating, **kw)
+        except Exception as e:
+            if not alternating:
+                raise
+            print(f"[{name}] no room for the second set of moments ({type(e).__name__}: {e}); updating in place", file=sys.stderr)
+            gc.collect()
+            torch.cuda.empty_cache()
+            flat, gflat = layout_mod.alloc_engine_state(padded, dev, **kw)
         placement = layout_mod.last_placement()
     print(f"[{name}] base addresses:", {k: hex(v.data_ptr()) for k, v in flat.items()}, [hex(g.data_ptr()) for g in gflat], file=sys.stderr)
     views = {k: synth.split_like(v, layout, 4) for k, v in flat.items()}
@@ -187,7 +200,8 @@ def measure(name: str, args, want_cpu_inputs: bool = False):
         B.gxpo_extrapolate(ctx)
     else:
         B.gxpo_extrapolate(ctx, g0, g1)
-    quad.grad(flat["theta"], 0, gflat[2])
+    # with alternating state theta~ is in the other set's parameter buffer (gxpo_state.current_set)
+    quad.grad(flat["theta_probe" if B.gxpo_get_state(ctx).current_set else "theta"], 0, gflat[2])
     B.gxpo_slow_step(ctx, gs)
     live_info = B.gxpo_gate(ctx)
 
@@ -282,15 +296,18 @@ def measure(name: str, args, want_cpu_inputs: bool = False):
         st = B.gxpo_get_state(ctx)
         st.s_star = st.t
         B.gxpo_set_state(ctx, st)
-        for _ in range(args.warmup):
-            B.gxpo_fallback_step(ctx, g0)
+        # with alternating state the steps read the two sets in turn; the gradient buffer next to each set is used
+        # (the third buffer lies next to the second set), as a trainer with two gradient buffers would
+        two_sets = "m_alt" in flat
+        for i in range(args.warmup + args.warmup % 2):
+            B.gxpo_fallback_step(ctx, gs if two_sets and i % 2 else g0)
         torch.cuda.synchronize()
         fev = []
         tf0 = time.perf_counter()
-        for _ in range(args.steps):
+        for i in range(args.steps):
             fa, fb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             fa.record()
-            B.gxpo_fallback_step(ctx, g0)
+            B.gxpo_fallback_step(ctx, gs if two_sets and i % 2 else g0)
             fb.record()
             fev.append((fa, fb))
         torch.cuda.synchronize()
@@ -303,6 +320,8 @@ def measure(name: str, args, want_cpu_inputs: bool = False):
     if placement["kind"] == "ranked":
         hbm_layout = "rank-aware placement (read streams of a slab in one DRAM rank" + (
             ", theta/m/v chunks chosen by measurement" if (placement["detail"] or {}).get("tuned") else "") + "), moments +32KiB mod 64KiB"
+    if "m_alt" in flat:
+        hbm_layout += "; two buffer sets, every pass reads one and writes the other (alternating state)"
     elif placement["kind"] == "same-phase":
         hbm_layout = "same-phase"
     else:

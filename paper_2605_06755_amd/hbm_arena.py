@@ -110,15 +110,16 @@ def _scatter(chunks: List[int], seed: int) -> List[int]:
 def plan_chunks(labels: Sequence[int], specs: Sequence[dict], chunk_bytes: int = CHUNK_BYTES, available: Optional[Sequence[int]] = None,
                 scatter: bool = True):
     """Which chunk backs which part of which buffer.  Pure bookkeeping (no GPU): `labels[i]` is the rank class of chunk
-    i, `specs` are dicts with name, numel, itemsize, group ('update' = read and written, 'read', or 'write') and
-    optionally phase_bytes; all buffers index the same elements.  Per slab of SLAB_ELEMS elements the chunks of every
-    'update' and 'read' buffer come from one class
-    (the planner stays in a class while it has room for a whole slab, then moves to the class with most room); 'write'
-    buffers are served afterwards from what is left, from another class than their slab's where possible.
+    i, `specs` are dicts with name, numel, itemsize, group ('update' = read and written, 'read', or 'write'),
+    optionally set (0 or 1, default 0) and phase_bytes; all buffers index the same elements.  Per slab of SLAB_ELEMS
+    elements the chunks of every 'update' and 'read' buffer of set 0 come from one class (the planner stays in a class
+    while it has room for a whole slab, then moves to the class with most room), those of set 1 -- the second buffer
+    set of the alternating schedule, which a pass writes while it reads set 0, and the other way round -- from one
+    other class; 'write' buffers are served afterwards from what is left, away from set 0's class where possible.
     Inside a class the chunks are handed out in a fixed pseudo-random order (`scatter`) rather than in index order:
     streams that advance in step through neighbouring or evenly spaced chunks of physical memory were measured
     0.5-1.5 % slower than streams whose chunks have no regular relation to each other.
-    Returns (name -> chunk ids in address order, class of each slab)."""
+    Returns (name -> chunk ids in address order, class of set 0 for each slab)."""
     free: Dict[int, List[int]] = {}
     for i in (range(len(labels)) if available is None else available):
         free.setdefault(labels[i], []).append(i)
@@ -129,21 +130,29 @@ def plan_chunks(labels: Sequence[int], specs: Sequence[dict], chunk_bytes: int =
     n_slabs = max(-(-need[s["name"]] // per_slab[s["name"]]) for s in specs)
     plan = {s["name"]: [] for s in specs}
     wants = lambda s, slab: max(0, min(per_slab[s["name"]], need[s["name"]] - slab * per_slab[s["name"]]))
-    reads = [s for s in specs if s["group"] in ("read", "update")]
+    together = [[s for s in specs if s["group"] in ("read", "update") and s.get("set", 0) == k] for k in (0, 1)]
     writes = [s for s in specs if s["group"] == "write"]
 
-    # 1. which class hosts the read streams of each slab: stay while a whole slab fits, then move to the roomiest class
+    # 1. which class hosts each set's streams of each slab: stay while a whole slab fits, then move to the roomiest
+    #    class; set 1 takes a class other than set 0's as long as one has room
     left = {lab: len(lst) for lab, lst in free.items()}
     roomiest = lambda: sorted(left, key=lambda lab: (-left[lab], lab))
-    slab_rank, current = [], None
+    slab_rank = [[], []]
+    current = [None, None]
     for slab in range(n_slabs):
-        read_need = sum(wants(s, slab) for s in reads)
-        if current is None or left[current] < read_need:
-            fits = [lab for lab in roomiest() if left[lab] >= read_need]
-            current = fits[0] if fits else None
-        slab_rank.append(current)                          # None: no class can hold this slab's read streams whole
-        if current is not None:
-            left[current] -= read_need
+        for k in (0, 1):
+            want = sum(wants(s, slab) for s in together[k])
+            if not together[k]:
+                slab_rank[k].append(None)
+                continue
+            avoid = slab_rank[0][slab] if k == 1 else None
+            if current[k] is None or left[current[k]] < want or current[k] == avoid:
+                fits = [lab for lab in roomiest() if left[lab] >= want]
+                fits = [lab for lab in fits if lab != avoid] or fits
+                current[k] = fits[0] if fits else None
+            slab_rank[k].append(current[k])                # None: no class can hold this set's streams of the slab whole
+            if current[k] is not None:
+                left[current[k]] -= want
 
     def take(label_order, count):
         out = []
@@ -157,25 +166,26 @@ def plan_chunks(labels: Sequence[int], specs: Sequence[dict], chunk_bytes: int =
         return out
 
     room = lambda: sorted(free, key=lambda lab: (-len(free[lab]), lab))
-    # 2. the read streams, slab by slab, from the slab's class; slabs no class could hold whole spill over classes
-    for slab in range(n_slabs):
-        if slab_rank[slab] is None:
-            continue
-        for s in reads:
-            plan[s["name"]] += [(slab, c) for c in take([slab_rank[slab]], wants(s, slab))]
-    for slab in range(n_slabs):
-        if slab_rank[slab] is None:
-            slab_rank[slab] = room()[0]
-            for s in reads:
-                if wants(s, slab):
-                    plan[s["name"]] += [(slab, c) for c in take(room(), wants(s, slab))]
+    # 2. the co-located streams, slab by slab, from their class; slabs no class could hold whole spill over classes
+    for k in (0, 1):
+        for slab in range(n_slabs):
+            if slab_rank[k][slab] is not None:
+                for s in together[k]:
+                    plan[s["name"]] += [(slab, c) for c in take([slab_rank[k][slab]], wants(s, slab))]
+    for k in (0, 1):
+        for slab in range(n_slabs):
+            if together[k] and slab_rank[k][slab] is None:
+                slab_rank[k][slab] = room()[0]
+                for s in together[k]:
+                    if wants(s, slab):
+                        plan[s["name"]] += [(slab, c) for c in take(room(), wants(s, slab))]
     # 3. the write-only streams, from what is left, away from the class their slab is read from
     for slab in range(n_slabs):
-        order = [lab for lab in room() if lab != slab_rank[slab]] + [slab_rank[slab]]
+        order = [lab for lab in room() if lab != slab_rank[0][slab]] + [slab_rank[0][slab]]
         for s in writes:
             if wants(s, slab):
                 plan[s["name"]] += [(slab, c) for c in take(order, wants(s, slab))]
-    return {name: [c for _, c in sorted(v, key=lambda x: x[0])] for name, v in plan.items()}, slab_rank
+    return {name: [c for _, c in sorted(v, key=lambda x: x[0])] for name, v in plan.items()}, slab_rank[0]
 
 
 def _lcg(seed: int):
@@ -400,95 +410,143 @@ class RankedArena:
         for theta, m, v there plus the spare ones) are timed with the engine's fallback step on windows at the
         start of the chunks, against the chunks planned there for the first and the last gradient stream (what the
         fused pass and the fallback step read, and what the slow step reads), and the best triple is kept.
+        With the second buffer set of the alternating schedule (theta_probe, m_alt, v_alt as 'update' buffers of
+        set 1) each set's triple is chosen while it is the written one: set 1 against set 0's planned triple and
+        the first gradient of set 0, then set 0 against the chosen set 1 and the first gradient of set 1.
         Edits `plan` in place; leaves it alone when the buffers are not the AdamW set."""
-        upd = [s for s in specs if s["group"] == "update"]
-        reads = [s for s in specs if s["group"] == "read"]
-        if [s["name"] for s in upd] != ["theta", "m", "v"] or not reads or any(s["dtype"] != torch.float32 for s in upd) \
-                or any(s.get("phase_bytes", 0) >= 65536 for s in upd + reads[:1]):
-            return
         cb, labels = self.chunk_bytes, self.labels
-        names = [s["name"] for s in upd]
-        n_pos = min(len(plan[n]) for n in names)
-        used = {c for chunks in plan.values() for c in chunks}
-        pools: Dict[int, List[int]] = {}
-        for c in available:
-            if c not in used:
-                pools.setdefault(labels[c], []).append(c)
-        positions = []
-        for k in range(n_pos):
-            labs = {labels[plan[n][k]] for n in names}
-            lab = labs.pop() if len(labs) == 1 else None
-            positions.append(lab)
-            if lab is not None:
-                pools.setdefault(lab, []).extend(plan[n][k] for n in names)
-        for lab in pools:
-            pools[lab].sort()
-        # the gradient streams the written passes read: the first (fused pass, fallback step) and the last (slow step)
-        g_specs = [reads[0]] + ([reads[-1]] if len(reads) > 1 and reads[-1]["dtype"] == reads[0]["dtype"] else [])
-        g_size = torch.empty((), dtype=g_specs[0]["dtype"]).element_size()
+        upd = [[s for s in specs if s["group"] == "update" and s.get("set", 0) == k] for k in (0, 1)]
+        reads = [[s for s in specs if s["group"] == "read" and s.get("set", 0) == k] for k in (0, 1)]
+        alternating = [s["name"] for s in upd[1]] == ["theta_probe", "m_alt", "v_alt"]
+        every = upd[0] + upd[1] + reads[0] + reads[1]
+        if [s["name"] for s in upd[0]] != ["theta", "m", "v"] or (upd[1] and not alternating) or not reads[0] \
+                or (alternating and not reads[1]) or any(s["dtype"] != torch.float32 for s in upd[0] + upd[1]) \
+                or any(s.get("phase_bytes", 0) >= 65536 for s in every) or len({s["dtype"] for s in reads[0] + reads[1]}) != 1:
+            return
+        g_size = torch.empty((), dtype=reads[0][0]["dtype"]).element_size()
         E = (cb - 65536) // 4
+        n_pos = min(len(plan[s["name"]]) for s in upd[0] + upd[1])
         va = self._reserve(len(self.handles) * cb)
         for c in available:
             self._map(va + c * cb, c)
         cfg = _B.make_config(K=2, lr=1e-9, weight_decay=0.0, delta=0.0, grad_dtype="f32" if g_size == 4 else "bf16")
+        f32 = lambda c, s: self._tensor(va + c * cb + s.get("phase_bytes", 0), E, torch.float32)
+
+        def gradient_window(g_spec, k):
+            at = k * (cb // 4) * g_size                                          # where position k starts in the gradient buffer
+            chunk = plan[g_spec["name"]][min(at // cb, len(plan[g_spec["name"]]) - 1)]
+            g = self._tensor(va + chunk * cb + min(at % cb, cb - E * g_size), E, g_spec["dtype"])
+            g.normal_(std=0.05)
+            return g
+
+        def timed(ctx, g, before_each=None):
+            if before_each:
+                before_each()
+            _B.gxpo_fallback_step(ctx, [g])
+            best = float("inf")
+            for _ in range(2):                                                   # disturbances only slow a measurement down
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for _ in range(3):
+                    if before_each:
+                        before_each()
+                    _B.gxpo_fallback_step(ctx, [g])
+                b.record()
+                b.synchronize()
+                best = min(best, a.elapsed_time(b) / 3)
+            return best
+
+        def pools_and_positions(which):
+            """Per chunk position the class the triple of set `which` is planned in (None where its three chunks
+            disagree), and per class the chunks a triple may be drawn from: the planned ones plus the spare ones."""
+            names = [s["name"] for s in upd[which]]
+            used = {c for chunks in plan.values() for c in chunks}
+            pools: Dict[int, List[int]] = {}
+            for c in available:
+                if c not in used:
+                    pools.setdefault(labels[c], []).append(c)
+            positions = []
+            for k in range(n_pos):
+                labs = {labels[plan[n][k]] for n in names}
+                lab = labs.pop() if len(labs) == 1 else None
+                positions.append(lab)
+                if lab is not None:
+                    pools.setdefault(lab, []).extend(plan[n][k] for n in names)
+            for lab in pools:
+                pools[lab].sort()
+            return names, pools, positions
+
+        stats = []
         cache = {}
-
-        def gradients(k):
-            if cache.get("k") != k:
-                gs = []
-                for g_spec in g_specs:
-                    at = k * (cb // 4) * g_size                                  # where position k starts in the gradient buffer
-                    chunk = plan[g_spec["name"]][min(at // cb, len(plan[g_spec["name"]]) - 1)]
-                    off = min(at % cb, cb - E * g_size)
-                    g = self._tensor(va + chunk * cb + off, E, g_spec["dtype"])
-                    g.normal_(std=0.05)
-                    gs.append(g)
-                cache.update(k=k, gs=gs)
-            return cache["gs"]
-
-        def measure(k, tup):
-            th, m, v = (self._tensor(va + c * cb + s.get("phase_bytes", 0), E, torch.float32) for c, s in zip(tup, upd))
-            th.normal_(std=0.02)
-            m.zero_()
-            v.fill_(1e-4)
-            ctx = _B.gxpo_init(cfg, [dict(theta=th, m=m, v=v)])
-            st = _B.gxpo_get_state(ctx)
-            st.s_star = 0
-            _B.gxpo_set_state(ctx, st)
-            total_ms = 0.0
-            for g in gradients(k):
-                _B.gxpo_fallback_step(ctx, [g])
-                best = float("inf")
-                for _ in range(2):                                               # disturbances only slow a measurement down
-                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    a.record()
-                    for _ in range(3):
-                        _B.gxpo_fallback_step(ctx, [g])
-                    b.record()
-                    b.synchronize()
-                    best = min(best, a.elapsed_time(b) / 3)
-                total_ms += best
-            _B.gxpo_destroy(ctx)
-            return len(g_specs) * (24.0 + g_size) * E / total_ms / 1e6
-
         try:
-            tuples, seen = choose_tuples(pools, positions, len(names), candidates, measure)
+            if not alternating:
+                names, pools, positions = pools_and_positions(0)
+                g_specs = [reads[0][0]] + ([reads[0][-1]] if len(reads[0]) > 1 else [])
+
+                def measure(k, tup):
+                    if cache.get("k") != k:
+                        cache.update(k=k, gs=[gradient_window(g, k) for g in g_specs])
+                    th, m, v = (f32(c, s) for c, s in zip(tup, upd[0]))
+                    th.normal_(std=0.02), m.zero_(), v.fill_(1e-4)
+                    ctx = _B.gxpo_init(cfg, [dict(theta=th, m=m, v=v)])
+                    st = _B.gxpo_get_state(ctx)
+                    st.s_star = 0
+                    _B.gxpo_set_state(ctx, st)
+                    total_ms = sum(timed(ctx, g) for g in cache["gs"])
+                    _B.gxpo_destroy(ctx)
+                    return len(g_specs) * (24.0 + g_size) * E / total_ms / 1e6
+
+                tuples, seen = choose_tuples(pools, positions, 3, candidates, measure)
+                stats.append(("theta, m, v", seen))
+                for k, tup in enumerate(tuples):
+                    if tup is not None:
+                        for n, c in zip(names, tup):
+                            plan[n][k] = c
+            else:
+                for written in (1, 0):                                           # set 1 first: it is written by the first pass of a step
+                    names, pools, positions = pools_and_positions(written)
+                    g_spec = reads[1 - written][0]                               # a gradient next to the set that is read
+
+                    def measure(k, tup, written=written, g_spec=g_spec):
+                        if cache.get("k") != (written, k):
+                            cache.update(k=(written, k), g=gradient_window(g_spec, k))
+                        chunks = {written: tup, 1 - written: [plan[s["name"]][k] for s in upd[1 - written]]}
+                        (th, m, v), (th1, m1, v1) = ([f32(c, s) for c, s in zip(chunks[w], upd[w])] for w in (0, 1))
+                        src = (th, m, v) if written == 1 else (th1, m1, v1)
+                        src[0].normal_(std=0.02), src[1].zero_(), src[2].fill_(1e-4)
+                        ctx = _B.gxpo_init(cfg, [dict(theta=th, m=m, v=v, theta_probe=th1, m_alt=m1, v_alt=v1)])
+                        st = _B.gxpo_get_state(ctx)
+                        st.s_star, st.current_set = 0, 1 - written
+
+                        def rewind():                                            # every timed step reads the same set again
+                            _B.gxpo_set_state(ctx, st)
+
+                        ms = timed(ctx, cache["g"], rewind)
+                        _B.gxpo_destroy(ctx)
+                        return (24.0 + g_size) * E / ms / 1e6
+
+                    tuples, seen = choose_tuples(pools, positions, 3, candidates, measure, seed=written)
+                    stats.append((", ".join(names), seen))
+                    for k, tup in enumerate(tuples):
+                        if tup is not None:
+                            for n, c in zip(names, tup):
+                                plan[n][k] = c
         finally:
             cache.clear()
             torch.cuda.synchronize(self.device)
             self._unmap_all()
-        for k, tup in enumerate(tuples):
-            if tup is not None:
-                for n, c in zip(names, tup):
-                    plan[n][k] = c
-        rated = [r for r in seen if r]
+        rated = [(what, [r for r in seen if r]) for what, seen in stats]
+        rated = [(what, r) for what, r in rated if r]
         if rated:
-            self.tuned = {"positions": len(rated), "candidates": candidates,
-                          "mean_gbps": round(sum(sum(r) for r in rated) / sum(len(r) for r in rated)),
-                          "chosen_gbps": round(sum(max(r) for r in rated) / len(rated))}
+            allr = [r for _, rs in rated for r in rs]
+            self.tuned = {"positions": len(rated[0][1]), "candidates": candidates,
+                          "mean_gbps": round(sum(sum(r) for r in allr) / sum(len(r) for r in allr)),
+                          "chosen_gbps": round(sum(max(r) for r in allr) / len(allr))}
             if verbose:
-                print(f"[hbm_arena] theta, m, v chosen by measurement at {len(rated)} chunk positions: candidates average "
-                      f"{self.tuned['mean_gbps']} GB/s on the fallback step, chosen ones {self.tuned['chosen_gbps']} GB/s", file=sys.stderr, flush=True)
+                for what, rs in rated:
+                    print(f"[hbm_arena] {what} chosen by measurement at {len(rs)} chunk positions: candidates average "
+                          f"{round(sum(sum(r) for r in rs) / sum(len(r) for r in rs))} GB/s on the fallback step, chosen ones "
+                          f"{round(sum(max(r) for r in rs) / len(rs))} GB/s", file=sys.stderr, flush=True)
 
     def close(self):
         if self._closed:

@@ -57,9 +57,16 @@ def last_placement() -> dict:
 
 def alloc_engine_state(numel: int, device, *, adam: bool = True, model_copy: bool = False, grad_dtype=torch.float32,
                        n_grad_buffers: int = 3, arena: bool = False, phases_kib=None, placement: str = "auto",
-                       with_probe: bool = True, probe_is_read: bool = False, verbose: bool = False):
+                       with_probe: bool = True, probe_is_read: bool = False, alternating: bool = False, verbose: bool = False):
     """Flat buffers for one engine context in the fast layout: a dict with
-    theta, theta_probe, (m, v), (model_copy) and a list of gradient buffers.
+    theta, theta_probe, (m, v), (m_alt, v_alt), (model_copy) and a list of gradient buffers.
+
+    alternating: also allocate m_alt, v_alt, the second buffers for the moments;
+    the engine then reads one of the sets {theta, m, v} / {theta_probe, m_alt,
+    v_alt} and writes the other in every pass that advances the state.  The
+    rank-aware placement puts the two sets into different DRAM ranks, the
+    first two gradient buffers next to the first set and the third (the
+    slow step's) next to the second.
 
     placement: "ranked" = rank-aware placement through HIP's virtual-memory API
     (hbm_arena.py: chunks of a rank handed out in scattered order, the chunks of
@@ -73,6 +80,8 @@ def alloc_engine_state(numel: int, device, *, adam: bool = True, model_copy: boo
     the fused schedule the engine only ever writes it.
     `phases_kib` overrides the phases for experiments: a dict name -> KiB
     (names theta, theta_probe, m, v, model_copy, g0, g1, g2)."""
+    if alternating and not (adam and with_probe) or alternating and arena:
+        raise ValueError("alternating state needs AdamW and theta_probe (and is not offered with arena=True)")
     if arena:
         _last_placement.update(kind="arena", detail=None)
         return _alloc_arena(numel, device, adam, model_copy, grad_dtype, n_grad_buffers)
@@ -81,12 +90,12 @@ def alloc_engine_state(numel: int, device, *, adam: bool = True, model_copy: boo
         raise ValueError(placement)
     if placement != "phased":
         gs = torch.empty((), dtype=grad_dtype).element_size()
-        total = numel * (4 * (1 + int(with_probe) + 2 * int(adam)) + 2 * int(model_copy) + gs * n_grad_buffers)
+        total = numel * (4 * (1 + int(with_probe) + 2 * int(adam) + 2 * int(alternating)) + 2 * int(model_copy) + gs * n_grad_buffers)
         if placement.startswith("ranked") or total >= RANKED_MIN_BYTES:
             try:
                 return _alloc_ranked(numel, device, adam, model_copy, grad_dtype, n_grad_buffers, phases_kib, with_probe,
                                      probe_is_read, verbose, scatter=placement != "ranked-adjacent",
-                                     tune=TUNE_CANDIDATES if placement in ("auto", "ranked") else 0)
+                                     tune=TUNE_CANDIDATES if placement in ("auto", "ranked") else 0, alternating=alternating)
             except Exception as e:          # the virtual-memory API refused, or the placement probe failed
                 if placement.startswith("ranked"):
                     raise
@@ -100,6 +109,9 @@ def alloc_engine_state(numel: int, device, *, adam: bool = True, model_copy: boo
     if adam:
         out["m"] = alloc_phased(numel, torch.float32, device, int(ph["m"] * 1024), fill=0.0)
         out["v"] = alloc_phased(numel, torch.float32, device, int(ph["v"] * 1024), fill=0.0)
+    if alternating:
+        out["m_alt"] = alloc_phased(numel, torch.float32, device, int(ph["m"] * 1024), fill=0.0)
+        out["v_alt"] = alloc_phased(numel, torch.float32, device, int(ph["v"] * 1024), fill=0.0)
     if model_copy:
         out["model_copy"] = alloc_phased(numel, torch.bfloat16, device, int(ph["model_copy"] * 1024))
     grads = [alloc_phased(numel, grad_dtype, device, int(ph.get(f"g{i}", 0) * 1024)) for i in range(n_grad_buffers)]
@@ -118,17 +130,23 @@ def _default_phases_kib(grad_dtype) -> dict:
 
 
 def _alloc_ranked(numel, device, adam, model_copy, grad_dtype, n_grad_buffers, phases_kib, with_probe, probe_is_read, verbose,
-                  scatter=True, tune=0):
+                  scatter=True, tune=0, alternating=False):
     """All buffers from one RankedArena: slab by slab, theta, m, v and the gradients share a rank;
-    theta_probe and the bf16 copy (only ever written by the engine) come from another."""
+    theta_probe and the bf16 copy (only ever written by the engine) come from another.  With alternating
+    state the second set (theta_probe, m_alt, v_alt) and the last gradient buffer, which the slow step reads
+    next to it, share that other rank."""
     ph = _default_phases_kib(grad_dtype)
     ph.update(phases_kib or {})
     specs = [dict(name="theta", numel=numel, dtype=torch.float32, group="update", phase_bytes=int(ph["theta"] * 1024))]
     if adam:
         specs += [dict(name=k, numel=numel, dtype=torch.float32, group="update", phase_bytes=int(ph[k] * 1024)) for k in ("m", "v")]
-    specs += [dict(name=f"g{i}", numel=numel, dtype=grad_dtype, group="read", phase_bytes=int(ph.get(f"g{i}", 0) * 1024))
+    specs += [dict(name=f"g{i}", numel=numel, dtype=grad_dtype, group="read", phase_bytes=int(ph.get(f"g{i}", 0) * 1024),
+                   set=1 if alternating and i == n_grad_buffers - 1 and n_grad_buffers > 1 else 0)
               for i in range(n_grad_buffers)]
-    if with_probe:
+    if alternating:
+        specs += [dict(name=k, numel=numel, dtype=torch.float32, group="update", set=1, phase_bytes=int(ph[p] * 1024))
+                  for k, p in (("theta_probe", "theta_probe"), ("m_alt", "m"), ("v_alt", "v"))]
+    elif with_probe:
         specs.append(dict(name="theta_probe", numel=numel, dtype=torch.float32, group="read" if probe_is_read else "write",
                           phase_bytes=int(ph["theta_probe"] * 1024)))
     if model_copy:
@@ -154,11 +172,12 @@ def _alloc_ranked(numel, device, adam, model_copy, grad_dtype, n_grad_buffers, p
         print(f"[layout] {n_chunks} chunks of {cb >> 20} MiB in ranks {counts}; read streams per slab in ranks {ar.slab_rank}", file=sys.stderr)
     counts = {lab: labels.count(lab) for lab in sorted(set(labels))}
     _last_placement.update(kind="ranked", detail={"chunk_mib": cb >> 20, "chunks_per_rank": counts, "slab_rank": list(ar.slab_rank),
-                                                   "order": "scattered" if scatter else "index", "tuned": ar.tuned})
-    out = {k: bufs[k] for k in ("theta", "theta_probe", "m", "v", "model_copy") if k in bufs}
-    if adam:
-        out["m"].zero_()
-        out["v"].zero_()
+                                                   "order": "scattered" if scatter else "index", "tuned": ar.tuned,
+                                                   "alternating": bool(alternating)})
+    out = {k: bufs[k] for k in ("theta", "theta_probe", "m", "v", "m_alt", "v_alt", "model_copy") if k in bufs}
+    for k in ("m", "v", "m_alt", "v_alt"):
+        if k in out:
+            out[k].zero_()
     grads = [bufs[f"g{i}"] for i in range(n_grad_buffers)]
     return out, grads
 

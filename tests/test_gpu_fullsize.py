@@ -160,23 +160,26 @@ class SampleGroup:
             floor = (2.0 + cfg.alpha * cfg.K) * 2.0 ** -24 * np.linalg.norm(ref)
             assert num <= 1e-4 * den + floor, f"{label}: displacement error {num:.3e} of {den:.3e}"
 
-    def check_copy(self, flat, ref, label):
+    def check_copy(self, flat, ref, label, key="theta"):
         got_bits = gather_raw(flat["model_copy"].view(torch.int16), self.wins).numpy().view(np.uint16)
-        th32 = gather_raw(flat["theta"], self.wins).numpy()
+        th32 = gather_raw(flat[key], self.wins).numpy()
         np.testing.assert_array_equal(got_bits, O.bf16_round_bits(th32), err_msg=label)
         H.assert_close(O.bf16_bits_to_f64(got_bits), ref, label, rtol=H.RTOL_BF16)
 
 
 def run_sampled_active_step(spec_layout, *, seed, grad_dtype, with_copy, step_index=0, K=8, alpha=0.5, diagnostics=False,
-                            clip_norm=0.0, total=MIN_DENSE):
+                            clip_norm=0.0, total=MIN_DENSE, alternating=False):
     """One active step at full size in bench.py's launch configuration; at least `total` coordinates
     (all tensor heads and tails, block-straddling windows, long random windows) are compared with
-    the oracle one by one after every call."""
+    the oracle one by one after every call.  `alternating`: with the second buffer set (bench.py --alternating);
+    theta~, m, v are then looked for in theta_probe, m_alt, v_alt."""
+    TH2, M2, V2 = ("theta_probe", "m_alt", "v_alt") if alternating else ("theta", "m", "v")
     dev = torch.device("cuda:0")
     numels = [n for _, n in spec_layout]
     padded = synth.padded_numel(spec_layout, 4)
     gdt = torch.float32 if grad_dtype == "f32" else torch.bfloat16
-    flat, gflat = layout_mod.alloc_engine_state(padded, dev, adam=True, model_copy=with_copy, grad_dtype=gdt)
+    flat, gflat = layout_mod.alloc_engine_state(padded, dev, adam=True, model_copy=with_copy, grad_dtype=gdt, alternating=alternating)
+    assert ("m_alt" in flat) == alternating
     views = {k: synth.split_like(v, spec_layout, 4) for k, v in flat.items()}
     g0, g1, gs = (synth.split_like(g, spec_layout, 4) for g in gflat)
     quad = synth.ChunkedQuadratic(padded, seed, 0.05, device=dev)
@@ -193,7 +196,7 @@ def run_sampled_active_step(spec_layout, *, seed, grad_dtype, with_copy, step_in
     quad.grad(flat["theta"], 100, gflat[0]); B.gxpo_fast_steps(ctx, 0, g0)
     quad.grad(flat["theta_probe"], 100, gflat[1]); B.gxpo_fast_steps(ctx, 1, g1)
     B.gxpo_extrapolate(ctx, g0, g1)
-    quad.grad(flat["theta"], 100, gflat[2]); B.gxpo_slow_step(ctx, gs)
+    quad.grad(flat[TH2], 100, gflat[2]); B.gxpo_slow_step(ctx, gs)
     B.gxpo_gate(ctx)
 
     st = B.gxpo_get_state(ctx)
@@ -226,14 +229,15 @@ def run_sampled_active_step(spec_layout, *, seed, grad_dtype, with_copy, step_in
         grp.g1 = gather(gflat[1], grp.wins) * c1
         grp.orc.fast_step_2([grp.g1])
         ref_t = grp.orc.extrapolate([grp.g0], [grp.g1])[0]
-        grp.check(flat, "theta", ref_t, "theta~", amplified=True, clip_norm=clip_norm)
-        grp.check(flat, "m", grp.orc.m[0], "m after step 2")
-        grp.check(flat, "v", grp.orc.v[0], "v after step 2")
+        grp.check(flat, TH2, ref_t, "theta~", amplified=True, clip_norm=clip_norm)
+        grp.check(flat, M2, grp.orc.m[0], "m after step 2")
+        grp.check(flat, V2, grp.orc.v[0], "v after step 2")
         if with_copy:
-            grp.check_copy(flat, ref_t, "bf16 copy at theta~")
+            grp.check_copy(flat, ref_t, "bf16 copy at theta~", TH2)
+    assert B.gxpo_get_state(ctx).current_set == (1 if alternating else 0)
     in_threads(after_extrapolate, groups)
 
-    quad.grad(flat["theta"], step_index, gflat[2])
+    quad.grad(flat[TH2], step_index, gflat[2])
     B.gxpo_slow_step(ctx, gs)
     cs = clip_of(gs)
 
@@ -281,6 +285,13 @@ def test_config2_qwen_1p5b_flat_full_size():
     info, n = run_sampled_active_step([("flat", synth.QWEN25_1P5B_PARAMS)], seed=1, grad_dtype="f32", with_copy=False)
     assert n >= MIN_DENSE
     assert 1900 < info.norm < 2100           # ~ sqrt(P) * 0.05 plus the curvature term
+
+
+def test_config2_full_size_with_alternating_state():
+    """bench.py --alternating: the second buffer set in another DRAM rank, every pass out of place."""
+    need_memory(90)
+    info, n = run_sampled_active_step([("flat", synth.QWEN25_1P5B_PARAMS)], seed=11, grad_dtype="f32", with_copy=False, alternating=True)
+    assert n >= MIN_DENSE
 
 
 def test_config3_qwen_7b_flat_with_bf16_copy_full_size():
@@ -576,24 +587,28 @@ def test_rank_aware_placement_changes_no_result():
     data written through torch reads back, and every tensor spans several mapped chunks (so the library's range check
     walks adjacent mappings, and blocks straddle chunk boundaries)."""
     from paper_2605_06755_amd import hbm_arena
-    need_memory(40)
+    need_memory(60)
     dev = torch.device("cuda:0")
     numel = 300_000_004                                   # 1.2 GB per fp32 buffer: three chunks each, ragged last block
     results = {}
-    for placement in ("phased", "ranked"):
+    for placement in ("phased", "ranked", "ranked, alternating state"):
+        alternating = placement.endswith("alternating state")
         try:
             flat, gflat = layout_mod.alloc_engine_state(numel, dev, adam=True, model_copy=True, grad_dtype=torch.bfloat16,
-                                                        placement=placement)
+                                                        placement=placement.split(",")[0], alternating=alternating)
         except hbm_arena.ArenaUnavailable as e:
             pytest.skip(f"virtual-memory API not available: {e}")
-        assert layout_mod.last_placement()["kind"] == placement
-        if placement == "ranked":                         # scattered order, and theta, m, v of every chunk position chosen by measurement
+        assert layout_mod.last_placement()["kind"] == placement.split(",")[0]
+        assert ("m_alt" in flat and "v_alt" in flat) == alternating
+        if placement != "phased":                         # scattered order, and theta, m, v of every chunk position chosen by measurement
             detail = layout_mod.last_placement()["detail"]
             assert detail["order"] == "scattered" and detail["tuned"]["positions"] == 3 and detail["tuned"]["candidates"] > 1
-            assert detail["tuned"]["chosen_gbps"] >= detail["tuned"]["mean_gbps"]
+            assert detail["tuned"]["chosen_gbps"] >= detail["tuned"]["mean_gbps"] and detail["alternating"] == alternating
         for k, t in list(flat.items()) + [(f"g{i}", g) for i, g in enumerate(gflat)]:
             assert t.is_contiguous() and t.numel() == numel and t.device.type == "cuda", k
-            assert t.data_ptr() % 65536 == {"m": 32768, "v": 32768, "g1": 1024}.get(k, 0), k
+            assert t.data_ptr() % 65536 == {"m": 32768, "v": 32768, "m_alt": 32768, "v_alt": 32768, "g1": 1024}.get(k, 0), k
+        if alternating:
+            assert not bool(flat["m_alt"].any()) and not bool(flat["v_alt"].any())
         quad = synth.ChunkedQuadratic(numel, 9, 0.05, device=dev)
         quad.init_theta(flat["theta"])
         quad_first = synth.ChunkedQuadratic(numel, 9, 0.05, device=dev).chunk_problem(0).theta_0[:1 << 20]
@@ -603,17 +618,21 @@ def test_rank_aware_placement_changes_no_result():
         quad.grad(flat["theta"], 0, gflat[0]); B.gxpo_fast_steps(ctx, 0, [gflat[0]])
         quad.grad(flat["theta_probe"], 0, gflat[1]); B.gxpo_fast_steps(ctx, 1, [gflat[1]])
         B.gxpo_extrapolate(ctx, [gflat[0]], [gflat[1]])
-        quad.grad(flat["theta"], 0, gflat[2]); B.gxpo_slow_step(ctx, [gflat[2]])
+        assert B.gxpo_get_state(ctx).current_set == (1 if alternating else 0)          # theta~ is in the other set now
+        quad.grad(flat["theta_probe" if alternating else "theta"], 0, gflat[2]); B.gxpo_slow_step(ctx, [gflat[2]])
         info = B.gxpo_gate(ctx)
-        results[placement] = ({k: v.clone() if placement == "phased" else v for k, v in flat.items()}, info.norm)
+        assert B.gxpo_get_state(ctx).current_set == 0
+        keep = ("theta", "m", "v", "model_copy") + (() if alternating else ("theta_probe",))
+        results[placement] = ({k: flat[k].clone() for k in keep}, info.norm)
         B.gxpo_destroy(ctx)
-        if placement == "phased":
-            del flat, gflat, quad
-            import gc
-            gc.collect()
-            torch.cuda.empty_cache()
-    (a, na), (b, nb) = results["phased"], results["ranked"]
-    assert na == nb
-    for k in ("theta", "theta_probe", "m", "v"):
-        assert torch.equal(a[k].view(torch.int32), b[k].view(torch.int32)), f"{k} depends on the placement"
-    assert torch.equal(a["model_copy"].view(torch.int16), b["model_copy"].view(torch.int16))
+        del flat, gflat, quad, ctx
+        import gc
+        gc.collect()
+        torch.cuda.empty_cache()
+    a, na = results["phased"]
+    for placement in ("ranked", "ranked, alternating state"):
+        b, nb = results[placement]
+        assert na == nb, placement
+        for k in b:
+            w = torch.int16 if k == "model_copy" else torch.int32
+            assert torch.equal(a[k].view(w), b[k].view(w)), f"{k} depends on the placement ({placement})"

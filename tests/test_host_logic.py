@@ -420,3 +420,33 @@ def test_choose_tuples_keeps_the_best_rated_candidate_and_never_reuses_a_chunk()
     assert sorted(c for t in tuples for c in t) == [5, 6, 7, 8, 9, 10]
     with pytest.raises(A.ArenaUnavailable):
         A.choose_tuples({0: [1, 2, 3, 4, 5]}, [0, 0], 3, 4, measure)
+
+
+def test_chunk_plan_puts_the_second_buffer_set_into_another_rank():
+    """Alternating state: theta, m, v and the first two gradient buffers (set 0) per slab in one rank, theta_probe,
+    m_alt, v_alt and the last gradient buffer (set 1) together in another."""
+    from paper_2605_06755_amd import hbm_arena as A
+    cb = A.CHUNK_BYTES
+    numel = 3_200_000_000
+    f32 = lambda name, group, st, ph=0: dict(name=name, numel=numel, itemsize=4, group=group, set=st, phase_bytes=ph)
+    specs = [f32("theta", "update", 0), f32("m", "update", 0, 32768), f32("v", "update", 0, 32768), f32("g0", "read", 0), f32("g1", "read", 0),
+             f32("g2", "read", 1), f32("theta_probe", "update", 1), f32("m_alt", "update", 1, 32768), f32("v_alt", "update", 1, 32768),
+             dict(name="model_copy", numel=numel, itemsize=2, group="write", phase_bytes=0)]
+    labels = [0] * 190 + [1] * 188 + [2] * 170
+    plan, rank0 = A.plan_chunks(labels, specs, cb)
+    used = [c for v in plan.values() for c in v]
+    assert len(used) == len(set(used))
+    per = 2                                                                # chunks of an fp32 buffer per slab
+    n_slabs = len(rank0)
+    for slab in range(n_slabs):
+        cls = {}
+        for s in specs[:9]:
+            chunks = plan[s["name"]][slab * per:(slab + 1) * per]
+            labs = {labels[c] for c in chunks}
+            assert len(labs) == 1, (s["name"], slab)
+            cls.setdefault(s["set"], set()).update(labs)
+        assert len(cls[0]) == 1 and len(cls[1]) == 1 and cls[0] != cls[1], slab   # each set together, the two apart
+        assert cls[0] == {rank0[slab]}
+    # with a single rank on offer the sets share it rather than fail
+    plan, _ = A.plan_chunks([0] * 300, [dict(s, numel=1 << 28) for s in specs], cb)
+    assert sum(len(v) for v in plan.values()) == 5 * 2 + 4 * 3 + 1         # 2^28 elements: 2 chunks per fp32 buffer, 3 with a phase, 1 for bf16
