@@ -98,6 +98,20 @@ int main() {
     assert(gxpo_init(&ctx, &c, &t, 1) == GXPO_ERR_INVALID_ARG);                  // m overlaps theta
     t.m = (float *)0x30004;
     assert(gxpo_init(&ctx, &c, &t, 1) == GXPO_ERR_ALIGNMENT);
+    // second buffers for the moments (alternating state): a pair, never half of one; only with the fused AdamW schedule
+    t.m = (float *)0x30000, t.m_alt = (float *)0x50000;
+    assert(gxpo_init(&ctx, &c, &t, 1) == GXPO_ERR_INVALID_ARG && strstr(gxpo_last_error(nullptr), "m_alt"));
+    t.v_alt = (float *)0x60000;
+    c.fuse_step2 = 0;
+    assert(gxpo_init(&ctx, &c, &t, 1) == GXPO_ERR_UNSUPPORTED);
+    c.fuse_step2 = 1, c.explicit_steps = 3;
+    assert(gxpo_init(&ctx, &c, &t, 1) == GXPO_ERR_UNSUPPORTED);
+    c.explicit_steps = 0;
+    t.v_alt = (float *)0x40010;
+    assert(gxpo_init(&ctx, &c, &t, 1) == GXPO_ERR_INVALID_ARG);                  // v_alt overlaps v
+    t.v_alt = (float *)0x60000, t.theta_probe = nullptr;
+    assert(gxpo_init(&ctx, &c, &t, 1) == GXPO_ERR_INVALID_ARG);                  // no second parameter buffer
+    t.theta_probe = (float *)0x20000, t.m_alt = t.v_alt = nullptr;
     // entry points on a NULL context / NULL arguments
     assert(gxpo_fast_steps(nullptr, 0, nullptr, nullptr) == GXPO_ERR_INVALID_ARG);
     assert(gxpo_extrapolate(nullptr, nullptr, nullptr, nullptr) == GXPO_ERR_INVALID_ARG);
