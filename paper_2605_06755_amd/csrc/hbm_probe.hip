@@ -9,6 +9,7 @@
 //     hbm_probe ranks      one read stream moved across a 200 GiB allocation (DRAM rank regions)
 //     hbm_probe bf16       the fused pass with two bf16 gradient streams: 64-bit vs 128-bit accesses
 //     hbm_probe chunks     512 MiB physical chunks (virtual-memory API): which pairs and triples of chunks slow each other down
+//     hbm_probe sets       the same chunks sorted by rank: which ranks a pass should read from and write to (in place / out of place)
 //
 // The pass modelled is the AdamW-shaped step: read theta, m, v, g; write theta', m, v (28 B per
 // element with fp32 gradients), arithmetic reduced to a few multiply-adds (the real arithmetic
@@ -141,6 +142,19 @@ __global__ __launch_bounds__(64) void k_copy(const float *src, float *dst, size_
     if (e0 >= n) return;
     const unsigned bytes = span_bytes(n, e0, 256);
     st<18>(rsrc(dst + e0, bytes), threadIdx.x * 16, ld<18>(rsrc(src + e0, bytes), threadIdx.x * 16));
+}
+
+// the slow step's shape out of place: read theta, m, v, g; write theta', m', v' elsewhere
+__global__ __launch_bounds__(64) void k_slow_oop(const float *th, const float *m, const float *v, const float *g, float *th2, float *m2,
+                                                  float *v2, size_t n) {
+    const size_t e0 = (size_t)blockIdx.x * 256;
+    if (e0 >= n) return;
+    const unsigned bytes = span_bytes(n, e0, 256);
+    const int off = threadIdx.x * 16;
+    f4 T = ld<18>(rsrc(th + e0, bytes), off), M = ld<18>(rsrc(m + e0, bytes), off), V = ld<18>(rsrc(v + e0, bytes), off);
+    const f4 G = ld<18>(rsrc(g + e0, bytes), off);
+    math(T, M, V, G);
+    st<18>(rsrc(th2 + e0, bytes), off, T), st<18>(rsrc(m2 + e0, bytes), off, M), st<18>(rsrc(v2 + e0, bytes), off, V);
 }
 
 // two streams read and written in place at the same element offset
@@ -442,6 +456,118 @@ static int run_chunks() {
     return 0;
 }
 
+static int run_sets() {
+    const size_t H = 512 * MiB;
+    size_t free_b, total_b;
+    CK(hipMemGetInfo(&free_b, &total_b));
+    const int slots = (int)std::min<size_t>(560, (free_b - 4 * GiB) / H);      // all three ranks, if the device is otherwise empty
+    const size_t n = (H - 64 * 1024) / 4;
+    const unsigned nb = (unsigned)((n + 255) / 256);
+    hipMemAllocationProp prop = {};
+    prop.type = hipMemAllocationTypePinned, prop.location.type = hipMemLocationTypeDevice, prop.location.id = 0;
+    hipMemAccessDesc acc = {};
+    acc.location = prop.location, acc.flags = hipMemAccessFlagsProtReadWrite;
+    std::vector<hipMemGenericAllocationHandle_t> h(slots);
+    for (int i = 0; i < slots; ++i) CK(hipMemCreate(&h[i], H, &prop, 0));
+    void *va;
+    CK(hipMemAddressReserve(&va, slots * H, 2 * MiB, nullptr, 0));
+    for (int i = 0; i < slots; ++i) CK(hipMemMap((char *)va + i * H, H, 0, h[i], 0));
+    CK(hipMemSetAccess(va, slots * H, &acc, 1));
+    char *base = (char *)va;
+    k_fill<<<16384, 256>>>((float *)base, slots * H / 4, 7);
+    CK(hipDeviceSynchronize());
+    auto P = [&](int chunk, size_t phase = 0) { return (float *)(base + (size_t)chunk * H + phase); };
+    // ranks by timing: the gradient window in the candidate against theta, m, v in quarter windows of one reference chunk
+    const size_t nq = n / 4 - 16384;
+    const unsigned nbq = (unsigned)((nq + 255) / 256);
+    std::vector<int> rank(slots, -1), members[3];
+    int found = 0;
+    for (int ref = 0; ref >= 0 && found < 3;) {
+        std::vector<double> r(slots, 0.0), sorted;
+        for (int c = 0; c < slots; ++c)
+            if (rank[c] < 0 && c != ref)
+                r[c] = gbps([&] { k_slow<<<nbq, 64>>>(P(ref), P(ref, 128 * MiB + 32768), P(ref, 256 * MiB + 32768), P(c, 384 * MiB), nq); }, 28.0 * nq, 6),
+                sorted.push_back(r[c]);
+        rank[ref] = found;
+        if (sorted.size() > 8) {
+            // the reference's rank is the fast cluster: two-means on the rates; one cluster if the centres are within 2.5 %
+            std::sort(sorted.begin(), sorted.end());
+            double lo = sorted.front(), hi = sorted.back(), cut = 0;
+            for (int it = 0; it < 10; ++it) {
+                cut = 0.5 * (lo + hi);
+                double sl = 0, sh = 0;
+                size_t nl = 0, nh = 0;
+                for (double y : sorted) (y <= cut ? (sl += y, ++nl) : (sh += y, ++nh));
+                if (!nl || !nh) break;
+                lo = sl / nl, hi = sh / nh;
+            }
+            cut = hi - lo > 0.025 * hi ? 0.5 * (lo + hi) : 0;
+            printf("  reference chunk %d: %zu candidates, cluster centres %.0f / %.0f GB/s\n", ref, sorted.size(), lo, hi);
+            for (int c = 0; c < slots; ++c)
+                if (rank[c] < 0 && r[c] > cut) rank[c] = found;
+        }
+        ++found;
+        // next reference: the slowest chunk still unlabelled, the one least likely to be a straggler of this rank
+        ref = -1;
+        for (int c = 0; c < slots; ++c)
+            if (rank[c] < 0 && (ref < 0 || r[c] < r[ref])) ref = c;
+    }
+    for (int c = 0; c < slots; ++c)
+        if (rank[c] >= 0) members[rank[c]].push_back(c);
+    printf("%d chunks of 512 MiB; by rank: %zu, %zu, %zu\n", slots, members[0].size(), members[1].size(), members[2].size());
+    if (members[0].size() < 16 || members[1].size() < 16 || members[2].size() < 16) {
+        printf("fewer than three ranks with 16 chunks each: run this on an otherwise empty device\n");
+        return 1;
+    }
+    struct Layout { const char *name; int rd[4]; int wr[3]; };       // rank of theta, m, v, g; rank of theta', m', v' (-1: in place)
+    const Layout layouts[] = {
+        {"in place, everything in rank A                     [the engine's default]", {0, 0, 0, 0}, {-1, -1, -1}},
+        {"in place, theta A, m A, v B, gradient A", {0, 0, 1, 0}, {-1, -1, -1}},
+        {"in place, theta A, m B, v C, gradient A", {0, 1, 2, 0}, {-1, -1, -1}},
+        {"out of place, read A, write A A A", {0, 0, 0, 0}, {0, 0, 0}},
+        {"out of place, read A, write B B B                  [alternating state]", {0, 0, 0, 0}, {1, 1, 1}},
+        {"out of place, read A, write B C C", {0, 0, 0, 0}, {1, 2, 2}},
+        {"out of place, read A, write A B C", {0, 0, 0, 0}, {0, 1, 2}},
+        {"out of place, read B C C (gradient B), write A A A [what would have to follow]", {1, 2, 2, 1}, {0, 0, 0}},
+    };
+    unsigned x = 4711;
+    auto rnd = [&](int m) { x = x * 1664525u + 1013904223u; return (int)((x >> 8) % (unsigned)m); };
+    printf("slow-step shape (read theta, m, v, gradient; write three streams), 120 random choices of chunks per line, GB/s:\n");
+    for (const Layout &L : layouts) {
+        std::vector<double> r;
+        for (int t = 0; t < 120; ++t) {
+            int used[7], nu = 0, rd[4], wr[3] = {0, 0, 0};
+            auto one = [&](int k) {
+                int c;
+                bool fresh;
+                do {
+                    c = members[k][rnd((int)members[k].size())], fresh = true;
+                    for (int j = 0; j < nu; ++j) fresh = fresh && used[j] != c;
+                } while (!fresh);
+                return used[nu++] = c;
+            };
+            for (int k = 0; k < 4; ++k) rd[k] = one(L.rd[k]);
+            if (L.wr[0] < 0) {
+                r.push_back(gbps([&] { k_slow<<<nb, 64>>>(P(rd[0]), P(rd[1], 32768), P(rd[2], 32768), P(rd[3]), n); }, 28.0 * n, 3));
+            } else {
+                for (int k = 0; k < 3; ++k) wr[k] = one(L.wr[k]);
+                r.push_back(gbps([&] { k_slow_oop<<<nb, 64>>>(P(rd[0]), P(rd[1], 32768), P(rd[2], 32768), P(rd[3]), P(wr[0]), P(wr[1], 32768),
+                                                              P(wr[2], 32768), n); }, 28.0 * n, 3));
+            }
+        }
+        double mean = 0;
+        for (double y : r) mean += y;
+        char what[128];
+        snprintf(what, sizeof what, "%-82s mean %5.0f", L.name, mean / r.size());
+        percentiles(r, what);
+    }
+    CK(hipDeviceSynchronize());
+    CK(hipMemUnmap(va, slots * H));
+    for (int i = 0; i < slots; ++i) CK(hipMemRelease(h[i]));
+    CK(hipMemAddressFree(va, slots * H));
+    return 0;
+}
+
 int main(int argc, char **argv) {
     const char *what = argc > 1 ? argv[1] : "";
     if (!strcmp(what, "shape")) return run_shape();
@@ -450,6 +576,7 @@ int main(int argc, char **argv) {
     if (!strcmp(what, "ranks")) return run_ranks();
     if (!strcmp(what, "bf16")) return run_bf16();
     if (!strcmp(what, "chunks")) return run_chunks();
-    printf("usage: hbm_probe shape | policy | phase | ranks | bf16 | chunks\n");
+    if (!strcmp(what, "sets")) return run_sets();
+    printf("usage: hbm_probe shape | policy | phase | ranks | bf16 | chunks | sets\n");
     return 2;
 }
