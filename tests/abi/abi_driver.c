@@ -41,6 +41,76 @@ static float h_of(uint64_t i) { return 0.125f + 0.0625f * (float)(i % 13); }    
 static float star_of(uint64_t i) { return 0.5f * (float)((int)(i % 7) - 3); }
 static float start_of(uint64_t i) { return 0.25f * (float)((int)(i % 11) - 5); }
 
+/* AdamW on the same surrogate, two active steps and one fallback step, once updating theta, m, v in place and once with
+ * the second buffer set (theta_probe, m_alt, v_alt) the passes alternate with: the parameters and both moments must
+ * come out bit for bit the same, in the set gxpo_state.current_set names.  Returns 0, or an exit status. */
+static int adamw_run(int alternating, float *out[3]) {
+    const uint64_t n = 4099;
+    const size_t bytes = n * sizeof(float);
+    gxpo_tensor x;
+    memset(&x, 0, sizeof x);
+    x.numel = n;
+    float **bufs[] = {&x.theta, &x.theta_probe, &x.m, &x.v, &x.m_alt, &x.v_alt};
+    for (int b = 0; b < (alternating ? 6 : 4); ++b) {
+        HIP_OK(hipMalloc((void **)bufs[b], bytes));
+        HIP_OK(hipMemset(*bufs[b], 0, bytes));
+    }
+    float *d_g[3], *h = (float *)malloc(bytes), *g = (float *)malloc(bytes);
+    for (int r = 0; r < 3; ++r) HIP_OK(hipMalloc((void **)&d_g[r], bytes));
+    for (uint64_t i = 0; i < n; ++i) h[i] = start_of(i);
+    HIP_OK(hipMemcpy(x.theta, h, bytes, hipMemcpyHostToDevice));
+    gxpo_config cfg;
+    memset(&cfg, 0, sizeof cfg);
+    cfg.struct_size = sizeof cfg, cfg.optimizer = GXPO_OPT_ADAMW, cfg.grad_dtype = GXPO_GRAD_F32, cfg.K = 5, cfg.fuse_step2 = 1;
+    cfg.window = 4, cfg.lr = 1e-2, cfg.beta1 = 0.9, cfg.beta2 = 0.999, cfg.adam_eps = 1e-8, cfg.weight_decay = 0.01;
+    cfg.alpha = 0.5, cfg.delta = 1e-3, cfg.r_max = 4.0, cfg.tau = 1e30, cfg.gate_eps = 1e-8;
+    gxpo_ctx *ctx = NULL;
+    GXPO_OK_OR_DIE(gxpo_init(&ctx, &cfg, &x, 1));
+    gxpo_state st;
+#define CURRENT(set) ((set) ? x.theta_probe : x.theta)
+#define GRAD_AT(buffer, role)                                                                      \
+    do {                                                                                           \
+        HIP_OK(hipMemcpy(h, (buffer), bytes, hipMemcpyDeviceToHost));                              \
+        for (uint64_t i = 0; i < n; ++i) g[i] = h_of(i) * (h[i] - star_of(i));                     \
+        HIP_OK(hipMemcpy(d_g[role], g, bytes, hipMemcpyHostToDevice));                             \
+    } while (0)
+    for (int step = 0; step < 3; ++step) {
+        const void *l0[1] = {d_g[0]}, *l1[1] = {d_g[1]}, *l2[1] = {d_g[2]};
+        GXPO_OK_OR_DIE(gxpo_get_state(ctx, &st));
+        const unsigned c = st.current_set;
+        if (!alternating && c != 0) return 8;
+        GRAD_AT(CURRENT(c), 0);
+        if (step == 2) {                                   /* the gate is forced shut: one fallback step */
+            st.s_star = st.t;
+            GXPO_OK_OR_DIE(gxpo_set_state(ctx, &st));
+            GXPO_OK_OR_DIE(gxpo_fallback_step(ctx, l0, NULL));
+            break;
+        }
+        GXPO_OK_OR_DIE(gxpo_fast_steps(ctx, 0, l0, NULL));
+        GRAD_AT(alternating ? CURRENT(1 - c) : x.theta_probe, 1);          /* theta^{t,1} */
+        GXPO_OK_OR_DIE(gxpo_fast_steps(ctx, 1, l1, NULL));
+        GXPO_OK_OR_DIE(gxpo_extrapolate(ctx, l0, l1, NULL));
+        GXPO_OK_OR_DIE(gxpo_get_state(ctx, &st));
+        if (st.current_set != (alternating ? 1 - c : 0)) return 8;
+        GRAD_AT(CURRENT(st.current_set), 2);                               /* theta~ */
+        GXPO_OK_OR_DIE(gxpo_slow_step(ctx, l2, NULL));
+        gxpo_gate_info info;
+        GXPO_OK_OR_DIE(gxpo_gate(ctx, &info, NULL));
+    }
+    GXPO_OK_OR_DIE(gxpo_get_state(ctx, &st));
+    if (st.current_set != (alternating ? 1u : 0u) || st.optim_steps != 7) return 8;
+    float *final[3] = {st.current_set ? x.theta_probe : x.theta, st.current_set ? x.m_alt : x.m, st.current_set ? x.v_alt : x.v};
+    for (int k = 0; k < 3; ++k) {
+        out[k] = (float *)malloc(bytes);
+        HIP_OK(hipMemcpy(out[k], final[k], bytes, hipMemcpyDeviceToHost));
+    }
+    gxpo_destroy(ctx);
+    for (int b = 0; b < (alternating ? 6 : 4); ++b) HIP_OK(hipFree(*bufs[b]));
+    for (int r = 0; r < 3; ++r) HIP_OK(hipFree(d_g[r]));
+    free(h), free(g);
+    return 0;
+}
+
 int main(void) {
     const double eta = 0.25;
     const unsigned K = 4;
@@ -147,6 +217,15 @@ int main(void) {
         free(h_theta[t]);
         free(h_g[t]);
     }
+    /* the second buffer set changes where the results are, not what they are */
+    float *in_place[3], *alternating[3];
+    int rc = adamw_run(0, in_place);
+    if (rc == 0) rc = adamw_run(1, alternating);
+    if (rc != 0) { fprintf(stderr, "AdamW run failed (%d)\n", rc); return rc; }
+    for (int k = 0; k < 3; ++k)
+        if (memcmp(in_place[k], alternating[k], 4099 * sizeof(float)) != 0) { fprintf(stderr, "alternating state: buffer %d differs from the in-place run\n", k); return 9; }
+    printf("alternating state: theta, m, v bit-identical to the in-place run after 2 active steps and 1 fallback step\n");
+    for (int k = 0; k < 3; ++k) free(in_place[k]), free(alternating[k]);
     puts("abi driver ok");
     return 0;
 }
