@@ -306,6 +306,13 @@ typedef struct gxpo_tensor_options {
 } gxpo_tensor_options;
 int gxpo_set_tensor_options(gxpo_ctx *ctx, const gxpo_tensor_options *opts);
 
+/* Where the parameters are: out_host[t] (host array of n_tensors pointers) receives the device pointer of
+ * tensor t's buffer that holds the current iterate -- theta^t between steps, theta~^t after gxpo_extrapolate,
+ * theta^{t+1} after gxpo_slow_step / gxpo_fallback_step.  That is always `theta`, except with alternating
+ * state (gxpo_tensor.m_alt), where it is `theta` or `theta_probe` according to gxpo_state.current_set.
+ * (The first probe theta^{t,1} is in the other of the two after gxpo_fast_steps(0).) */
+int gxpo_current_params(const gxpo_ctx *ctx, float **out_host);
+
 /* ---- for callers that cannot allocate ------------------------------------------------- */
 
 /* gxpo_slow_step() without a context, for callers that cannot call hipMalloc:

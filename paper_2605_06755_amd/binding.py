@@ -45,7 +45,7 @@ EXPORTED_SYMBOLS = [
     "gxpo_init", "gxpo_destroy", "gxpo_fast_steps", "gxpo_extrapolate", "gxpo_slow_step", "gxpo_gate",
     "gxpo_fallback_step", "gxpo_tensor_norms", "gxpo_get_diagnostics", "gxpo_get_state", "gxpo_set_state", "gxpo_last_error",
     "gxpo_validate_config", "gxpo_host_gate_step", "gxpo_plan_blocks", "gxpo_stream_copy", "gxpo_update_config",
-    "gxpo_set_tensor_options", "gxpo_layout_hint", "gxpo_slow_step_noalloc",
+    "gxpo_set_tensor_options", "gxpo_layout_hint", "gxpo_slow_step_noalloc", "gxpo_current_params",
 ]
 
 
@@ -112,6 +112,8 @@ _lib.gxpo_tensor_norms.restype = ctypes.c_int
 _lib.gxpo_tensor_norms.argtypes = [_ctx_p, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
 _lib.gxpo_get_diagnostics.restype = ctypes.c_int
 _lib.gxpo_get_diagnostics.argtypes = [_ctx_p, ctypes.POINTER(gxpo_diagnostics), ctypes.c_void_p]
+_lib.gxpo_current_params.argtypes = [_ctx_p, ctypes.POINTER(ctypes.c_void_p)]
+_lib.gxpo_current_params.restype = ctypes.c_int
 _lib.gxpo_get_state.restype = ctypes.c_int
 _lib.gxpo_get_state.argtypes = [_ctx_p, ctypes.POINTER(gxpo_state)]
 _lib.gxpo_set_state.restype = ctypes.c_int
@@ -292,6 +294,16 @@ def gxpo_get_diagnostics(ctx: Context, stream=None) -> gxpo_diagnostics:
     d = gxpo_diagnostics()
     ctx._check(_lib.gxpo_get_diagnostics(ctx.handle, ctypes.byref(d), _stream_ptr(stream)))
     return d
+
+
+def gxpo_current_params(ctx: Context) -> List[torch.Tensor]:
+    """The tensors (out of the ones the context was built from) that hold the current iterate."""
+    out = (ctypes.c_void_p * ctx.n_tensors)()
+    ctx._check(_lib.gxpo_current_params(ctx.handle, out))
+    found = []
+    for t, ptr in zip(ctx._keep, out):
+        found.append(next(t[k] for k in ("theta", "theta_probe") if t.get(k) is not None and t[k].data_ptr() == ptr))
+    return found
 
 
 def gxpo_get_state(ctx: Context) -> gxpo_state:

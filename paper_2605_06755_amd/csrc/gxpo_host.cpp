@@ -751,6 +751,13 @@ int gxpo_get_diagnostics(gxpo_ctx *ctx, gxpo_diagnostics *out, void *stream) {
     return GXPO_OK;
 }
 
+int gxpo_current_params(const gxpo_ctx *ctx, float **out_host) {
+    if (!ctx) return GXPO_ERR_INVALID_ARG;
+    if (!out_host) return fail(ctx, GXPO_ERR_INVALID_ARG, "gxpo_current_params: out is NULL");
+    for (uint32_t t = 0; t < ctx->n; ++t) out_host[t] = ctx->st.current_set ? ctx->tensors[t].theta_probe : ctx->tensors[t].theta;
+    return GXPO_OK;
+}
+
 int gxpo_get_state(const gxpo_ctx *ctx, gxpo_state *out) {
     if (!ctx) return GXPO_ERR_INVALID_ARG;
     if (!out) return fail(ctx, GXPO_ERR_INVALID_ARG, "gxpo_get_state: out is NULL");

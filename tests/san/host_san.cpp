@@ -119,6 +119,7 @@ int main() {
     assert(gxpo_gate(nullptr, nullptr, nullptr) == GXPO_ERR_INVALID_ARG);
     assert(gxpo_fallback_step(nullptr, nullptr, nullptr) == GXPO_ERR_INVALID_ARG);
     assert(gxpo_get_state(nullptr, nullptr) == GXPO_ERR_INVALID_ARG);
+    assert(gxpo_current_params(nullptr, nullptr) == GXPO_ERR_INVALID_ARG);
     assert(gxpo_set_state(nullptr, nullptr) == GXPO_ERR_INVALID_ARG);
     assert(gxpo_update_config(nullptr, &c) == GXPO_ERR_INVALID_ARG);
     assert(gxpo_set_tensor_options(nullptr, nullptr) == GXPO_ERR_INVALID_ARG);

@@ -1151,6 +1151,8 @@ def test_alternating_state_is_bit_identical_to_the_in_place_schedule(grad_dtype,
     def same_state(what):
         cur = B.gxpo_get_state(alt_ctx).current_set
         th, m, v = H.DeviceState.set_keys(cur)
+        assert [x.data_ptr() for x in B.gxpo_current_params(alt_ctx)] == [x.data_ptr() for x in alt_dev.views[th]]
+        assert [x.data_ptr() for x in B.gxpo_current_params(ref_ctx)] == [x.data_ptr() for x in ref_dev.views["theta"]]
         same("theta", th, what), same("m", m, what), same("v", v, what), same("model_copy", "model_copy", what)
         return cur
 
