@@ -360,7 +360,9 @@ class RankedArena:
             if verbose:
                 print(f"[hbm_arena] reference chunk {ref}: {len(same)} of {len(todo)} chunks share its rank "
                       f"(cluster centres {lo_c:.0f} / {hi_c:.0f} GB/s)", file=sys.stderr, flush=True)
-            todo = [c for c in todo if labels[c] < 0]
+            # next reference: the slowest chunk still unlabelled, the one least likely to be a straggler of this rank
+            # (a straggler as reference would make everything else look like one foreign cluster)
+            todo = sorted((c for c in todo if labels[c] < 0), key=lambda c: rate[c])
             next_label += 1
         for c in todo:                                      # more clusters than ranks can be: lump the rest together
             labels[c] = next_label
