@@ -320,12 +320,12 @@ def measure(name: str, args, want_cpu_inputs: bool = False):
     if placement["kind"] == "ranked":
         hbm_layout = "rank-aware placement (read streams of a slab in one DRAM rank" + (
             ", theta/m/v chunks chosen by measurement" if (placement["detail"] or {}).get("tuned") else "") + "), moments +32KiB mod 64KiB"
-    if "m_alt" in flat:
-        hbm_layout += "; two buffer sets, every pass reads one and writes the other (alternating state)"
     elif placement["kind"] == "same-phase":
         hbm_layout = "same-phase"
     else:
         hbm_layout = "moments +32KiB mod 64KiB"
+    if "m_alt" in flat:
+        hbm_layout += "; two buffer sets, every pass reads one and writes the other (alternating state)"
     res = {
         "workload": workload_title(name, spec), "params": P, "tensors": len(numels), "grad_dtype": spec["grad_dtype"],
         "fused_step2": fused, "hbm_layout": hbm_layout, "bytes_per_param_per_step": step_bpp,
