@@ -317,15 +317,7 @@ def measure(name: str, args, want_cpu_inputs: bool = False):
                     "bytes_per_param": bpp["fallback_step"], "gbps": round(bpp["fallback_step"] * P / fms / 1e6, 1),
                     "frac_of_peak": round(bpp["fallback_step"] * P / fms / 1e6 / HBM_PEAK_GBPS, 4)}
 
-    if placement["kind"] == "ranked":
-        hbm_layout = "rank-aware placement (read streams of a slab in one DRAM rank" + (
-            ", theta/m/v chunks chosen by measurement" if (placement["detail"] or {}).get("tuned") else "") + "), moments +32KiB mod 64KiB"
-    elif placement["kind"] == "same-phase":
-        hbm_layout = "same-phase"
-    else:
-        hbm_layout = "moments +32KiB mod 64KiB"
-    if "m_alt" in flat:
-        hbm_layout += "; two buffer sets, every pass reads one and writes the other (alternating state)"
+    hbm_layout = describe_layout(placement, "m_alt" in flat)
     res = {
         "workload": workload_title(name, spec), "params": P, "tensors": len(numels), "grad_dtype": spec["grad_dtype"],
         "fused_step2": fused, "hbm_layout": hbm_layout, "bytes_per_param_per_step": step_bpp,
@@ -357,6 +349,20 @@ def measure(name: str, args, want_cpu_inputs: bool = False):
     gc.collect()
     torch.cuda.empty_cache()
     return res, cpu_inputs
+
+
+def describe_layout(placement: dict, two_sets: bool) -> str:
+    """The `hbm_layout` entry of the result: how the buffers were placed (layout.last_placement())."""
+    if placement["kind"] == "ranked":
+        text = "rank-aware placement (read streams of a slab in one DRAM rank" + (
+            ", theta/m/v chunks chosen by measurement" if (placement["detail"] or {}).get("tuned") else "") + "), moments +32KiB mod 64KiB"
+    elif placement["kind"] == "same-phase":
+        text = "same-phase"
+    else:
+        text = "moments +32KiB mod 64KiB"
+    if two_sets:
+        text += "; two buffer sets, every pass reads one and writes the other (alternating state)"
+    return text
 
 
 def kernel_source_stamp() -> str:

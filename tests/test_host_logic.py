@@ -450,3 +450,18 @@ def test_chunk_plan_puts_the_second_buffer_set_into_another_rank():
     # with a single rank on offer the sets share it rather than fail
     plan, _ = A.plan_chunks([0] * 300, [dict(s, numel=1 << 28) for s in specs], cb)
     assert sum(len(v) for v in plan.values()) == 5 * 2 + 4 * 3 + 1         # 2^28 elements: 2 chunks per fp32 buffer, 3 with a phase, 1 for bf16
+
+
+def test_bench_describes_the_placement_it_used():
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    ranked = {"kind": "ranked", "detail": {"tuned": {"positions": 12}}}
+    assert bench.describe_layout(ranked, False).startswith("rank-aware placement") and "chosen by measurement" in bench.describe_layout(ranked, False)
+    assert "chosen by measurement" not in bench.describe_layout({"kind": "ranked", "detail": {"tuned": None}}, False)
+    assert bench.describe_layout({"kind": "phased", "detail": None}, False) == "moments +32KiB mod 64KiB"
+    assert bench.describe_layout({"kind": "same-phase", "detail": None}, False) == "same-phase"
+    both = bench.describe_layout(ranked, True)
+    assert both.startswith("rank-aware placement") and both.endswith("(alternating state)")
+    assert bench.describe_layout({"kind": "phased", "detail": None}, True).startswith("moments +32KiB")
